@@ -1,0 +1,385 @@
+"""CPU checker for Probabilistic Chunk Masking and the masked GRPO actor step.
+
+TEST INFRASTRUCTURE ONLY.  This file is a plain, slow, fp64 restatement of what
+the paper's training step computes (Algorithm 1): it exists so that tests, the
+smoke check and the benchmark's CPU-baseline leg have something independent to
+compare the GPU library against.  It shares no code, tables or helpers with the
+GPU library and must never be imported by it.
+
+Every function names the passage of the paper it follows.  Where the paper is
+silent or ambiguous the reading taken is stated in the docstring.
+
+Parity status of each function (what pins it is in tests/test_oracle_*.py):
+  advantages          pinned: closed form for binary rewards (Eq. 1)
+  phase_scores        pinned: plain conditional-mean definition (Eq. 5), planted gaps,
+                      symmetries
+  KeepProbState       pinned: hand-worked example, Eq. 8 written via rho_c, invariants
+  philox4x32_10       pinned: published known-answer vectors of the generator
+  sample_chunks       pinned: brute-force Plackett-Luce enumeration on tiny inputs
+  compact / sample    pinned: set properties (|K_i| = min(B, N_i), ascending, unique)
+  actor_step          pinned by invariants only (finite differences, all-kept = unmasked,
+                      zero gradient for uniform rewards, rho = 1 reduces to A * grad log pi);
+                      no value printed in the paper fixes the head numerics.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+ACTION_SCALE_BITS = 24          # actions enter the score as integers round(a * 2^24)
+WEIGHT_SCALE = 65536            # keep probabilities enter the sampler as round(p * 2^16)
+MASK32 = 0xFFFFFFFF
+MASK64 = 0xFFFFFFFFFFFFFFFF
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. 1 -- group-relative advantages
+# ----------------------------------------------------------------------------------------
+
+def advantages(reward, G, eps=1e-6):
+    """Group-relative advantage of Eq. 1 for binary rewards.
+
+    A_i = (r_i - mu) / (sigma + eps) with mu, sigma the mean and the population
+    (1/G) standard deviation of the group's rewards.  A group whose rewards are
+    all equal ("collapsed", Sec. 1 and App. A) has A_i = 0; it is detected on the
+    integer success count, never on a float.  Returns (adv f64[T], active u8[T]).
+    """
+    reward = np.asarray(reward).astype(np.int64)
+    T = reward.shape[0]
+    assert T % G == 0
+    adv = np.zeros(T, dtype=F64)
+    active = np.zeros(T, dtype=np.uint8)
+    for g in range(T // G):
+        r = reward[g * G:(g + 1) * G]
+        s = int(r.sum())
+        if s == 0 or s == G:
+            continue
+        mu = F64(s) / F64(G)
+        sigma = np.sqrt(mu * (F64(1.0) - mu))
+        adv[g * G:(g + 1) * G] = (r.astype(F64) - mu) / (sigma + F64(eps))
+        active[g * G:(g + 1) * G] = 1
+    return adv, active
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. 5 -- success-vs-failure action score per phase
+# ----------------------------------------------------------------------------------------
+
+def phase_scores(actions, phase, reward, n_chunks, n_groups, G, K):
+    """Batch-level phase score C_c^(t) (Eq. 5; Sec. 4.3 first paragraph; App. D.2 last paragraph).
+
+    For every group with both outcomes (Sec. 4.1: only groups with non-zero reward
+    variance) and every phase c, the chunks (i, k) of the group with phase c are
+    pooled into a success set and a failure set; the score of (group, phase) is the
+    Euclidean norm of the difference of the two sets' mean action vectors (each
+    chunk's action is its L*D values flattened).  A (group, phase) pair lacking
+    either outcome is skipped (App. D.2).  The batch score is the unweighted mean
+    over the groups that contributed; valid_c says whether any did.
+
+    Arithmetic convention shared with the GPU library so that the sampler
+    downstream sees identical keep probabilities: each action enters as the
+    integer q = rint(a * 2^24) (round half to even), sums are exact integers,
+    means are taken as double(sum)/double(count), squared differences are added
+    for j ascending without fused multiply-add, the norm is sqrt of that sum
+    times 2^-24, and the mean over groups adds g ascending and divides once.
+    Returns (C f64[K], valid u8[K]).
+    """
+    actions = np.asarray(actions, dtype=np.float32)
+    T, N, A = actions.shape
+    phase = np.asarray(phase)
+    reward = np.asarray(reward).astype(np.int64)
+    n_chunks = np.full(T, N, dtype=np.int64) if n_chunks is None else np.asarray(n_chunks, dtype=np.int64)
+    q = np.rint(actions.astype(F64) * F64(2.0 ** ACTION_SCALE_BITS)).astype(np.int64)
+    unscale = F64(2.0 ** -ACTION_SCALE_BITS)
+
+    total = np.zeros(K, dtype=F64)
+    contributors = np.zeros(K, dtype=np.int64)
+    for g in range(n_groups):
+        rows = range(g * G, (g + 1) * G)
+        s = int(reward[g * G:(g + 1) * G].sum())
+        if s == 0 or s == G:
+            continue
+        # integer sums and counts per (outcome, phase): index 1 = success, 0 = failure
+        S = np.zeros((2, K, A), dtype=np.int64)
+        n = np.zeros((2, K), dtype=np.int64)
+        for i in rows:
+            o = int(reward[i])
+            for k in range(int(n_chunks[i])):
+                c = int(phase[i, k])
+                S[o, c] += q[i, k]
+                n[o, c] += 1
+        for c in range(K):
+            n_pos, n_neg = int(n[1, c]), int(n[0, c])
+            if n_pos == 0 or n_neg == 0:
+                continue
+            acc = F64(0.0)
+            for j in range(A):
+                diff = F64(int(S[1, c, j])) / F64(n_pos) - F64(int(S[0, c, j])) / F64(n_neg)
+                acc = acc + diff * diff
+            total[c] = total[c] + np.sqrt(acc) * unscale
+            contributors[c] += 1
+    C = np.zeros(K, dtype=F64)
+    valid = np.zeros(K, dtype=np.uint8)
+    for c in range(K):
+        if contributors[c] > 0:
+            C[c] = total[c] / F64(int(contributors[c]))
+            valid[c] = 1
+    return C, valid
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. 7-9 -- score buffer, share/max normalisation, keep probabilities
+# ----------------------------------------------------------------------------------------
+
+class KeepProbState:
+    """Per-phase score buffers and keep probabilities (Eq. 7-9; Algorithm 1, buffer steps).
+
+    The buffer of a phase is held as its running sum S_c and its entry count
+    (Eq. 8 only needs the sum).  Each step appends the valid scores; on the first
+    step and then whenever T_rc steps have been appended since the last refresh,
+    the buffers are collapsed: S_c -> share rho_c = S_c / sum S -> rho~_c =
+    rho_c / max rho (Eq. 8), p_c = max(p_min, rho~_c) (Eq. 9), buffers reset.
+    Between refreshes p is held fixed (Sec. 4.4).
+
+    Readings: the trigger counts steps (Sec. 4.3 "every T_rc steps"), because with
+    skipped phases the per-phase buffer lengths differ; a skipped phase simply has
+    no entry that step; Eq. 8 sums (it does not average); the specified value of
+    rho~_c is S_c / max S (the share denominator cancels; rho_c is still formed in
+    `shares` so a test can confirm the two routes agree); when every S_c is zero
+    rho~_c = 0 for all c, i.e. p_c = p_min (uniform sampling).  Before the first
+    update p_c = 1.
+    """
+
+    def __init__(self, K):
+        self.K = K
+        self.S = np.zeros(K, dtype=F64)
+        self.cnt = np.zeros(K, dtype=np.int64)
+        self.step = 0
+        self.since = 0
+        self.p = np.ones(K, dtype=F64)
+        self.shares = np.zeros(K, dtype=F64)
+
+    def update(self, C, valid, p_min=0.1, T_rc=5):
+        C = np.asarray(C, dtype=F64)
+        for c in range(self.K):
+            if valid[c]:
+                self.S[c] = self.S[c] + C[c]
+                self.cnt[c] += 1
+        self.since += 1
+        if self.step == 0 or self.since == T_rc:
+            S_max = F64(0.0)
+            S_sum = F64(0.0)
+            for c in range(self.K):
+                S_sum = S_sum + self.S[c]
+                if self.S[c] > S_max:
+                    S_max = self.S[c]
+            for c in range(self.K):
+                rho_tilde = self.S[c] / S_max if S_max > 0 else F64(0.0)
+                self.shares[c] = self.S[c] / S_sum if S_sum > 0 else F64(0.0)
+                self.p[c] = rho_tilde if rho_tilde > p_min else F64(p_min)
+            self.S[:] = 0
+            self.cnt[:] = 0
+            self.since = 0
+        self.step += 1
+        return self.p.copy()
+
+
+# ----------------------------------------------------------------------------------------
+# counter-based random numbers: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11)
+# ----------------------------------------------------------------------------------------
+
+_PHILOX_M0 = 0xD2511F53
+_PHILOX_M1 = 0xCD9E8D57
+_PHILOX_W0 = 0x9E3779B9
+_PHILOX_W1 = 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """Philox-4x32 with 10 rounds as published; counter = 4 words, key = 2 words (32-bit each)."""
+    c0, c1, c2, c3 = (int(x) & MASK32 for x in counter)
+    k0, k1 = (int(x) & MASK32 for x in key)
+    for _ in range(10):
+        p0 = _PHILOX_M0 * c0
+        p1 = _PHILOX_M1 * c2
+        hi0, lo0 = p0 >> 32, p0 & MASK32
+        hi1, lo1 = p1 >> 32, p1 & MASK32
+        c0, c1, c2, c3 = (hi1 ^ c1 ^ k0) & MASK32, lo1, (hi0 ^ c3 ^ k1) & MASK32, lo0
+        k0 = (k0 + _PHILOX_W0) & MASK32
+        k1 = (k1 + _PHILOX_W1) & MASK32
+    return c0, c1, c2, c3
+
+
+def rng64(seed, step, traj, rnd):
+    """64 random bits for sampling round `rnd` of trajectory `traj` at training step `step`.
+
+    Stateless and keyed by global ids, so the draw does not depend on how the work
+    is laid out.  key = (seed low, seed high); counter = (traj, rnd, step low,
+    step high); result = word0 | word1 << 32.
+    """
+    seed = int(seed) & MASK64
+    step = int(step) & MASK64
+    out = philox4x32_10((traj, rnd, step & MASK32, step >> 32), (seed & MASK32, seed >> 32))
+    return out[0] | (out[1] << 32)
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. 10 -- fixed-budget weighted sampling without replacement, then compaction
+# ----------------------------------------------------------------------------------------
+
+def quantise_keep_probs(p):
+    """Integer sampling weights q_c = floor(p_c * 2^16 + 0.5), clamped to [1, 2^16]."""
+    p = np.asarray(p, dtype=F64)
+    q = np.ones(p.shape[0], dtype=np.int64)
+    for c in range(p.shape[0]):
+        x = p[c] * F64(WEIGHT_SCALE) + F64(0.5)
+        if x >= WEIGHT_SCALE:
+            q[c] = WEIGHT_SCALE
+        elif x >= 1.0:
+            q[c] = int(np.floor(x))
+        else:                      # includes NaN
+            q[c] = 1
+    return q
+
+
+def sample_trajectory(weights, m, seed, step, traj):
+    """Successive (Plackett-Luce) sampling of m items without replacement (Eq. 10).
+
+    `weights` are positive integers.  Round r draws x = rng64(seed, step, traj, r),
+    maps it to t = floor(x * W_rem / 2^64) in [0, W_rem) and picks the first
+    remaining index (ascending) whose inclusive running weight exceeds t, i.e.
+    index k is picked with probability w_k / W_rem up to the 2^-64 granularity of
+    x.  Returns the picks in draw order.
+    """
+    w = [int(x) for x in weights]
+    W_rem = sum(w)
+    picks = []
+    for r in range(m):
+        x = rng64(seed, step, traj, r)
+        t = (x * W_rem) >> 64
+        run = 0
+        chosen = -1
+        for k, wk in enumerate(w):
+            run += wk
+            if wk > 0 and run > t:
+                chosen = k
+                break
+        assert chosen >= 0
+        picks.append(chosen)
+        W_rem -= w[chosen]
+        w[chosen] = 0
+    return picks
+
+
+def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step):
+    """Kept set per trajectory and its compaction (Eq. 10; Algorithm 1 inner loop; Sec. 4.5).
+
+    Every chunk inherits its phase's keep probability as weight (Sec. 4.4); each
+    active trajectory keeps min(B, N_i) chunks; trajectories of collapsed groups
+    (active = 0) keep none, since their advantage, hence every term of Eq. 11, is
+    zero.  Physical shrinking is expressed as the ascending list of global chunk
+    ids i*N + k of the kept chunks, trajectories in order, plus the exclusive scan
+    of per-trajectory kept counts.
+    Returns (kept_idx i32[n_kept], offsets i32[T+1], n_kept).
+    """
+    phase = np.asarray(phase)
+    T, N = phase.shape
+    q = quantise_keep_probs(keep_probs)
+    n_chunks = np.full(T, N, dtype=np.int64) if n_chunks is None else np.asarray(n_chunks, dtype=np.int64)
+    kept = []
+    offsets = np.zeros(T + 1, dtype=np.int32)
+    for i in range(T):
+        Ni = int(n_chunks[i])
+        if (active is not None and not active[i]) or Ni == 0:
+            offsets[i + 1] = offsets[i]
+            continue
+        m = min(B, Ni)
+        w = [int(q[int(phase[i, k])]) for k in range(Ni)]
+        picks = sorted(sample_trajectory(w, m, seed, step, i))
+        kept.extend(i * N + k for k in picks)
+        offsets[i + 1] = offsets[i] + m
+    return np.asarray(kept, dtype=np.int32), offsets, int(offsets[T])
+
+
+# ----------------------------------------------------------------------------------------
+# Eq. 2 / Eq. 11 -- (masked) GRPO actor step through the action head
+# ----------------------------------------------------------------------------------------
+
+def _silu_parts(u):
+    s = 1.0 / (1.0 + np.exp(-u))
+    return s, u * s
+
+
+def head_forward(X, Wg, Wu, Wd, Wo):
+    """Action head: gated MLP then bin logits.  u = X Wg, v = X Wu, a = silu(u) * v, y = a Wd, z = y Wo."""
+    u = X @ Wg
+    v = X @ Wu
+    s, su = _silu_parts(u)
+    a = su * v
+    y = a @ Wd
+    z = y @ Wo
+    return u, v, s, su, a, y, z
+
+
+def log_softmax_rows(z):
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    denom = e.sum(axis=1, keepdims=True)
+    return (z - zmax) - np.log(denom), e / denom
+
+
+def actor_step(hidden, tokens, logp_old, adv, kept_idx, N, A, Wg, Wu, Wd, Wo,
+               eps_low=0.2, eps_high=0.2, loss_scale=1.0, want_grads=True):
+    """Masked GRPO actor step over the kept chunks (Eq. 11; Eq. 2 when every chunk is kept).
+
+    Rows: the A action tokens of each kept chunk, in kept order.  For a row with
+    hidden state x, target bin b, old log-probability l0 and trajectory advantage A_i:
+    l = log softmax(z)[b]; rho = exp(l - l0); term = min(rho A_i, clip(rho, 1 - eps_low,
+    1 + eps_high) A_i) (the PPO clipping that Eq. 2 leaves out for clarity; App. D gives
+    its thresholds); loss = -loss_scale * sum of terms, so that loss_scale = 1/T gives
+    the mean over trajectories of the sum over kept chunks of Eq. 11, the chunk's log
+    probability being the sum of its tokens'.  With rho = 1 the gradient is that of
+    -loss_scale * sum A_i log pi.  A ratio exactly on a clip boundary counts as unclipped.
+
+    hidden [T*N*A, d], tokens [T*N*A], logp_old [T*N*A], adv [T], kept_idx: global chunk ids.
+    Returns a dict with loss, logp (per kept row), ratio, dz, and (if want_grads)
+    dWg, dWu, dWd, dWo, dX plus stats = [clipped fraction, mean ratio, mean(l0 - l), rows].
+    """
+    kept_idx = np.asarray(kept_idx, dtype=np.int64)
+    rows = (kept_idx[:, None] * A + np.arange(A)[None, :]).reshape(-1)
+    X = np.asarray(hidden)[rows].astype(F64)
+    tok = np.asarray(tokens)[rows].astype(np.int64)
+    l0 = np.asarray(logp_old)[rows].astype(F64)
+    adv_row = np.repeat(np.asarray(adv, dtype=F64)[kept_idx // N], A)
+    Wg, Wu, Wd, Wo = (np.asarray(w).astype(F64) for w in (Wg, Wu, Wd, Wo))
+    M = X.shape[0]
+
+    u, v, s, su, a, y, z = head_forward(X, Wg, Wu, Wd, Wo)
+    logsm, sm = log_softmax_rows(z)
+    lp = logsm[np.arange(M), tok]
+    rho = np.exp(lp - l0)
+    clipped = np.clip(rho, 1.0 - eps_low, 1.0 + eps_high)
+    term = np.minimum(rho * adv_row, clipped * adv_row)
+    loss = -F64(loss_scale) * term.sum()
+    flows = ((adv_row >= 0) & (rho <= 1.0 + eps_high)) | ((adv_row < 0) & (rho >= 1.0 - eps_low))
+    out = {"loss": loss, "logp": lp, "ratio": rho, "rows": rows}
+    if M:
+        out["stats"] = np.array([1.0 - flows.mean(), rho.mean(), (l0 - lp).mean(), float(M)])
+    else:
+        out["stats"] = np.array([0.0, 0.0, 0.0, 0.0])
+    if not want_grads:
+        return out
+    gcoef = np.where(flows, rho * adv_row, 0.0)
+    onehot = np.zeros_like(z)
+    onehot[np.arange(M), tok] = 1.0
+    dz = (-F64(loss_scale) * gcoef)[:, None] * (onehot - sm)
+    dWo = y.T @ dz
+    dy = dz @ Wo.T
+    dWd = a.T @ dy
+    da = dy @ Wd.T
+    dv = da * su
+    du = da * v * (s * (1.0 + u * (1.0 - s)))
+    dWg = X.T @ du
+    dWu = X.T @ dv
+    dX = du @ Wg.T + dv @ Wu.T
+    out.update(dz=dz, dWg=dWg, dWu=dWu, dWd=dWd, dWo=dWo, dX=dX)
+    return out

@@ -1,0 +1,179 @@
+"""Pins for the CPU checker's actor step (Eq. 2 and Eq. 11 of the paper, with PPO clipping).
+
+No number printed in the paper fixes the head's arithmetic, so the pins are the
+invariants the objective must satisfy: finite differences of the scalar loss,
+the all-kept mask reproducing the unmasked objective, zero gradient for uniform
+rewards, the rho = 1 case reducing to A * grad log pi, and textbook definitions
+of softmax and matrix products evaluated independently.
+"""
+import numpy as np
+import pytest
+from scipy.special import logsumexp
+
+from oracle import pcm_oracle as O
+
+
+def _problem(seed=0, T=4, G=4, N=5, A=3, d=6, ff=8, V=7, wstd=0.4):
+    r = np.random.default_rng(seed)
+    rows = T * N * A
+    hidden = r.standard_normal((rows, d))
+    tokens = r.integers(0, V, size=rows)
+    W = {"Wg": r.standard_normal((d, ff)) * wstd, "Wu": r.standard_normal((d, ff)) * wstd,
+         "Wd": r.standard_normal((ff, d)) * wstd, "Wo": r.standard_normal((d, V)) * wstd}
+    reward = np.array([1, 0, 0, 1] * (T // 4), dtype=np.uint8)
+    adv, _ = O.advantages(reward, G)
+    return dict(hidden=hidden, tokens=tokens, adv=adv, N=N, A=A, T=T, **W)
+
+
+def _call(p, kept, logp_old, **kw):
+    return O.actor_step(p["hidden"], p["tokens"], logp_old, p["adv"], kept, p["N"], p["A"],
+                        p["Wg"], p["Wu"], p["Wd"], p["Wo"], **kw)
+
+
+def _logp_all(p, W=None):
+    W = W or p
+    *_, z = O.head_forward(p["hidden"].astype(np.float64), W["Wg"], W["Wu"], W["Wd"], W["Wo"])
+    return (z - logsumexp(z, axis=1, keepdims=True))[np.arange(z.shape[0]), p["tokens"]]
+
+
+def test_logsoftmax_and_matmul_against_independent_definitions():
+    r = np.random.default_rng(1)
+    z = r.standard_normal((9, 11)) * 30
+    ls, sm = O.log_softmax_rows(z)
+    assert np.allclose(ls, z - logsumexp(z, axis=1, keepdims=True), rtol=1e-13, atol=1e-13)
+    assert np.allclose(sm.sum(1), 1.0, rtol=1e-14)
+    # head forward against explicit triple loops
+    X, Wg, Wu = r.standard_normal((3, 4)), r.standard_normal((4, 5)), r.standard_normal((4, 5))
+    Wd, Wo = r.standard_normal((5, 4)), r.standard_normal((4, 6))
+    u, v, s, su, a, y, z = O.head_forward(X, Wg, Wu, Wd, Wo)
+    for m in range(3):
+        a_ref = np.zeros(5)
+        for j in range(5):
+            uu = sum(X[m, i] * Wg[i, j] for i in range(4))
+            vv = sum(X[m, i] * Wu[i, j] for i in range(4))
+            a_ref[j] = uu / (1 + np.exp(-uu)) * vv
+        y_ref = [sum(a_ref[j] * Wd[j, i] for j in range(5)) for i in range(4)]
+        z_ref = [sum(y_ref[i] * Wo[i, b] for i in range(4)) for b in range(6)]
+        assert np.allclose(z[m], z_ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("perturb", [0.0, 0.15])
+def test_gradients_match_finite_differences(perturb):
+    # central differences of the scalar loss in fp64; with perturb = 0 the ratio is 1 everywhere,
+    # with perturb > 0 some rows sit on the flat (clipped) side and must contribute nothing
+    p = _problem(seed=2)
+    r = np.random.default_rng(5)
+    old = {k: p[k] + perturb * r.standard_normal(p[k].shape) for k in ("Wg", "Wu", "Wd", "Wo")}
+    logp_old = _logp_all(p, old)
+    kept = np.array([0, 3, 4, 7, 11, 12, 18, 19])
+    kw = dict(eps_low=0.2, eps_high=0.3, loss_scale=0.25)
+    ref = _call(p, kept, logp_old, **kw)
+    if perturb > 0:
+        flows_frac = 1 - ref["stats"][0]
+        assert 0.05 < flows_frac < 0.95                   # both branches of the clip are exercised
+    h = 1e-6
+    for name in ("Wg", "Wu", "Wd", "Wo", "hidden"):
+        W = p[name]
+        g = ref["d" + name] if name != "hidden" else None
+        for _ in range(6):
+            if name == "hidden":
+                kr = int(r.integers(0, len(ref["rows"])))
+                idx = (int(ref["rows"][kr]), int(r.integers(0, W.shape[1])))
+                analytic = ref["dX"][kr, idx[1]]
+            else:
+                idx = tuple(int(r.integers(0, s)) for s in W.shape)
+                analytic = g[idx]
+            keep = W[idx]
+            W[idx] = keep + h
+            lp = _call(p, kept, logp_old, want_grads=False, **kw)["loss"]
+            W[idx] = keep - h
+            lm = _call(p, kept, logp_old, want_grads=False, **kw)["loss"]
+            W[idx] = keep
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - analytic) <= 1e-6 * max(1.0, abs(analytic)) + 1e-8, (name, idx, fd, analytic)
+
+
+def test_all_kept_equals_unmasked_objective():
+    # Eq. 11 with K_i = all chunks is Eq. 2: loss = -(1/T) sum_i A_i sum_k log pi(chunk), at rho = 1
+    p = _problem(seed=3)
+    lp_all = _logp_all(p)
+    kept = np.arange(p["T"] * p["N"])
+    out = _call(p, kept, lp_all, loss_scale=1.0 / p["T"])
+    chunk_logp = lp_all.reshape(p["T"], p["N"], p["A"]).sum(-1)
+    # value of the surrogate at rho = 1 is -(1/T) sum A_i * N_i * A  (each token term equals A_i)
+    assert np.isclose(out["loss"], -(p["adv"] * p["N"] * p["A"]).sum() / p["T"], rtol=1e-12, atol=1e-12)
+    # its gradient is that of -(1/T) sum_i A_i sum_k log pi(a_ik | s_ik): check through Wo by differences
+    h = 1e-6
+    r = np.random.default_rng(0)
+    for _ in range(5):
+        idx = (int(r.integers(0, p["Wo"].shape[0])), int(r.integers(0, p["Wo"].shape[1])))
+        keep = p["Wo"][idx]
+        p["Wo"][idx] = keep + h
+        fp = -(p["adv"][:, None] * _logp_all(p).reshape(p["T"], p["N"], p["A"]).sum(-1)).sum() / p["T"]
+        p["Wo"][idx] = keep - h
+        fm = -(p["adv"][:, None] * _logp_all(p).reshape(p["T"], p["N"], p["A"]).sum(-1)).sum() / p["T"]
+        p["Wo"][idx] = keep
+        assert abs((fp - fm) / (2 * h) - out["dWo"][idx]) < 1e-7
+    assert chunk_logp.shape == (p["T"], p["N"])
+    # a mask that keeps everything, given in sampler form, is bit-identical
+    kept2, _, _ = O.sample_chunks(np.ones(2), np.zeros((p["T"], p["N"]), dtype=np.uint8), None, None,
+                                  p["N"], seed=0, step=0)
+    out2 = _call(p, kept2, lp_all, loss_scale=1.0 / p["T"])
+    for k in ("loss", "dWg", "dWu", "dWd", "dWo", "dX"):
+        assert np.array_equal(out[k], out2[k])
+
+
+def test_uniform_rewards_give_zero_gradient():
+    p = _problem(seed=4)
+    p["adv"], _ = O.advantages(np.ones(p["T"], dtype=np.uint8), 4)
+    out = _call(p, np.arange(0, 20, 3), _logp_all(p) + 0.05)
+    for k in ("dWg", "dWu", "dWd", "dWo", "dX"):
+        assert not out[k].any()
+    assert out["loss"] == 0.0
+
+
+def test_dz_rows_sum_to_zero_and_clipped_rows_vanish():
+    p = _problem(seed=5)
+    lp = _logp_all(p)
+    r = np.random.default_rng(9)
+    logp_old = lp + r.uniform(-0.6, 0.6, size=lp.shape)    # ratios spread over [0.55, 1.8]
+    kept = np.arange(p["T"] * p["N"])
+    out = _call(p, kept, logp_old, eps_low=0.2, eps_high=0.2)
+    assert np.allclose(out["dz"].sum(1), 0, atol=1e-14)
+    adv_row = np.repeat(p["adv"][kept // p["N"]], p["A"])
+    rho = out["ratio"]
+    dead = ((adv_row > 0) & (rho > 1.2)) | ((adv_row < 0) & (rho < 0.8))
+    assert dead.any() and (~dead).any()
+    assert not out["dz"][dead].any() and not out["dX"][dead].any()
+    assert np.abs(out["dz"][~dead]).sum(1).min() > 0
+    assert np.isclose(out["stats"][0], dead.mean())
+    assert np.isclose(out["stats"][1], rho.mean())
+
+
+def test_gradient_additive_over_groups_and_linear_in_advantage():
+    p = _problem(seed=6, T=8)
+    lp = _logp_all(p) + 0.01
+    kept = np.arange(p["T"] * p["N"])[::2]
+    whole = _call(p, kept, lp)
+    first = _call(p, kept[kept // p["N"] < 4], lp)
+    second = _call(p, kept[kept // p["N"] >= 4], lp)
+    for k in ("dWg", "dWu", "dWd", "dWo"):
+        assert np.allclose(whole[k], first[k] + second[k], rtol=1e-12, atol=1e-14)
+    assert np.allclose(whole["dX"], np.concatenate([first["dX"], second["dX"]]), rtol=1e-13, atol=0)
+    p2 = dict(p, adv=3.0 * p["adv"])
+    tripled = _call(p2, kept, lp)
+    assert np.allclose(tripled["dWd"], 3.0 * whole["dWd"], rtol=1e-12, atol=1e-14)
+
+
+def test_dropping_zero_advantage_trajectories_changes_nothing():
+    # compaction drops trajectories of collapsed groups; their terms are exactly zero
+    p = _problem(seed=7, T=8)
+    reward = np.array([1, 0, 0, 1, 1, 1, 1, 1], dtype=np.uint8)
+    p["adv"], active = O.advantages(reward, 4)
+    lp = _logp_all(p) - 0.02
+    kept_all = np.arange(p["T"] * p["N"])
+    kept_act = kept_all[active[kept_all // p["N"]] == 1]
+    a, b = _call(p, kept_all, lp), _call(p, kept_act, lp)
+    assert a["loss"] == b["loss"]
+    for k in ("dWg", "dWu", "dWd", "dWo"):
+        assert np.allclose(a[k], b[k], rtol=1e-13, atol=1e-16)
