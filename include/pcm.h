@@ -1,0 +1,202 @@
+/*
+ * pcm.h -- C boundary of the MI355X (gfx950) library for Probabilistic Chunk Masking (PCM)
+ * and the masked GRPO actor step it feeds.
+ *
+ * One training step of the paper's Algorithm 1 maps onto four calls, in this order:
+ *
+ *   pcm_score_phases        advantages (Eq. 1) and the batch phase score C_c^(t) (Eq. 5)
+ *   pcm_update_keep_probs   score buffers, share/max normalisation, keep probabilities (Eq. 7-9)
+ *   pcm_sample_chunks       fixed-budget weighted sampling without replacement (Eq. 10) and
+ *                           physical shrinking expressed as compacted chunk ids (Sec. 4.5)
+ *   grpo_masked_actor_step  gather of the kept chunks, action-head forward, clipped GRPO
+ *                           surrogate (Eq. 11; Eq. 2 when every chunk is kept) and backward
+ *
+ * Conventions common to every entry point
+ *   - Return value: PCM_OK or a negative pcm_status.  Nothing throws, aborts or prints.
+ *   - "device" pointers are HIP device memory owned by the caller; they must stay valid until
+ *     `stream` has executed the call.  "host" values are plain arguments.  The library never
+ *     allocates or frees device memory and never synchronises the stream or the device: all
+ *     work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Scratch memory comes from the caller: `workspace` (device, 256-byte aligned) of at least
+ *     the size returned by the matching *_workspace_bytes query (host-only, no GPU work).  Its
+ *     contents on entry are irrelevant; two calls that share a workspace must be ordered on
+ *     one stream.
+ *   - Argument checks are made on host scalars and on pointer nullness only; device data is
+ *     never read by the host.  Out-of-range device data (phase >= K, token >= V, n_chunks > N,
+ *     chunk id out of range) is clamped or ignored by the kernels as stated per call, never
+ *     dereferenced out of bounds.
+ *   - Layouts are dense row-major; T = n_groups * G trajectories, the G rollouts of group g
+ *     being rows g*G .. g*G+G-1; N chunk slots per trajectory; A = L*D action values (and
+ *     action tokens) per chunk (8 * 7 = 56 in the paper's setup, Sec. 5.1).
+ */
+#ifndef PCM_H_
+#define PCM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PCM_OK = 0,
+    PCM_EINVAL = -1,       /* null pointer, non-positive size, value out of the stated range */
+    PCM_EWORKSPACE = -2,   /* workspace missing, misaligned or smaller than the query says */
+    PCM_EHIP = -3,         /* a HIP call (kernel launch, event) reported an error */
+    PCM_EUNSUPPORTED = -4  /* shape or dtype outside what the kernels implement */
+} pcm_status;
+
+typedef enum { PCM_F32 = 0, PCM_BF16 = 1 } pcm_dtype;
+
+/* Exported symbols (the library is built with hidden default visibility). */
+#if defined(__GNUC__)
+#define PCM_API __attribute__((visibility("default")))
+#else
+#define PCM_API
+#endif
+
+/* Limits of the kernels (host-checked). */
+#define PCM_MAX_PHASES 64        /* K */
+#define PCM_MAX_CHUNK_SLOTS 4096 /* N */
+
+/* Library version string (host). */
+PCM_API const char* pcm_version(void);
+/* Short text for a status code (host). */
+PCM_API const char* pcm_status_string(int status);
+
+/* ------------------------------------------------------------------------------------------
+ * Keep-probability state (Eq. 7-9; Algorithm 1: buffer initialisation, append, refresh).
+ *
+ * A flat block in device memory, trivially copyable (it is the only state PCM carries between
+ * steps, so copying it out and back is a checkpoint).  Layout, all 8-byte words:
+ *   int64 step; int64 since_refresh; double S[K]; int64 count[K]; double p[K]
+ * ------------------------------------------------------------------------------------------ */
+PCM_API size_t pcm_state_bytes(int K);
+/* device state: step = 0, buffers empty, p_c = 1.  Enqueued on stream. */
+PCM_API int pcm_state_init(void* state, int K, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * pcm_score_phases -- Eq. 1 and Eq. 5 (with the skip rule of App. D.2, last paragraph).
+ *
+ * For every group with both outcomes and every phase c: pool the group's chunks of phase c
+ * (chunk slot k < n_chunks[i]) into successes (reward 1) and failures (reward 0); the pair's
+ * score is the Euclidean norm of the difference of the two pooled mean action vectors; a pair
+ * missing either outcome is skipped.  C_out[c] is the mean of the pair scores over the groups
+ * that were not skipped, valid_out[c] whether any group contributed (C_out[c] = 0 if none).
+ * Groups whose rewards are all equal are ignored for the score and get advantage 0, active 0.
+ *
+ * Exactness: actions enter as integers rint(a * 2^24); sums are 64-bit integers, so the result
+ * does not depend on launch geometry or summation order; the remaining fp64 operations are
+ * done in a fixed order without fused multiply-add.  Required: |a| <= 2^20, finite.
+ *
+ *   actions   device f32 [T, N, A]
+ *   phase     device u8  [T, N]; entries >= K are ignored
+ *   reward    device u8  [T]; non-zero = success
+ *   n_chunks  device i32 [T] valid chunk slots per trajectory (clamped to [0, N]); NULL = all N
+ *   adv_eps   host, epsilon of Eq. 1 (>= 0)
+ *   C_out     device f64 [K];  valid_out device u8 [K]
+ *   adv_out   device f32 [T] or NULL;  active_out device u8 [T] or NULL
+ * Limits: 1 <= K <= PCM_MAX_PHASES, 1 <= A <= 256, G >= 1, n_groups >= 1, N >= 1.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API size_t pcm_score_phases_workspace_bytes(int n_groups, int G, int N, int A, int K);
+PCM_API int pcm_score_phases(const float* actions, const uint8_t* phase, const uint8_t* reward,
+                     const int32_t* n_chunks, int n_groups, int G, int N, int A, int K,
+                     double adv_eps, double* C_out, uint8_t* valid_out, float* adv_out,
+                     uint8_t* active_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * pcm_update_keep_probs -- Eq. 7 (append), Eq. 8 (collapse), Eq. 9 (floor); Sec. 4.3-4.4.
+ *
+ * Appends the valid scores to the per-phase buffers (kept as running sums).  On the first call
+ * after pcm_state_init and then whenever T_rc calls have been appended since the last refresh:
+ * rho~_c = S_c / max_c' S_c' (0 if every S is 0), p_c = max(p_min, rho~_c), buffers reset.
+ * Otherwise p is left as it was.  keep_probs_out receives a copy of p either way.
+ *
+ *   state  device block of pcm_state_bytes(K);  C device f64 [K];  valid device u8 [K]
+ *   p_min  host, in (0, 1];  T_rc host, >= 1;  keep_probs_out device f64 [K] or NULL
+ * ------------------------------------------------------------------------------------------ */
+PCM_API int pcm_update_keep_probs(void* state, const double* C, const uint8_t* valid, int K, double p_min,
+                          int T_rc, double* keep_probs_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * pcm_sample_chunks -- Eq. 10 and the shrinking step of Algorithm 1's inner loop (Sec. 4.5).
+ *
+ * Every chunk slot k < n_chunks[i] of an active trajectory i carries the integer weight
+ * q = clamp(floor(p_phase * 2^16 + 0.5), 1, 2^16) of its phase (phase ids >= K use phase K-1).
+ * min(B, n_chunks[i]) chunks are drawn by successive weighted sampling without replacement:
+ * round r takes 64 random bits x = Philox4x32-10(counter = (i, r, step low, step high),
+ * key = (seed low, seed high)), words 0 and 1, maps them to t = floor(x * W_rem / 2^64) and
+ * picks the first remaining slot whose inclusive running weight exceeds t.  The draw depends
+ * only on (seed, step, i, r), not on launch geometry.  Inactive trajectories keep nothing.
+ *
+ *   keep_probs device f64 [K];  phase device u8 [T, N];  n_chunks device i32 [T] or NULL
+ *   active     device u8 [T] or NULL (= all active)
+ *   kept_idx     device i32 [T * min(B, N)]: global chunk ids i*N + k, ascending; entries at
+ *                and beyond *n_kept are left untouched
+ *   kept_offsets device i32 [T + 1]: exclusive scan of per-trajectory kept counts
+ *   n_kept       device i32 [1] = kept_offsets[T]
+ * Limits: 1 <= K <= PCM_MAX_PHASES, 1 <= N <= PCM_MAX_CHUNK_SLOTS, B >= 1, T >= 1,
+ *         T * N < 2^31.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API size_t pcm_sample_chunks_workspace_bytes(int T, int N, int K, int B);
+PCM_API int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
+                      const uint8_t* active, int T, int N, int K, int B, uint64_t seed,
+                      uint64_t step, int32_t* kept_idx, int32_t* kept_offsets, int32_t* n_kept,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * grpo_masked_actor_step -- Eq. 11 (Eq. 2 when kept_idx lists every chunk), with the PPO
+ * clipping the paper leaves out of Eq. 2 for clarity (thresholds as in App. D).
+ *
+ * Rows are the A action tokens of each kept chunk, in kept order: row r of the compacted batch
+ * is token r % A of chunk kept_idx[r / A], i.e. row kept_idx[r / A] * A + r % A of `hidden`.
+ * Head (weights stored [in, out], no bias): u = x Wg, v = x Wu, a = silu(u) * v, y = a Wd,
+ * z = y Wo (V logits).  Per row: l = log softmax(z)[token], rho = exp(l - logp_old),
+ * term = min(rho * A_i, clip(rho, 1 - eps_low, 1 + eps_high) * A_i) with A_i the advantage of
+ * the chunk's trajectory; loss = -loss_scale * sum of terms over the first *n_kept chunks.
+ * Gradients are those of that loss; a ratio exactly on a clip boundary counts as unclipped.
+ *
+ *   hidden    device [T*N*A, d] of dtype;  tokens device u8 [T*N*A] (values >= V use V-1)
+ *   logp_old  device f32 [T*N*A];  adv device f32 [T]
+ *   kept_idx  device i32 [>= max_kept_chunks]; ids outside [0, T*N) are treated as id 0 with
+ *             advantage 0;  n_kept device i32 [1], clamped to [0, max_kept_chunks]
+ *   Wg, Wu    device [d, ff];  Wd device [ff, d];  Wo device [d, V]  (dtype)
+ *   loss_out  device f32 [1]
+ *   logp_out  device f32 [max_kept_chunks * A] or NULL (rows beyond the kept ones: untouched)
+ *   dWg, dWu  device f32 [d, ff]; dWd device f32 [ff, d]; dWo device f32 [d, V]: overwritten.
+ *             Pass all four NULL (and dX NULL) for a forward-only call.
+ *   dX        device [max_kept_chunks * A, d] of dtype, or NULL
+ *   stats_out device f32 [4] or NULL: fraction of rows with clipped (zero) gradient, mean rho,
+ *             mean (logp_old - l), number of rows
+ * dtype PCM_F32: fp32 storage and arithmetic; any d, ff >= 1, 1 <= V <= 1024.
+ * dtype PCM_BF16: bf16 storage, MFMA with fp32 accumulation, bf16 intermediates;
+ *             requires d % 256 == 0, ff % 256 == 0, V == 256.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API size_t grpo_masked_actor_step_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V,
+                                              int dtype, int want_grads);
+PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_old,
+                           const float* adv, const int32_t* kept_idx, const int32_t* n_kept,
+                           int max_kept_chunks, int T, int N, int A, int d, int ff, int V,
+                           int dtype, const void* Wg, const void* Wu, const void* Wd,
+                           const void* Wo, float eps_low, float eps_high, float loss_scale,
+                           float* loss_out, float* logp_out, float* dWg, float* dWu, float* dWd,
+                           float* dWo, void* dX, float* stats_out, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Stage timing (measurement aid, host side).  When enabled, grpo_masked_actor_step and the
+ * selection calls record HIP events on `stream` between their kernels; pcm_profile_collect
+ * waits for the last recorded event and adds each stage's elapsed time to a running total.
+ * Disabled by default; enabling it does not change any result.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API int pcm_profile_enable(int on);                 /* returns PCM_OK; resets totals when turned on */
+PCM_API int pcm_profile_stage_count(void);
+PCM_API const char* pcm_profile_stage_name(int stage);  /* NULL if out of range */
+/* host arrays of pcm_profile_stage_count() entries: total milliseconds and launch counts */
+PCM_API int pcm_profile_collect(double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCM_H_ */

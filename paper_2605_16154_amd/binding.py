@@ -1,0 +1,241 @@
+"""ctypes binding of ``include/pcm.h``: same names, argument marshalling only.
+
+PyTorch provides device memory (tensors) and the stream; nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+PCM_F32, PCM_BF16 = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpcm.so")
+_lib = None
+
+
+class PcmError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _sig(fn, res, args):
+    fn.restype = res
+    fn.argtypes = args
+
+
+def lib() -> C.CDLL:
+    """The loaded C library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise PcmError(f"{_LIB_PATH} is missing: build it with `python -m paper_2605_16154_amd.build` "
+                       "(or __graft_entry__.build()); there is no fallback path")
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, i64, u64, f32, f64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_float, C.c_double, C.c_size_t
+    _sig(L.pcm_version, C.c_char_p, [])
+    _sig(L.pcm_status_string, C.c_char_p, [i32])
+    _sig(L.pcm_state_bytes, sz, [i32])
+    _sig(L.pcm_state_init, i32, [vp, i32, vp])
+    _sig(L.pcm_score_phases_workspace_bytes, sz, [i32] * 5)
+    _sig(L.pcm_score_phases, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f64, vp, vp, vp, vp, vp, sz, vp])
+    _sig(L.pcm_update_keep_probs, i32, [vp, vp, vp, i32, f64, i32, vp, vp])
+    _sig(L.pcm_sample_chunks_workspace_bytes, sz, [i32] * 4)
+    _sig(L.pcm_sample_chunks, i32, [vp, vp, vp, vp, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, sz, vp])
+    _sig(L.grpo_masked_actor_step_workspace_bytes, sz, [i32] * 7)
+    _sig(L.grpo_masked_actor_step, i32,
+         [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, f32,
+          vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp])
+    _sig(L.pcm_profile_enable, i32, [i32])
+    _sig(L.pcm_profile_stage_count, i32, [])
+    _sig(L.pcm_profile_stage_name, C.c_char_p, [i32])
+    _sig(L.pcm_profile_collect, i32, [C.POINTER(f64), C.POINTER(i64)])
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise PcmError(f"{what} failed: {lib().pcm_status_string(rc).decode()} ({rc})")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name: str = "tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise PcmError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise PcmError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise PcmError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+_workspaces: Dict[torch.device, torch.Tensor] = {}
+
+
+def _workspace(nbytes: int, device) -> Tuple[Optional[int], int]:
+    """One growing scratch tensor per device, shared by all calls (they are stream-ordered)."""
+    if nbytes == 0:
+        return None, 0
+    dev = torch.device(device)
+    ws = _workspaces.get(dev)
+    if ws is None or ws.numel() < nbytes:
+        _workspaces[dev] = ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    return ws.data_ptr(), ws.numel()
+
+
+def pcm_version() -> str:
+    return lib().pcm_version().decode()
+
+
+def pcm_state_bytes(K: int) -> int:
+    return lib().pcm_state_bytes(K)
+
+
+def pcm_state_init(K: int, device="cuda") -> torch.Tensor:
+    """Allocates and initialises the keep-probability state block (int64 words)."""
+    nbytes = pcm_state_bytes(K)
+    if nbytes == 0:
+        raise PcmError("pcm_state_bytes: K out of range")
+    state = torch.empty(nbytes // 8, dtype=torch.int64, device=device)
+    _check(lib().pcm_state_init(state.data_ptr(), K, _stream()), "pcm_state_init")
+    return state
+
+
+def pcm_score_phases(actions, phase, reward, n_chunks, n_groups: int, G: int, K: int, adv_eps: float = 1e-6,
+                     out=None):
+    """-> (C f64[K], valid u8[K], adv f32[T], active u8[T])."""
+    T, N, A = actions.shape
+    dev = actions.device
+    if out is None:
+        out = (torch.empty(K, dtype=torch.float64, device=dev), torch.empty(K, dtype=torch.uint8, device=dev),
+               torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.uint8, device=dev))
+    Cc, valid, adv, active = out
+    need = lib().pcm_score_phases_workspace_bytes(n_groups, G, N, A, K)
+    ws, ws_bytes = _workspace(need, dev)
+    rc = lib().pcm_score_phases(_ptr(actions, torch.float32, "actions"), _ptr(phase, torch.uint8, "phase"),
+                                _ptr(reward, torch.uint8, "reward"), _ptr(n_chunks, torch.int32, "n_chunks"),
+                                n_groups, G, N, A, K, adv_eps, _ptr(Cc, torch.float64, "C_out"),
+                                _ptr(valid, torch.uint8, "valid_out"), _ptr(adv, torch.float32, "adv_out"),
+                                _ptr(active, torch.uint8, "active_out"), ws, ws_bytes, _stream())
+    _check(rc, "pcm_score_phases")
+    return out
+
+
+def pcm_update_keep_probs(state, Cc, valid, p_min: float = 0.1, T_rc: int = 5, keep_probs_out=None):
+    K = Cc.shape[0]
+    if keep_probs_out is None:
+        keep_probs_out = torch.empty(K, dtype=torch.float64, device=Cc.device)
+    rc = lib().pcm_update_keep_probs(_ptr(state, torch.int64, "state"), _ptr(Cc, torch.float64, "C"),
+                                     _ptr(valid, torch.uint8, "valid"), K, p_min, T_rc,
+                                     _ptr(keep_probs_out, torch.float64, "keep_probs_out"), _stream())
+    _check(rc, "pcm_update_keep_probs")
+    return keep_probs_out
+
+
+def pcm_sample_chunks(keep_probs, phase, n_chunks, active, B: int, seed: int, step: int, out=None):
+    """-> (kept_idx i32[T*min(B,N)], kept_offsets i32[T+1], n_kept i32[1])."""
+    T, N = phase.shape
+    K = keep_probs.shape[0]
+    dev = phase.device
+    if out is None:
+        out = (torch.empty(T * min(B, N), dtype=torch.int32, device=dev),
+               torch.empty(T + 1, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev))
+    kept_idx, kept_offsets, n_kept = out
+    need = lib().pcm_sample_chunks_workspace_bytes(T, N, K, B)
+    ws, ws_bytes = _workspace(need, dev)
+    rc = lib().pcm_sample_chunks(_ptr(keep_probs, torch.float64, "keep_probs"), _ptr(phase, torch.uint8, "phase"),
+                                 _ptr(n_chunks, torch.int32, "n_chunks"), _ptr(active, torch.uint8, "active"),
+                                 T, N, K, B, seed & 0xFFFFFFFFFFFFFFFF, step & 0xFFFFFFFFFFFFFFFF,
+                                 _ptr(kept_idx, torch.int32, "kept_idx"), _ptr(kept_offsets, torch.int32, "kept_offsets"),
+                                 _ptr(n_kept, torch.int32, "n_kept"), ws, ws_bytes, _stream())
+    _check(rc, "pcm_sample_chunks")
+    return out
+
+
+def grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, want_grads) -> int:
+    return lib().grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, int(want_grads))
+
+
+def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: int, N: int, A: int,
+                           Wg, Wu, Wd, Wo, eps_low: float = 0.2, eps_high: float = 0.2, loss_scale: float = 1.0,
+                           want_grads: bool = True, want_dX: bool = True, max_kept_chunks: Optional[int] = None,
+                           out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
+    """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[4], and if requested dWg, dWu, dWd, dWo, dX).
+
+    `out` may carry preallocated tensors under those names (they are reused, not reallocated).
+    """
+    dev = hidden.device
+    d, ff = Wg.shape
+    V = Wo.shape[1]
+    if hidden.dtype == torch.float32:
+        dtype = PCM_F32
+    elif hidden.dtype == torch.bfloat16:
+        dtype = PCM_BF16
+    else:
+        raise PcmError(f"hidden must be float32 or bfloat16, got {hidden.dtype}")
+    for name, w, shape in (("Wg", Wg, (d, ff)), ("Wu", Wu, (d, ff)), ("Wd", Wd, (ff, d)), ("Wo", Wo, (d, V))):
+        if tuple(w.shape) != shape or w.dtype != hidden.dtype:
+            raise PcmError(f"{name} must be {shape} of {hidden.dtype}")
+    if hidden.shape != (T * N * A, d):
+        raise PcmError("hidden must be [T*N*A, d]")
+    if max_kept_chunks is None:
+        max_kept_chunks = kept_idx.shape[0]
+    if kept_idx.shape[0] < max_kept_chunks:
+        raise PcmError("kept_idx is shorter than max_kept_chunks")
+    rows = max_kept_chunks * A
+    out = {} if out is None else out
+
+    def buf(name, shape, dt):
+        t = out.get(name)
+        if t is None:
+            out[name] = t = torch.empty(shape, dtype=dt, device=dev)
+        elif tuple(t.shape) != tuple(shape):
+            raise PcmError(f"out[{name!r}] has shape {tuple(t.shape)}, expected {tuple(shape)}")
+        return t
+
+    loss = buf("loss", (1,), torch.float32)
+    logp = buf("logp", (rows,), torch.float32)
+    stats = buf("stats", (4,), torch.float32)
+    grads = [None] * 4
+    if want_grads:
+        grads = [buf("dWg", (d, ff), torch.float32), buf("dWu", (d, ff), torch.float32),
+                 buf("dWd", (ff, d), torch.float32), buf("dWo", (d, V), torch.float32)]
+    dX = buf("dX", (rows, d), hidden.dtype) if want_dX else None
+    need = grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, want_grads or want_dX)
+    if need == 0:
+        raise PcmError("grpo_masked_actor_step: unsupported shape or dtype for this path")
+    ws, ws_bytes = _workspace(need, dev)
+    rc = lib().grpo_masked_actor_step(
+        _ptr(hidden, None, "hidden"), _ptr(tokens, torch.uint8, "tokens"), _ptr(logp_old, torch.float32, "logp_old"),
+        _ptr(adv, torch.float32, "adv"), _ptr(kept_idx, torch.int32, "kept_idx"), _ptr(n_kept, torch.int32, "n_kept"),
+        max_kept_chunks, T, N, A, d, ff, V, dtype, _ptr(Wg, None, "Wg"), _ptr(Wu, None, "Wu"), _ptr(Wd, None, "Wd"),
+        _ptr(Wo, None, "Wo"), eps_low, eps_high, loss_scale, _ptr(loss, torch.float32, "loss"),
+        _ptr(logp, torch.float32, "logp"), *[_ptr(g, torch.float32, "dW") for g in grads], _ptr(dX, None, "dX"),
+        _ptr(stats, torch.float32, "stats"), ws, ws_bytes, _stream())
+    _check(rc, "grpo_masked_actor_step")
+    return out
+
+
+def pcm_profile_enable(on: bool) -> None:
+    _check(lib().pcm_profile_enable(int(on)), "pcm_profile_enable")
+
+
+def pcm_profile_collect() -> Dict[str, Tuple[float, int]]:
+    """-> {stage name: (total milliseconds, launches)} accumulated since profiling was enabled."""
+    n = lib().pcm_profile_stage_count()
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib().pcm_profile_collect(ms, cnt), "pcm_profile_collect")
+    return {lib().pcm_profile_stage_name(i).decode(): (ms[i], cnt[i]) for i in range(n)}

@@ -1,0 +1,53 @@
+// grpo_masked_actor_step: argument checks and dispatch to the fp32 or bf16 path.
+#include "actor.h"
+
+using namespace pcm;
+
+namespace {
+
+bool shape_supported(const ActorShape& sh, int dtype) {
+    if (dtype == PCM_F32) return sh.V <= 1024;
+    if (dtype == PCM_BF16) return sh.d % 256 == 0 && sh.ff % 256 == 0 && sh.V == 256;
+    return false;
+}
+
+bool shape_valid(const ActorShape& sh) {
+    return sh.max_chunks >= 1 && sh.A >= 1 && sh.d >= 1 && sh.ff >= 1 && sh.V >= 1 &&
+           sh.rows_max() < ((int64_t)1 << 31) - 256;
+}
+
+}  // namespace
+
+extern "C" size_t grpo_masked_actor_step_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V,
+                                                         int dtype, int want_grads) {
+    ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
+    if (!shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
+    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, want_grads != 0)
+                            : actor_bf16_workspace_bytes(sh, want_grads != 0);
+}
+
+extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_old,
+                                      const float* adv, const int32_t* kept_idx, const int32_t* n_kept,
+                                      int max_kept_chunks, int T, int N, int A, int d, int ff, int V, int dtype,
+                                      const void* Wg, const void* Wu, const void* Wd, const void* Wo,
+                                      float eps_low, float eps_high, float loss_scale, float* loss_out,
+                                      float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
+                                      float* stats_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!hidden || !tokens || !logp_old || !adv || !kept_idx || !n_kept || !Wg || !Wu || !Wd || !Wo || !loss_out)
+        return PCM_EINVAL;
+    const int n_grad = (dWg != nullptr) + (dWu != nullptr) + (dWd != nullptr) + (dWo != nullptr);
+    if (n_grad != 0 && n_grad != 4) return PCM_EINVAL;
+    ActorShape sh{max_kept_chunks, T, N, A, d, ff, V};
+    if (!shape_valid(sh) || T < 1 || N < 1 || (int64_t)T * N >= (int64_t)1 << 31) return PCM_EINVAL;
+    if (!(eps_low >= 0.f) || !(eps_high >= 0.f) || loss_scale != loss_scale) return PCM_EINVAL;
+    if (dtype != PCM_F32 && dtype != PCM_BF16) return PCM_EINVAL;
+    if (!shape_supported(sh, dtype)) return PCM_EUNSUPPORTED;
+    const bool bwd = n_grad == 4 || dX != nullptr;
+    const size_t need = dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd);
+    if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
+
+    ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, eps_low, eps_high, loss_scale,
+               loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return dtype == PCM_F32 ? actor_f32_run(sh, io, workspace, s) : actor_bf16_run(sh, io, workspace, s);
+}

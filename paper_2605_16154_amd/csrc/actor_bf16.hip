@@ -1,0 +1,239 @@
+// bf16 path of the masked GRPO actor step (Eq. 11): matrix-core GEMMs with fused epilogues.
+//
+// Forward:  X -> [gate|up] GEMM with silu(u)*v fused -> down GEMM -> logit GEMM with the
+//           log-softmax / ratio / clipped surrogate / dz fused.
+// Backward: dy = dz Wo^T; da = dy Wd^T with the gated-activation derivative fused (du, dv
+//           overwrite u, v); weight gradients as split reductions over the row dimension with
+//           fp32 atomics; dX = du Wg^T + dv Wu^T as one GEMM over two reduction segments.
+//
+// Every GEMM runs in the "both operands reduction-contiguous" form of gemm_bf16.h; operands that
+// are stored the other way round (the [in, out] weights in the forward pass, the activations in
+// the weight-gradient products) are copied transposed by a streaming kernel first.
+//
+// Rows are padded to a multiple of 256; padding rows are zero with zero advantage, so they
+// contribute nothing to any output.
+#include "gemm_bf16.h"
+
+namespace pcm {
+namespace {
+
+constexpr int kPackNone = 0, kPackGate = 1, kPackUp = 2;
+
+__device__ inline int packed_row(int c, int mode) {
+    if (mode == kPackNone) return c;
+    return (c / 64) * 128 + (c % 64) + (mode == kPackUp ? 64 : 0);
+}
+
+// dst[map(c), r] = src[r, c] for a [R, C] bf16 matrix (R, C multiples of 64); 64 x 64 tiles.
+__global__ __launch_bounds__(256) void transpose_bf16(const uint16_t* __restrict__ src, int64_t ld_src,
+                                                      uint16_t* __restrict__ dst, int64_t ld_dst, int mode) {
+    __shared__ uint16_t tile[64][66];
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    const int t = threadIdx.x, tr = t >> 4, tv = t & 15;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int row = tr + 16 * q;
+        const uint2 v = *reinterpret_cast<const uint2*>(src + (int64_t)(r0 + row) * ld_src + c0 + tv * 4);
+        tile[row][tv * 4 + 0] = (uint16_t)(v.x & 0xFFFF);
+        tile[row][tv * 4 + 1] = (uint16_t)(v.x >> 16);
+        tile[row][tv * 4 + 2] = (uint16_t)(v.y & 0xFFFF);
+        tile[row][tv * 4 + 3] = (uint16_t)(v.y >> 16);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int c = tr + 16 * q;
+        uint2 v;
+        v.x = (uint32_t)tile[tv * 4 + 0][c] | ((uint32_t)tile[tv * 4 + 1][c] << 16);
+        v.y = (uint32_t)tile[tv * 4 + 2][c] | ((uint32_t)tile[tv * 4 + 3][c] << 16);
+        *reinterpret_cast<uint2*>(dst + (int64_t)packed_row(c0 + c, mode) * ld_dst + r0 + tv * 4) = v;
+    }
+}
+
+void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t ld_dst, int mode = kPackNone) {
+    dim3 grid(C / 64, R / 64);
+    transpose_bf16<<<grid, 256, 0, s>>>(reinterpret_cast<const uint16_t*>(src), C,
+                                        reinterpret_cast<uint16_t*>(dst), ld_dst, mode);
+}
+
+__global__ void fill_zero_f32(float* p, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+}
+
+void zero(hipStream_t s, float* p, size_t n) {
+    size_t blocks = (n + 1023) / 1024;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    fill_zero_f32<<<(unsigned)blocks, 256, 0, s>>>(p, n);
+}
+
+struct Bf16Workspace {
+    bf16 *WguT, *WdT, *WoT;
+    bf16 *X, *u, *v, *a, *y, *dz;
+    bf16 *dy, *XT, *aT, *yT, *dzT, *dyT, *duT, *dvT;
+    RowMeta meta;
+    RowOut out;
+    int64_t Mp;
+    size_t bytes;
+};
+
+Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
+    Carver c(ws);
+    Bf16Workspace w{};
+    const size_t Mp = (size_t)ceil_div64(sh.rows_max(), kTileM) * kTileM;
+    const size_t d = sh.d, ff = sh.ff, V = sh.V;
+    w.Mp = (int64_t)Mp;
+    w.WguT = c.take<bf16>(2 * ff * d);
+    w.WdT = c.take<bf16>(d * ff);
+    w.WoT = c.take<bf16>(V * d);
+    w.X = c.take<bf16>(Mp * d);
+    w.u = c.take<bf16>(Mp * ff);
+    w.v = c.take<bf16>(Mp * ff);
+    w.a = c.take<bf16>(Mp * ff);
+    w.y = c.take<bf16>(Mp * d);
+    w.dz = c.take<bf16>(Mp * V);
+    w.meta.token = c.take<uint8_t>(Mp);
+    w.meta.logp_old = c.take<float>(Mp);
+    w.meta.adv = c.take<float>(Mp);
+    w.out.term = c.take<float>(Mp);
+    w.out.ratio = c.take<float>(Mp);
+    w.out.dlogp = c.take<float>(Mp);
+    w.out.clipped = c.take<uint8_t>(Mp);
+    if (bwd) w.dy = c.take<bf16>(Mp * d);
+    if (grads) {
+        w.XT = c.take<bf16>(d * Mp);
+        w.aT = c.take<bf16>(ff * Mp);
+        w.yT = c.take<bf16>(d * Mp);
+        w.dzT = c.take<bf16>(V * Mp);
+        w.dyT = c.take<bf16>(d * Mp);
+        w.duT = c.take<bf16>(ff * Mp);
+        w.dvT = c.take<bf16>(ff * Mp);
+    }
+    w.bytes = c.used();
+    return w;
+}
+
+// Reduction split for an output of `tiles` tiles and `steps` 64-wide reduction steps: the
+// smallest split whose workgroup count fills whole rounds of the chip's 256 CUs to >= 97 %.
+int pick_splits(int tiles, int steps) {
+    int max_s = steps / 8;
+    if (max_s < 1) max_s = 1;
+    if (max_s > 64) max_s = 64;
+    int best = 1;
+    double best_eff = 0.0;
+    for (int s = 1; s <= max_s; ++s) {
+        const double rounds = (double)tiles * s / 256.0;
+        const double eff = rounds / (double)(int64_t)(rounds + 0.999999);
+        if (eff > best_eff + 1e-9) {
+            best_eff = eff;
+            best = s;
+        }
+        if (eff >= 0.97) return s;
+    }
+    return best;
+}
+
+GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K) {
+    GemmProblem p{};
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.A2 = A; p.B2 = B; p.lda2 = lda; p.ldb2 = ldb;
+    p.M = M; p.N = N; p.K1 = K; p.K2 = 0; p.splits = 1;
+    return p;
+}
+
+}  // namespace
+
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads) {
+    return carve(nullptr, sh, want_grads, want_grads).bytes;
+}
+
+int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s) {
+    const bool grads = io.want_grads();
+    const bool bwd = grads || io.dX != nullptr;
+    Bf16Workspace w = carve(ws, sh, bwd, grads);
+    const int Mp = (int)w.Mp;
+    const int d = sh.d, ff = sh.ff, V = sh.V;
+    const bf16* Wg = static_cast<const bf16*>(io.Wg);
+    const bf16* Wu = static_cast<const bf16*>(io.Wu);
+    const bf16* Wd = static_cast<const bf16*>(io.Wd);
+    const bf16* Wo = static_cast<const bf16*>(io.Wo);
+
+    {
+        StageTimer t(ST_WEIGHT_LAYOUT, s);
+        transpose(s, Wg, d, ff, w.WguT, d, kPackGate);   // [d, ff] -> packed rows of [2 ff, d]
+        transpose(s, Wu, d, ff, w.WguT, d, kPackUp);
+        transpose(s, Wd, ff, d, w.WdT, ff);              // [ff, d] -> [d, ff]
+        transpose(s, Wo, d, V, w.WoT, d);                // [d, V]  -> [V, d]
+    }
+    int rc = launch_gather(sh, io, 2, w.X, Mp, w.meta, s);
+    if (rc != PCM_OK) return rc;
+    {
+        StageTimer t(ST_GEMM_GATE_UP, s);
+        launch_gemm(problem(w.X, d, w.WguT, d, Mp, 2 * ff, d), EpiSwigluForward{w.u, w.v, w.a, ff}, s);
+    }
+    {
+        StageTimer t(ST_GEMM_DOWN, s);
+        launch_gemm(problem(w.a, ff, w.WdT, ff, Mp, d, ff), EpiStoreBf16{w.y, d, Mp}, s);
+    }
+    {
+        StageTimer t(ST_GEMM_LOGITS_LOSS, s);
+        EpiLogitsLoss epi{w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A,
+                          io.eps_low, io.eps_high, io.loss_scale, bwd ? w.dz : nullptr, io.logp_out, w.out};
+        launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d), epi, s);
+    }
+    rc = launch_loss_reduce(sh, io, w.out, s);
+    if (rc != PCM_OK) return rc;
+    if (!bwd) return launch_status();
+
+    {
+        StageTimer t(ST_GEMM_DY, s);
+        launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
+    }
+    if (grads) {
+        StageTimer t(ST_GEMM_DWO, s);
+        transpose(s, w.y, Mp, d, w.yT, Mp);
+        transpose(s, w.dz, Mp, V, w.dzT, Mp);
+        GemmProblem p = problem(w.yT, Mp, w.dzT, Mp, d, V, Mp);                                   // dWo = y^T dz
+        p.splits = pick_splits((d / kTileM) * (V / kTileN), Mp / kTileK);
+        if (p.splits > 1) zero(s, io.dWo, (size_t)d * V);
+        launch_gemm(p, EpiAccumulateF32{io.dWo, V, p.splits > 1}, s);
+    }
+    if (grads) {
+        StageTimer t(ST_GEMM_DWD, s);
+        transpose(s, w.a, Mp, ff, w.aT, Mp);
+        transpose(s, w.dy, Mp, d, w.dyT, Mp);
+        GemmProblem p = problem(w.aT, Mp, w.dyT, Mp, ff, d, Mp);                                  // dWd = a^T dy
+        p.splits = pick_splits((ff / kTileM) * (d / kTileN), Mp / kTileK);
+        if (p.splits > 1) zero(s, io.dWd, (size_t)ff * d);
+        launch_gemm(p, EpiAccumulateF32{io.dWd, d, p.splits > 1}, s);
+    }
+    {
+        StageTimer t(ST_GEMM_DA, s);
+        launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
+    }
+    if (grads) {
+        StageTimer t(ST_GEMM_DWG_DWU, s);
+        transpose(s, w.X, Mp, d, w.XT, Mp);
+        transpose(s, w.u, Mp, ff, w.duT, Mp);
+        transpose(s, w.v, Mp, ff, w.dvT, Mp);
+        GemmProblem p = problem(w.XT, Mp, w.duT, Mp, d, ff, Mp);                                  // dWg = X^T du
+        p.splits = pick_splits((d / kTileM) * (ff / kTileN), Mp / kTileK);
+        if (p.splits > 1) {
+            zero(s, io.dWg, (size_t)d * ff);
+            zero(s, io.dWu, (size_t)d * ff);
+        }
+        launch_gemm(p, EpiAccumulateF32{io.dWg, ff, p.splits > 1}, s);
+        p.B = w.dvT;                                                                              // dWu = X^T dv
+        launch_gemm(p, EpiAccumulateF32{io.dWu, ff, p.splits > 1}, s);
+    }
+    if (io.dX) {
+        StageTimer t(ST_GEMM_DX, s);
+        GemmProblem p = problem(w.u, ff, Wg, ff, Mp, d, ff);                                      // dX = du Wg^T + dv Wu^T
+        p.A2 = w.v; p.B2 = Wu; p.lda2 = ff; p.ldb2 = ff; p.K2 = ff;
+        launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX), d, (int)sh.rows_max()}, s);
+    }
+    return launch_status();
+}
+
+}  // namespace pcm

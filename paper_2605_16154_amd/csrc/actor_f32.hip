@@ -1,0 +1,282 @@
+// fp32 path of the masked GRPO actor step (Eq. 11): plain vector-ALU kernels.
+//
+// This path exists for small heads and for checking the method at fp32 accuracy; it is bound by
+// the fp32 vector ALUs, not by the matrix cores.  One LDS-tiled GEMM kernel with general strides
+// serves all nine products of the forward and backward pass; reductions over the row dimension
+// (the weight gradients) are split across workgroups and combined with fp32 atomics.
+#include "actor.h"
+
+namespace pcm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int BM = 64, BN = 64, BK = 16;
+
+// C[m,n] (+)= sum_k A[m*sam + k*sak] * B[k*sbk + n*sbn]; grid = (tiles_n, tiles_m, splits).
+// splits > 1: each z-slice adds its partial product with atomics (C must hold the base value).
+__global__ __launch_bounds__(kThreads) void sgemm(const float* __restrict__ A, int64_t sam, int64_t sak,
+                                                  const float* __restrict__ B, int64_t sbk, int64_t sbn,
+                                                  float* __restrict__ C, int64_t ldc, int M, int N, int K,
+                                                  int k_per_split, int accumulate) {
+    __shared__ float As[BK][BM + 4];
+    __shared__ float Bs[BK][BN + 4];
+    const int tid = threadIdx.x;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int kb = blockIdx.z * k_per_split;
+    const int ke = min(K, kb + k_per_split);
+    const int tm = (tid / 16) * 4, tn = (tid % 16) * 4;
+    float acc[4][4] = {};
+    for (int k0 = kb; k0 < ke; k0 += BK) {
+#pragma unroll
+        for (int q = 0; q < (BM * BK) / kThreads; ++q) {
+            const int e = tid + q * kThreads;
+            int mm, kk;
+            if (sak == 1) { mm = e / BK; kk = e % BK; } else { kk = e / BM; mm = e % BM; }
+            const int gm = m0 + mm, gk = k0 + kk;
+            As[kk][mm] = (gm < M && gk < ke) ? A[gm * sam + gk * sak] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < (BN * BK) / kThreads; ++q) {
+            const int e = tid + q * kThreads;
+            int nn, kk;
+            if (sbk == 1) { nn = e / BK; kk = e % BK; } else { kk = e / BN; nn = e % BN; }
+            const int gn = n0 + nn, gk = k0 + kk;
+            Bs[kk][nn] = (gn < N && gk < ke) ? B[gk * sbk + gn * sbn] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][tm + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tn + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int gm = m0 + tm + i;
+        if (gm >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gn = n0 + tn + j;
+            if (gn >= N) continue;
+            float* c = C + gm * ldc + gn;
+            if (gridDim.z > 1) atomicAdd(c, acc[i][j]);
+            else if (accumulate) *c += acc[i][j];
+            else *c = acc[i][j];
+        }
+    }
+}
+
+__global__ void fill_zero(float* p, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+}
+
+__global__ void swiglu_forward(const float* __restrict__ u, const float* __restrict__ v, float* __restrict__ a,
+                               size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float x = u[i];
+        a[i] = x / (1.f + expf(-x)) * v[i];
+    }
+}
+
+// In place: u <- du = da * v * silu'(u), v <- dv = da * silu(u).
+__global__ void swiglu_backward(float* __restrict__ u, float* __restrict__ v, const float* __restrict__ da,
+                                size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const float x = u[i], g = da[i], vv = v[i];
+        const float s = 1.f / (1.f + expf(-x));
+        u[i] = g * vv * (s * (1.f + x * (1.f - s)));
+        v[i] = g * (x * s);
+    }
+}
+
+__device__ inline float wave_max(float x) {
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) x = fmaxf(x, __shfl_xor(x, d, kWave));
+    return x;
+}
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) x += __shfl_xor(x, d, kWave);
+    return x;
+}
+
+// One wavefront per row: log-softmax at the target bin, ratio, clipped surrogate, and (in place)
+// z <- dz = coef * (onehot - softmax).
+__global__ __launch_bounds__(kThreads) void loss_rows(float* __restrict__ z, int V, const uint8_t* __restrict__ token,
+                                                      const float* __restrict__ logp_old,
+                                                      const float* __restrict__ adv_row,
+                                                      const int32_t* __restrict__ n_kept, int max_chunks, int A,
+                                                      int64_t rows_total, float eps_low, float eps_high,
+                                                      float loss_scale, int write_dz, float* logp_out, float* term,
+                                                      float* ratio, float* dlogp, uint8_t* clipped) {
+    const int lane = threadIdx.x % kWave;
+    const int64_t r = (int64_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+    if (r >= rows_total) return;
+    int nk = *n_kept;
+    nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
+    const bool live = r < (int64_t)nk * A;
+    float* zr = z + r * V;
+    float mx = -INFINITY;
+    for (int j = lane; j < V; j += kWave) mx = fmaxf(mx, zr[j]);
+    mx = wave_max(mx);
+    float se = 0.f;
+    for (int j = lane; j < V; j += kWave) se += expf(zr[j] - mx);
+    se = wave_sum(se);
+    const int b = token[r];
+    const float lse = mx + logf(se);
+    const float lp = zr[b] - lse;
+    const LossRow lr = loss_row(lp, logp_old[r], adv_row[r], eps_low, eps_high, loss_scale);
+    if (lane == 0) {
+        term[r] = live ? lr.term : 0.f;
+        ratio[r] = lr.ratio;
+        dlogp[r] = lr.dlogp;
+        clipped[r] = lr.clipped;
+        if (logp_out && live) logp_out[r] = lp;
+    }
+    if (write_dz) {
+        const float coef = live ? lr.coef : 0.f;
+        for (int j = lane; j < V; j += kWave) {
+            const float p = expf(zr[j] - lse);
+            zr[j] = coef * ((j == b ? 1.f : 0.f) - p);
+        }
+    }
+}
+
+struct F32Workspace {
+    float *X, *u, *v, *a, *y, *z, *dy, *da;
+    RowMeta meta;
+    RowOut out;
+    size_t bytes;
+};
+
+F32Workspace carve(void* ws, const ActorShape& sh, bool grads) {
+    Carver c(ws);
+    F32Workspace w{};
+    const size_t M = (size_t)sh.rows_max();
+    w.X = c.take<float>(M * sh.d);
+    w.u = c.take<float>(M * sh.ff);
+    w.v = c.take<float>(M * sh.ff);
+    w.a = c.take<float>(M * sh.ff);
+    w.y = c.take<float>(M * sh.d);
+    w.z = c.take<float>(M * sh.V);
+    w.meta.token = c.take<uint8_t>(M);
+    w.meta.logp_old = c.take<float>(M);
+    w.meta.adv = c.take<float>(M);
+    w.out.term = c.take<float>(M);
+    w.out.ratio = c.take<float>(M);
+    w.out.dlogp = c.take<float>(M);
+    w.out.clipped = c.take<uint8_t>(M);
+    if (grads) {
+        w.dy = c.take<float>(M * sh.d);
+        w.da = c.take<float>(M * sh.ff);
+    }
+    w.bytes = c.used();
+    return w;
+}
+
+enum Layout { kRowMajor, kTransposed };
+
+// C[M,N] (+)= op(A) op(B) with A given as [M,K] row-major (or [K,M] if a_t) and B as [K,N]
+// row-major (or [N,K] if b_t).
+void gemm(hipStream_t s, const float* A, bool a_t, const float* B, bool b_t, float* C, int M, int N, int K,
+          int splits, bool accumulate) {
+    const int64_t sam = a_t ? 1 : K, sak = a_t ? M : 1;
+    const int64_t sbk = b_t ? 1 : N, sbn = b_t ? K : 1;
+    if (splits < 1) splits = 1;
+    int k_per = ceil_div(ceil_div(K, splits), BK) * BK;
+    splits = ceil_div(K, k_per);
+    dim3 grid(ceil_div(N, BN), ceil_div(M, BM), splits);
+    sgemm<<<grid, kThreads, 0, s>>>(A, sam, sak, B, sbk, sbn, C, N, M, N, K, k_per, accumulate ? 1 : 0);
+}
+
+int pick_splits(int M, int N, int K) {
+    const int tiles = ceil_div(M, BM) * ceil_div(N, BN);
+    int splits = ceil_div(1024, tiles);
+    const int max_splits = ceil_div(K, 4 * BK);
+    if (splits > max_splits) splits = max_splits;
+    return splits < 1 ? 1 : splits;
+}
+
+void zero(hipStream_t s, float* p, size_t n) {
+    const unsigned blocks = (unsigned)((n + 1023) / 1024);
+    fill_zero<<<blocks < 2048 ? (blocks ? blocks : 1) : 2048, 256, 0, s>>>(p, n);
+}
+
+}  // namespace
+
+size_t actor_f32_workspace_bytes(const ActorShape& sh, bool want_grads) {
+    return carve(nullptr, sh, want_grads).bytes;
+}
+
+int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s) {
+    const bool bwd = io.want_grads() || io.dX != nullptr;
+    F32Workspace w = carve(ws, sh, bwd);
+    const int M = (int)sh.rows_max();
+    const int d = sh.d, ff = sh.ff, V = sh.V;
+    const float* Wg = static_cast<const float*>(io.Wg);
+    const float* Wu = static_cast<const float*>(io.Wu);
+    const float* Wd = static_cast<const float*>(io.Wd);
+    const float* Wo = static_cast<const float*>(io.Wo);
+    const size_t n_ff = (size_t)M * ff;
+    const unsigned ew_blocks = (unsigned)((n_ff + 1023) / 1024) < 4096 ? (unsigned)((n_ff + 1023) / 1024) : 4096;
+
+    int rc = launch_gather(sh, io, 4, w.X, M, w.meta, s);
+    if (rc != PCM_OK) return rc;
+    {
+        StageTimer t(ST_F32_FORWARD, s);
+        gemm(s, w.X, false, Wg, false, w.u, M, ff, d, 1, false);
+        gemm(s, w.X, false, Wu, false, w.v, M, ff, d, 1, false);
+        swiglu_forward<<<ew_blocks, 256, 0, s>>>(w.u, w.v, w.a, n_ff);
+        gemm(s, w.a, false, Wd, false, w.y, M, d, ff, 1, false);
+        gemm(s, w.y, false, Wo, false, w.z, M, V, d, 1, false);
+    }
+    {
+        StageTimer t(ST_F32_LOSS, s);
+        loss_rows<<<(unsigned)ceil_div64(M, kThreads / kWave), kThreads, 0, s>>>(
+            w.z, V, w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A, M, io.eps_low,
+            io.eps_high, io.loss_scale, bwd ? 1 : 0, io.logp_out, w.out.term, w.out.ratio,
+            w.out.dlogp, w.out.clipped);
+    }
+    rc = launch_loss_reduce(sh, io, w.out, s);
+    if (rc != PCM_OK) return rc;
+    if (!bwd) return launch_status();
+    {
+        StageTimer t(ST_F32_BACKWARD, s);
+        float* dz = w.z;
+        if (io.want_grads()) {
+            zero(s, io.dWo, (size_t)d * V);
+            zero(s, io.dWd, (size_t)ff * d);
+            zero(s, io.dWg, (size_t)d * ff);
+            zero(s, io.dWu, (size_t)d * ff);
+            gemm(s, w.y, true, dz, false, io.dWo, d, V, M, pick_splits(d, V, M), false);      // dWo = y^T dz
+        }
+        gemm(s, dz, false, Wo, true, w.dy, M, d, V, 1, false);                                  // dy = dz Wo^T
+        if (io.want_grads())
+            gemm(s, w.a, true, w.dy, false, io.dWd, ff, d, M, pick_splits(ff, d, M), false);  // dWd = a^T dy
+        gemm(s, w.dy, false, Wd, true, w.da, M, ff, d, 1, false);                               // da = dy Wd^T
+        swiglu_backward<<<ew_blocks, 256, 0, s>>>(w.u, w.v, w.da, n_ff);                        // u <- du, v <- dv
+        if (io.want_grads()) {
+            gemm(s, w.X, true, w.u, false, io.dWg, d, ff, M, pick_splits(d, ff, M), false);   // dWg = X^T du
+            gemm(s, w.X, true, w.v, false, io.dWu, d, ff, M, pick_splits(d, ff, M), false);   // dWu = X^T dv
+        }
+        if (io.dX) {
+            float* dX = static_cast<float*>(io.dX);
+            gemm(s, w.u, false, Wg, true, dX, M, d, ff, 1, false);                              // dX = du Wg^T
+            gemm(s, w.v, false, Wu, true, dX, M, d, ff, 1, true);                               //    + dv Wu^T
+        }
+    }
+    return launch_status();
+}
+
+}  // namespace pcm

@@ -1,0 +1,151 @@
+// Physical shrinking of the batch (Sec. 4.5): copy the kept chunks' hidden rows into a dense
+// matrix and expand the per-trajectory advantage to rows; plus the fixed-order reduction of the
+// per-row loss terms of Eq. 11.
+//
+// The gather is a pure streaming copy (row r of the compacted batch is token r % A of chunk
+// kept_idx[r / A]); each workgroup moves a block of rows with 16-byte accesses, several loads in
+// flight per lane.  Rows at and beyond n_kept * A are zero-filled with advantage 0, so they add
+// nothing downstream.
+#include "actor.h"
+
+namespace pcm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerBlock = 8;
+
+template <typename Vec>
+__device__ inline Vec zero_vec();
+template <>
+__device__ inline uint4 zero_vec<uint4>() { return make_uint4(0, 0, 0, 0); }
+template <>
+__device__ inline uint32_t zero_vec<uint32_t>() { return 0u; }
+template <>
+__device__ inline uint16_t zero_vec<uint16_t>() { return 0; }
+
+template <typename Vec>
+__global__ __launch_bounds__(kThreads) void gather_rows(
+    const Vec* __restrict__ hidden, const uint8_t* __restrict__ tokens, const float* __restrict__ logp_old,
+    const float* __restrict__ adv, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ n_kept,
+    int max_chunks, int T, int N, int A, int V, int vec_per_row, int64_t rows_pad, Vec* __restrict__ X,
+    uint8_t* m_token, float* m_logp_old, float* m_adv) {
+    __shared__ int64_t src_row[kRowsPerBlock];
+    int nk = *n_kept;
+    nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
+    const int64_t rows_valid = (int64_t)nk * A;
+    const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlock;
+    const int tid = threadIdx.x;
+    if (tid < kRowsPerBlock) {
+        const int64_t r = r0 + tid;
+        int64_t src = -1;
+        if (r < rows_valid) {
+            const int ci = (int)(r / A), tok = (int)(r % A);
+            int id = kept_idx[ci];
+            float a = 0.f;
+            if (id >= 0 && (int64_t)id < (int64_t)T * N) a = adv[id / N];
+            else id = 0;
+            src = (int64_t)id * A + tok;
+            int b = tokens[src];
+            m_token[r] = (uint8_t)(b < V ? b : V - 1);
+            m_logp_old[r] = logp_old[src];
+            m_adv[r] = a;
+        } else if (r < rows_pad) {
+            m_token[r] = 0;
+            m_logp_old[r] = 0.f;
+            m_adv[r] = 0.f;
+        }
+        src_row[tid] = src;
+    }
+    __syncthreads();
+    const int total = kRowsPerBlock * vec_per_row;
+    constexpr int kUnroll = 8;
+    for (int base = tid; base < total; base += kThreads * kUnroll) {
+        Vec v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int e = base + u * kThreads;
+            v[u] = zero_vec<Vec>();
+            if (e < total) {
+                const int64_t src = src_row[e / vec_per_row];
+                if (src >= 0) v[u] = hidden[src * vec_per_row + e % vec_per_row];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int e = base + u * kThreads;
+            if (e < total) {
+                const int64_t r = r0 + e / vec_per_row;
+                if (r < rows_pad) X[r * vec_per_row + e % vec_per_row] = v[u];
+            }
+        }
+    }
+}
+
+// One workgroup; lane-strided fp64 partials combined by a fixed tree, so the result does not
+// depend on anything but the row values.
+__global__ __launch_bounds__(1024) void loss_reduce(const float* __restrict__ term,
+                                                     const float* __restrict__ ratio,
+                                                     const float* __restrict__ dlogp,
+                                                     const uint8_t* __restrict__ clipped,
+                                                     const int32_t* __restrict__ n_kept, int max_chunks, int A,
+                                                     float loss_scale, float* loss_out, float* stats_out) {
+    __shared__ double red[4][1024];
+    int nk = *n_kept;
+    nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
+    const int64_t rows = (int64_t)nk * A;
+    double acc[4] = {0, 0, 0, 0};
+    for (int64_t r = threadIdx.x; r < rows; r += 1024) {
+        acc[0] += (double)term[r];
+        acc[1] += (double)ratio[r];
+        acc[2] += (double)dlogp[r];
+        acc[3] += (double)clipped[r];
+    }
+    for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = acc[q];
+    __syncthreads();
+    for (int half = 512; half > 0; half >>= 1) {
+        if ((int)threadIdx.x < half)
+            for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + half];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        *loss_out = (float)(-(double)loss_scale * red[0][0]);
+        if (stats_out) {
+            const double n = rows > 0 ? (double)rows : 1.0;
+            stats_out[0] = (float)(red[3][0] / n);
+            stats_out[1] = (float)(red[1][0] / n);
+            stats_out[2] = (float)(red[2][0] / n);
+            stats_out[3] = (float)rows;
+        }
+    }
+}
+
+}  // namespace
+
+int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t rows_pad,
+                  RowMeta meta, hipStream_t s) {
+    StageTimer t(ST_GATHER, s);
+    const int64_t row_bytes = (int64_t)sh.d * elem_bytes;
+    const unsigned blocks = (unsigned)ceil_div64(rows_pad, kRowsPerBlock);
+    const bool aligned16 = row_bytes % 16 == 0 && (reinterpret_cast<uintptr_t>(io.hidden) & 15u) == 0 &&
+                           (reinterpret_cast<uintptr_t>(X) & 15u) == 0;
+#define PCM_GATHER(Vec, vpr)                                                                             \
+    gather_rows<Vec><<<blocks, kThreads, 0, s>>>(static_cast<const Vec*>(io.hidden), io.tokens,          \
+                                                 io.logp_old, io.adv, io.kept_idx, io.n_kept,            \
+                                                 sh.max_chunks, sh.T, sh.N, sh.A, sh.V, (int)(vpr),      \
+                                                 rows_pad, static_cast<Vec*>(X), meta.token,             \
+                                                 meta.logp_old, meta.adv)
+    if (aligned16) PCM_GATHER(uint4, row_bytes / 16);
+    else if (elem_bytes == 4) PCM_GATHER(uint32_t, sh.d);
+    else PCM_GATHER(uint16_t, sh.d);
+#undef PCM_GATHER
+    return launch_status();
+}
+
+int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipStream_t s) {
+    StageTimer t(ST_REDUCE, s);
+    loss_reduce<<<1, 1024, 0, s>>>(out.term, out.ratio, out.dlogp, out.clipped, io.n_kept, sh.max_chunks,
+                                   sh.A, io.loss_scale, io.loss_out, io.stats_out);
+    return launch_status();
+}
+
+}  // namespace pcm

@@ -1,0 +1,204 @@
+// pcm_sample_chunks: fixed-budget weighted sampling without replacement (Eq. 10) and the
+// compaction that expresses physical shrinking (Sec. 4.5; Algorithm 1, inner loop).
+//
+// Two launches:
+//   scan     per-trajectory kept counts min(B, N_i) (0 if inactive) are known before any draw;
+//            one workgroup turns them into exclusive offsets with an LDS prefix scan
+//   compact  one wavefront per trajectory: integer weights in LDS, lanes own contiguous runs of
+//            chunk slots, an inclusive wave scan of lane sums is kept up to date across the
+//            min(B, N_i) successive draws, then kept slots are written in ascending order at the
+//            trajectory's offset (wave prefix of per-lane popcounts)
+//
+// All arithmetic after the weight quantisation is integer, and the random bits depend only on
+// (seed, step, trajectory, round), so the kept set is a pure function of the inputs.
+#include "common.h"
+
+namespace pcm {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / kWave;
+
+// Philox-4x32, 10 rounds (Salmon et al., SC'11): multipliers and Weyl key increments as published.
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
+
+__device__ inline uint64_t philox_bits(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                       uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(kPhiloxM0, c0), lo0 = kPhiloxM0 * c0;
+        const uint32_t hi1 = __umulhi(kPhiloxM1, c2), lo1 = kPhiloxM1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += kPhiloxW0; k1 += kPhiloxW1;
+    }
+    return (uint64_t)c0 | ((uint64_t)c1 << 32);
+}
+
+__device__ inline int kept_count(const int32_t* n_chunks, const uint8_t* active, int i, int N, int B) {
+    if (active && !active[i]) return 0;
+    int Ni = n_chunks ? n_chunks[i] : N;
+    Ni = Ni < 0 ? 0 : (Ni > N ? N : Ni);
+    return Ni < B ? Ni : B;
+}
+
+__device__ inline int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int up = __shfl_up(v, d, kWave);
+        if (lane >= d) v += up;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(kThreads) void sample_scan(const int32_t* __restrict__ n_chunks,
+                                                        const uint8_t* __restrict__ active, int T, int N,
+                                                        int B, int32_t* kept_offsets, int32_t* n_kept) {
+    __shared__ int wave_total[kWavesPerBlock];
+    const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+    int carry = 0;
+    for (int base = 0; base < T; base += kThreads) {
+        const int i = base + tid;
+        const int cnt = i < T ? kept_count(n_chunks, active, i, N, B) : 0;
+        const int incl = wave_inclusive_scan(cnt, lane);
+        if (lane == kWave - 1) wave_total[wv] = incl;
+        __syncthreads();
+        int before = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) {
+            if (w < wv) before += wave_total[w];
+            all += wave_total[w];
+        }
+        if (i < T) kept_offsets[i] = carry + before + incl - cnt;
+        carry += all;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        kept_offsets[T] = carry;
+        *n_kept = carry;
+    }
+}
+
+// LDS: K quantised phase weights, then one N-entry weight array per wavefront.
+__global__ __launch_bounds__(kThreads) void sample_compact(
+    const double* __restrict__ keep_probs, const uint8_t* __restrict__ phase,
+    const int32_t* __restrict__ n_chunks, const uint8_t* __restrict__ active, int T, int N, int K, int B,
+    uint64_t seed, uint64_t step, const int32_t* __restrict__ kept_offsets, int32_t* kept_idx) {
+    extern __shared__ uint32_t lds[];
+    uint32_t* qtab = lds;
+    const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+    uint32_t* w = lds + PCM_MAX_PHASES + (size_t)wv * N;
+
+    const int waves_per_block = blockDim.x / kWave;
+    for (int c = tid; c < K; c += blockDim.x) {
+        const double x = keep_probs[c] * 65536.0 + 0.5;
+        uint32_t q = 1u;
+        if (x >= 65536.0) q = 65536u;
+        else if (x >= 1.0) q = (uint32_t)x;   // truncation = floor for positive x
+        qtab[c] = q;
+    }
+    __syncthreads();
+
+    const int i = blockIdx.x * waves_per_block + wv;
+    if (i >= T) return;                       // no barrier below this point
+    const int m = kept_count(n_chunks, active, i, N, B);
+    if (m == 0) return;
+    int Ni = n_chunks ? n_chunks[i] : N;
+    Ni = Ni > N ? N : Ni;
+
+    const int per_lane = (N + kWave - 1) / kWave;   // <= 64 because N <= 4096
+    const int k_lo = lane * per_lane;
+    const uint8_t* ph = phase + (size_t)i * N;
+    uint32_t lane_sum = 0;
+    for (int j = 0; j < per_lane; ++j) {
+        const int k = k_lo + j;
+        uint32_t wk = 0;
+        if (k < Ni) {
+            int c = ph[k];
+            c = c < K ? c : K - 1;
+            wk = qtab[c];
+        }
+        if (k < N) w[k] = wk;
+        lane_sum += wk;
+    }
+    uint32_t incl = (uint32_t)wave_inclusive_scan((int)lane_sum, lane);
+    uint32_t W_rem = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+    uint64_t mask = 0;
+
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    const uint32_t s0 = (uint32_t)step, s1 = (uint32_t)(step >> 32);
+    for (int r = 0; r < m; ++r) {
+        const uint64_t x = philox_bits((uint32_t)i, (uint32_t)r, s0, s1, k0, k1);
+        const uint32_t t = (uint32_t)__umul64hi(x, (uint64_t)W_rem);   // in [0, W_rem)
+        const uint64_t over = __ballot(incl > t);
+        if (over == 0) break;                 // cannot happen while W_rem > 0; keeps the loop total
+        const int L = __ffsll((long long)over) - 1;
+        uint32_t picked_w = 0;
+        if (lane == L) {
+            uint32_t run = incl - lane_sum;
+            for (int j = 0; j < per_lane; ++j) {
+                const int k = k_lo + j;
+                if (k >= N) break;
+                const uint32_t wk = w[k];
+                run += wk;
+                if (wk > 0 && run > t) {
+                    picked_w = wk;
+                    w[k] = 0;
+                    mask |= (uint64_t)1 << j;
+                    break;
+                }
+            }
+            lane_sum -= picked_w;
+        }
+        picked_w = (uint32_t)__shfl((int)picked_w, L, kWave);
+        if (lane >= L) incl -= picked_w;
+        W_rem -= picked_w;
+    }
+
+    const int mine = __popcll(mask);
+    int pos = kept_offsets[i] + wave_inclusive_scan(mine, lane) - mine;
+    while (mask) {
+        const int j = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        kept_idx[pos++] = i * N + k_lo + j;
+    }
+}
+
+bool shape_ok(int T, int N, int K, int B) {
+    return T >= 1 && N >= 1 && N <= PCM_MAX_CHUNK_SLOTS && K >= 1 && K <= PCM_MAX_PHASES && B >= 1 &&
+           (int64_t)T * N < (int64_t)1 << 31;
+}
+
+}  // namespace
+}  // namespace pcm
+
+using namespace pcm;
+
+extern "C" size_t pcm_sample_chunks_workspace_bytes(int T, int N, int K, int B) {
+    (void)T; (void)N; (void)K; (void)B;
+    return 0;   // offsets and counts live in the caller's output arrays
+}
+
+extern "C" int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
+                                 const uint8_t* active, int T, int N, int K, int B, uint64_t seed,
+                                 uint64_t step, int32_t* kept_idx, int32_t* kept_offsets, int32_t* n_kept,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!keep_probs || !phase || !kept_idx || !kept_offsets || !n_kept) return PCM_EINVAL;
+    if (!shape_ok(T, N, K, B)) return PCM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        StageTimer t(ST_SAMPLE_SCAN, s);
+        sample_scan<<<1, kThreads, 0, s>>>(n_chunks, active, T, N, B, kept_offsets, n_kept);
+    }
+    {
+        StageTimer t(ST_SAMPLE_COMPACT, s);
+        // one weight array per wavefront must fit the 64 KB a workgroup may take by default
+        const int waves = N > 2048 ? 2 : kWavesPerBlock;
+        const size_t lds_bytes = (PCM_MAX_PHASES + (size_t)waves * N) * sizeof(uint32_t);
+        sample_compact<<<ceil_div(T, waves), waves * kWave, lds_bytes, s>>>(
+            keep_probs, phase, n_chunks, active, T, N, K, B, seed, step, kept_offsets, kept_idx);
+    }
+    return launch_status();
+}

@@ -1,0 +1,276 @@
+"""GPU parity of grpo_masked_actor_step (Eq. 11 / Eq. 2 with PPO clipping) against the CPU checker.
+
+Tolerances: fp32 path relative 1e-5; bf16 path relative Frobenius 2e-2 on gradients (the GPU
+rounds intermediates to bf16, the checker works in fp64 on the same bf16-valued inputs).
+
+The clip decision is discrete: a row whose ratio sits on a threshold flips its whole gradient
+under the smallest perturbation.  Inputs are therefore conditioned so that no row's reference
+ratio lies within the path's accuracy of a threshold (logp_old of such rows is moved away by a
+fixed amount); both sides then take the same decisions and the comparison is well-posed.
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import pcm_oracle as O
+from workloads import (CONFIGS, make_head_numpy, make_head_torch, make_hidden_numpy, make_hidden_torch,
+                       make_rollouts, perturb_numpy, perturb_torch)
+
+pytestmark = pytest.mark.gpu
+GRADS = ("dWg", "dWu", "dWd", "dWo")
+
+
+@pytest.fixture(scope="module")
+def pcm():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2605_16154_amd as pcm
+    pcm.lib()
+    return pcm
+
+
+def dev(x, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def rel(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    den = np.linalg.norm(ref)
+    return np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got)
+
+
+def condition_logp_old(logp_old, logp_ref_rows, rows, eps_low, eps_high, margin):
+    """Move logp_old of rows whose reference log-ratio is within `margin` of a clip threshold."""
+    logp_old = logp_old.copy()
+    lr = logp_ref_rows - logp_old[rows]
+    for thr in (np.log1p(-eps_low), np.log1p(eps_high)):
+        near = np.abs(lr - thr) < margin
+        # push the ratio to the far side it is already on
+        logp_old[rows[near]] -= np.where(lr[near] >= thr, 2 * margin, -2 * margin)
+    return logp_old
+
+
+def make_problem(cfg, wstd=0.02, margin=0.0, kept=None, seed_step=0, eps=(0.2, 0.2), old_rel=0.5):
+    """Inputs of one actor step; old-policy weights = current + N(0, old_rel * wstd)."""
+    ro = make_rollouts(cfg, seed_step)
+    W = make_head_numpy(cfg, std=wstd)
+    W_old = perturb_numpy(cfg, W, std=wstd * old_rel)
+    hidden = make_hidden_numpy(cfg, seed_step)
+    tokens = (ro["tokens"].reshape(-1) % cfg.V).astype(np.uint8)
+    adv, active = O.advantages(ro["reward"], cfg.G)
+    if kept is None:
+        p = np.maximum(0.1, np.linspace(1.0, 0.05, cfg.K))
+        kept, _, _ = O.sample_chunks(p, ro["phase"], ro["n_chunks"], active, cfg.B, cfg.seed, seed_step)
+    zeros = np.zeros(hidden.shape[0])
+    old = O.actor_step(hidden, tokens, zeros, adv, kept, cfg.N, cfg.A, W_old["Wg"], W_old["Wu"], W_old["Wd"],
+                       W_old["Wo"], want_grads=False)
+    logp_old = np.zeros(hidden.shape[0])
+    logp_old[old["rows"]] = old["logp"]
+    if margin > 0:
+        cur = O.actor_step(hidden, tokens, zeros, adv, kept, cfg.N, cfg.A, W["Wg"], W["Wu"], W["Wd"], W["Wo"],
+                           want_grads=False)
+        logp_old = condition_logp_old(logp_old, cur["logp"], cur["rows"], eps[0], eps[1], margin)
+    logp_old = logp_old.astype(np.float32)
+    return dict(cfg=cfg, hidden=hidden, tokens=tokens, adv=adv, kept=kept.astype(np.int32), W=W, logp_old=logp_old)
+
+
+def run_both(pcm, pr, eps=(0.2, 0.2), scale=None, torch_dtype=torch.float32, max_kept=None, **kw):
+    cfg, W = pr["cfg"], pr["W"]
+    scale = 1.0 / cfg.T if scale is None else scale
+    ref = O.actor_step(pr["hidden"], pr["tokens"], pr["logp_old"], pr["adv"], pr["kept"], cfg.N, cfg.A,
+                       W["Wg"], W["Wu"], W["Wd"], W["Wo"], eps[0], eps[1], scale)
+    kept = pr["kept"]
+    max_kept = len(kept) if max_kept is None else max_kept
+    kept_buf = np.full(max_kept, -7, dtype=np.int32)       # tail entries are garbage on purpose
+    kept_buf[:len(kept)] = kept
+    out = pcm.grpo_masked_actor_step(
+        dev(pr["hidden"], torch_dtype), dev(pr["tokens"]), dev(pr["logp_old"]), dev(pr["adv"].astype(np.float32)),
+        dev(kept_buf), dev(np.array([len(kept)], np.int32)), cfg.T, cfg.N, cfg.A,
+        *(dev(W[k], torch_dtype) for k in ("Wg", "Wu", "Wd", "Wo")), eps[0], eps[1], scale,
+        max_kept_chunks=max_kept, **kw)
+    torch.cuda.synchronize()
+    return ref, {k: v.float().cpu().numpy() for k, v in out.items()}
+
+
+def check(ref, got, tol, n_rows, stats_tol=None):
+    stats_tol = max(tol, 1e-5) if stats_tol is None else stats_tol
+    assert abs(got["loss"][0] - ref["loss"]) <= tol * max(1.0, abs(ref["loss"])), (got["loss"], ref["loss"])
+    assert rel(got["logp"][:n_rows], ref["logp"]) <= tol
+    for k in GRADS:
+        assert rel(got[k], ref[k]) <= tol, (k, rel(got[k], ref[k]))
+    assert rel(got["dX"][:n_rows], ref["dX"]) <= tol, rel(got["dX"][:n_rows], ref["dX"])
+    assert np.allclose(got["stats"], ref["stats"], rtol=stats_tol, atol=stats_tol), (got["stats"], ref["stats"])
+
+
+# ------------------------------------------------------------------------------------------ fp32
+
+def test_fp32_cfg1_matches_checker(pcm):
+    pr = make_problem(CONFIGS["cfg1"])
+    ref, got = run_both(pcm, pr)
+    lr = np.log(ref["ratio"])
+    assert np.min(np.abs(lr - np.log(0.8))) > 1e-4 and np.min(np.abs(lr - np.log(1.2))) > 1e-4
+    check(ref, got, 1e-5, len(ref["rows"]))
+
+
+def test_fp32_ragged_shapes_clipping_and_padding(pcm):
+    # sizes that are not multiples of any tile, asymmetric clip, kept list shorter than its buffer
+    cfg = CONFIGS["cfg1"].with_(n_groups=3, G=4, N=9, K=3, B=4, d=72, ff=200, V=101, L=3, D=5, seed=8)
+    pr = make_problem(cfg, wstd=0.3, margin=1e-3, eps=(0.2, 0.4))
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), max_kept=len(pr["kept"]) + 5)
+    assert 0.02 < ref["stats"][0] < 0.98                      # both sides of the clip occur
+    check(ref, got, 1e-5, len(ref["rows"]))
+
+
+def test_fp32_all_kept_equals_unmasked_and_forward_only(pcm):
+    cfg = CONFIGS["cfg1"].with_(n_groups=1, N=8, B=8, d=64, ff=128)
+    kept = np.arange(cfg.T * cfg.N)
+    pr = make_problem(cfg, wstd=0.2, kept=kept)
+    ref, got = run_both(pcm, pr)
+    check(ref, got, 1e-5, len(ref["rows"]))
+    # kept ids produced by the sampler with B >= N are the same list: identical output
+    k2, _, nk = pcm.pcm_sample_chunks(dev(np.ones(cfg.K)), dev(np.zeros((cfg.T, cfg.N), np.uint8)), None, None,
+                                      cfg.N, 0, 0)
+    assert np.array_equal(k2.cpu().numpy(), kept)
+    # forward only: loss and logp without any gradient buffer
+    _, fwd = run_both(pcm, pr, want_grads=False, want_dX=False)
+    assert fwd["loss"][0] == got["loss"][0] and np.array_equal(fwd["logp"], got["logp"])
+    assert "dWg" not in fwd and "dX" not in fwd
+
+
+def test_fp32_uniform_rewards_and_empty_kept_list(pcm):
+    cfg = CONFIGS["cfg1"].with_(n_groups=1, N=8, B=3, d=64, ff=128)
+    pr = make_problem(cfg, wstd=0.2, kept=np.array([1, 5, 9, 20]))
+    pr["adv"] = np.zeros(cfg.T)                               # a collapsed group: every advantage is zero
+    ref, got = run_both(pcm, pr)
+    for k in GRADS + ("dX",):
+        assert not got[k].any()
+    assert got["loss"][0] == 0.0
+    pr["kept"] = np.zeros(0, np.int32)                        # nothing kept at all
+    pr["adv"] = np.ones(cfg.T)
+    _, got = run_both(pcm, pr, max_kept=4)
+    assert got["loss"][0] == 0.0 and got["stats"][3] == 0.0
+    for k in GRADS:
+        assert not got[k].any()
+
+
+# ------------------------------------------------------------------------------------------ bf16
+
+BF16_TOL = 2e-2
+
+
+def test_bf16_small_head_matches_checker(pcm):
+    # several 256-row tiles plus a ragged tail (37 chunks * 56 = 2072 rows), 2 x 3 x 1 weight tiles
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=4, N=16, K=4, B=5, d=512, ff=768, seed=12)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, 12, 0)
+    kept = kept[:37]
+    pr = make_problem(cfg, wstd=0.05, margin=0.08, kept=kept, old_rel=0.1)
+    ref, got = run_both(pcm, pr, torch_dtype=torch.bfloat16, max_kept=40)
+    assert 0.05 < ref["stats"][0] < 0.95
+    check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2)
+
+
+def test_bf16_all_kept_and_forward_only(pcm):
+    cfg = CONFIGS["cfg2"].with_(n_groups=1, G=4, N=6, K=3, B=6, d=256, ff=256, seed=13)
+    pr = make_problem(cfg, wstd=0.08, margin=0.08, kept=np.arange(cfg.T * cfg.N), old_rel=0.1)
+    ref, got = run_both(pcm, pr, torch_dtype=torch.bfloat16)
+    check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2)
+    _, fwd = run_both(pcm, pr, torch_dtype=torch.bfloat16, want_grads=False, want_dX=False)
+    assert fwd["loss"][0] == got["loss"][0] and np.array_equal(fwd["logp"], got["logp"])
+    pr["adv"] = np.zeros(cfg.T)
+    _, zero = run_both(pcm, pr, torch_dtype=torch.bfloat16)
+    for k in GRADS + ("dX",):
+        assert not zero[k].any()
+
+
+@pytest.mark.timeout(900)
+def test_bf16_full_size_head_sampled_rows_and_one_group(pcm):
+    """LIBERO-shaped head (d = 4096, ff = 11008) in the launch configuration the benchmark times.
+
+    (a) whole batch (64 trajectories x 12 kept chunks): per-row outputs (logp, dX) of sampled
+        chunks against the checker, which can compute a row on its own;
+    (b) the weight gradients of the whole batch equal the sum over groups of per-group calls
+        (additivity of Eq. 11 over trajectories), tying the full launch to (c);
+    (c) one group's kept rows (5,376 rows) against the full checker, weight gradients included.
+    """
+    cfg = CONFIGS["cfg2"]
+    dv = torch.device("cuda")
+    ro = make_rollouts(cfg, 0)
+    adv, active = O.advantages(ro["reward"], cfg.G)
+    C, valid = O.phase_scores(ro["actions"], ro["phase"], ro["reward"], None, cfg.n_groups, cfg.G, cfg.K)
+    p = O.KeepProbState(cfg.K).update(C, valid)
+    kept, off, nk = O.sample_chunks(p, ro["phase"], None, active, cfg.B, cfg.seed, 0)
+    hidden = make_hidden_torch(cfg, dv)
+    W = make_head_torch(cfg, dv)
+    W_old = perturb_torch(cfg, W, std=0.002)
+    tokens = dev(ro["tokens"].reshape(-1))
+    adv_t = dev(adv.astype(np.float32))
+    kept_t, nk_t = dev(kept), dev(np.array([nk], np.int32))
+    zeros = torch.zeros(hidden.shape[0], device=dv)
+    scale = 1.0 / cfg.T
+    args = (cfg.T, cfg.N, cfg.A)
+
+    # old-policy log-probabilities of the kept rows from a forward-only call (an input of the step)
+    old = pcm.grpo_masked_actor_step(hidden, tokens, zeros, adv_t, kept_t, nk_t, *args, W_old["Wg"], W_old["Wu"],
+                                     W_old["Wd"], W_old["Wo"], want_grads=False, want_dX=False)
+    rows_all = (torch.from_numpy(kept.astype(np.int64))[:, None] * cfg.A + torch.arange(cfg.A)[None, :]).reshape(-1)
+    logp_old = torch.zeros(hidden.shape[0], device=dv)
+    logp_old[rows_all.to(dv)] = old["logp"]
+    # condition against the checker's ratios on the rows that will be compared
+    Wn = {k: v.float().cpu().numpy() for k, v in W.items()}
+    g0 = kept[kept // cfg.N < cfg.G]                              # group 0's kept chunks
+    pick = np.concatenate([g0, kept[len(g0)::97][:6]])            # plus 6 chunks spread over the batch
+    rows_pick = (pick[:, None].astype(np.int64) * cfg.A + np.arange(cfg.A)[None, :]).reshape(-1)
+    hid_rows = hidden[torch.from_numpy(rows_pick).to(dv)].float().cpu().numpy()
+    # a compact stand-in problem holding only the picked chunks, for the checker
+    sub_hidden = hid_rows
+    sub_tokens = ro["tokens"].reshape(-1)[rows_pick]
+    sub_kept = np.arange(len(pick))
+    sub_adv_per_chunk = adv[pick // cfg.N]
+    lp_old_pick = logp_old[torch.from_numpy(rows_pick).to(dv)].cpu().numpy().astype(np.float64)
+    cur = O.actor_step(sub_hidden, sub_tokens, lp_old_pick, sub_adv_per_chunk, sub_kept, 1, cfg.A,
+                       Wn["Wg"], Wn["Wu"], Wn["Wd"], Wn["Wo"], want_grads=False)
+    lp_old_pick = condition_logp_old(lp_old_pick, cur["logp"], np.arange(len(rows_pick)), 0.2, 0.2, 0.08)
+    logp_old[torch.from_numpy(rows_pick).to(dv)] = torch.from_numpy(lp_old_pick.astype(np.float32)).to(dv)
+    lp_old_pick = logp_old[torch.from_numpy(rows_pick).to(dv)].cpu().numpy().astype(np.float64)
+
+    # (a) whole batch
+    full = pcm.grpo_masked_actor_step(hidden, tokens, logp_old, adv_t, kept_t, nk_t, *args, W["Wg"], W["Wu"], W["Wd"],
+                                      W["Wo"], 0.2, 0.2, scale)
+    torch.cuda.synchronize()
+    ref = O.actor_step(sub_hidden, sub_tokens, lp_old_pick, sub_adv_per_chunk, sub_kept, 1, cfg.A,
+                       Wn["Wg"], Wn["Wu"], Wn["Wd"], Wn["Wo"], 0.2, 0.2, scale)
+    pos = {c: j for j, c in enumerate(kept)}
+    sel = np.concatenate([np.arange(pos[c] * cfg.A, (pos[c] + 1) * cfg.A) for c in pick])
+    assert rel(full["logp"].cpu().numpy()[sel], ref["logp"]) <= BF16_TOL
+    assert rel(full["dX"].float().cpu().numpy()[sel], ref["dX"]) <= BF16_TOL
+
+    # (b) additivity over groups, GPU against GPU
+    acc = {k: torch.zeros_like(full[k]) for k in GRADS}
+    loss_sum = 0.0
+    for g in range(cfg.n_groups):
+        kg = kept[(kept // cfg.N) // cfg.G == g]
+        part = pcm.grpo_masked_actor_step(hidden, tokens, logp_old, adv_t, dev(kg), dev(np.array([len(kg)], np.int32)),
+                                          *args, W["Wg"], W["Wu"], W["Wd"], W["Wo"], 0.2, 0.2, scale, want_dX=False)
+        for k in GRADS:
+            acc[k] += part[k]
+        loss_sum += part["loss"].item()
+        if g == 0:
+            first = {k: part[k].float().cpu().numpy() for k in GRADS}
+            first["loss"] = part["loss"].item()
+    for k in GRADS:
+        assert rel(acc[k].cpu().numpy(), full[k].cpu().numpy()) <= 2e-3, k
+    assert abs(loss_sum - full["loss"].item()) <= 1e-4 * max(1.0, abs(loss_sum))
+
+    # (c) group 0 against the full checker
+    n0 = len(g0)
+    ref0 = O.actor_step(sub_hidden[:n0 * cfg.A], sub_tokens[:n0 * cfg.A], lp_old_pick[:n0 * cfg.A],
+                        sub_adv_per_chunk[:n0], np.arange(n0), 1, cfg.A, Wn["Wg"], Wn["Wu"], Wn["Wd"], Wn["Wo"],
+                        0.2, 0.2, scale)
+    for k in GRADS:
+        assert rel(first[k], ref0[k]) <= BF16_TOL, (k, rel(first[k], ref0[k]))
+    assert abs(first["loss"] - ref0["loss"]) <= BF16_TOL * max(1.0, abs(ref0["loss"]))

@@ -1,0 +1,73 @@
+"""The built C-ABI library loads and exports every function that include/pcm.h declares.
+
+No GPU work is issued here: only host-side queries are called.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pcm.h")
+LIB = os.path.join(ROOT, "paper_2605_16154_amd", "libpcm.so")
+
+
+def _declared():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"^PCM_API\s+[\w\s\*]+?\b((?:pcm|grpo)_\w+)\s*\(", text, flags=re.M)))
+
+
+@pytest.fixture(scope="module")
+def cdll():
+    if not os.path.exists(LIB):
+        import __graft_entry__
+        __graft_entry__.build()
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_four_calls():
+    names = _declared()
+    for need in ("pcm_score_phases", "pcm_update_keep_probs", "pcm_sample_chunks", "grpo_masked_actor_step"):
+        assert need in names
+    assert len(names) >= 12
+
+
+def test_every_declared_symbol_is_exported(cdll):
+    for name in _declared():
+        assert hasattr(cdll, name), name
+
+
+def test_host_side_queries(cdll):
+    cdll.pcm_version.restype = ctypes.c_char_p
+    assert b"pcm" in cdll.pcm_version()
+    cdll.pcm_state_bytes.restype = ctypes.c_size_t
+    assert cdll.pcm_state_bytes(5) == 16 + 24 * 5
+    assert cdll.pcm_state_bytes(0) == 0 and cdll.pcm_state_bytes(65) == 0
+    cdll.pcm_score_phases_workspace_bytes.restype = ctypes.c_size_t
+    assert cdll.pcm_score_phases_workspace_bytes(8, 8, 64, 56, 5) >= 8 * 2 * 5 * 56 * 8
+    q = cdll.grpo_masked_actor_step_workspace_bytes
+    q.restype = ctypes.c_size_t
+    assert q(96, 56, 256, 1024, 256, 0, 1) > q(96, 56, 256, 1024, 256, 0, 0) > 0
+    assert q(768, 56, 4096, 11008, 256, 1, 1) > 768 * 56 * 11008 * 2 * 3
+    assert q(768, 56, 4000, 11008, 256, 1, 1) == 0          # bf16 path needs d % 256 == 0
+    cdll.pcm_status_string.restype = ctypes.c_char_p
+    assert cdll.pcm_status_string(-2).startswith(b"workspace")
+
+
+def test_null_and_range_arguments_are_rejected_on_the_host(cdll):
+    # argument validation happens before any GPU call, so these run without a device
+    assert cdll.pcm_state_init(None, 5, None) == -1
+    assert cdll.pcm_score_phases(None, None, None, None, 1, 1, 1, 1, 1, ctypes.c_double(0.0), None, None, None,
+                                 None, None, ctypes.c_size_t(0), None) == -1
+    assert cdll.pcm_update_keep_probs(None, None, None, 5, ctypes.c_double(0.1), 5, None, None) == -1
+    assert cdll.pcm_sample_chunks(None, None, None, None, 1, 1, 1, 1, ctypes.c_uint64(0), ctypes.c_uint64(0),
+                                  None, None, None, None, ctypes.c_size_t(0), None) == -1
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    import paper_2605_16154_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "_LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(b.PcmError):
+        b.lib()
