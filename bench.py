@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Throughput of the PCM hot path on one MI355X: kept action tokens per second.
+
+One step = one pass of the whole path over one synthetic rollout batch that is already resident
+in HBM: pcm_score_phases -> pcm_update_keep_probs -> pcm_sample_chunks -> grpo_masked_actor_step
+(gather, head forward, fused clipped-GRPO loss, full backward), all through the C-ABI library.
+Prints one JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+GEMM_STAGES = ("gemm_gate_up", "gemm_down", "gemm_logits_loss", "gemm_dWo", "gemm_dy", "gemm_dWd", "gemm_da",
+               "gemm_dWg_dWu", "gemm_dX")
+
+
+def gemm_flops_per_launch(M, d, ff, V):
+    """Algorithmic flops of one launch of each head GEMM over M token rows (2 flops per multiply-add)."""
+    return {"gemm_gate_up": 2.0 * M * d * 2 * ff, "gemm_down": 2.0 * M * ff * d, "gemm_logits_loss": 2.0 * M * d * V,
+            "gemm_dWo": 2.0 * M * d * V, "gemm_dy": 2.0 * M * V * d, "gemm_dWd": 2.0 * M * ff * d,
+            "gemm_da": 2.0 * M * d * ff, "gemm_dWg_dWu": 2.0 * M * d * ff, "gemm_dX": 2.0 * M * 2 * ff * d}
+
+
+class Workload:
+    """Device-resident inputs of `n_batches` consecutive training steps plus the head."""
+
+    def __init__(self, cfg, device, n_batches):
+        import torch
+        from workloads import make_head_torch, make_hidden_torch, make_rollouts, perturb_torch
+        import paper_2605_16154_amd as pcm
+        self.cfg, self.dev, self.pcm, self.torch = cfg, device, pcm, torch
+        t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(device)
+        self.host = [make_rollouts(cfg, s) for s in range(n_batches)]
+        self.batches = [{k: t(ro[k]) for k in ("actions", "phase", "reward", "n_chunks")} for ro in self.host]
+        for b, ro in zip(self.batches, self.host):
+            b["tokens"] = t(ro["tokens"].reshape(-1))
+        self.hidden = make_hidden_torch(cfg, device)
+        self.W = make_head_torch(cfg, device)
+        W_old = perturb_torch(cfg, self.W)
+        # old-policy log-probabilities of every action token: forward-only pass over all chunks
+        all_idx = torch.arange(cfg.T * cfg.N, dtype=torch.int32, device=device)
+        n_all = torch.tensor([cfg.T * cfg.N], dtype=torch.int32, device=device)
+        zeros = torch.zeros(cfg.T * cfg.N * cfg.A, dtype=torch.float32, device=device)
+        adv0 = torch.zeros(cfg.T, dtype=torch.float32, device=device)
+        for b in self.batches:
+            out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], zeros, adv0, all_idx, n_all, cfg.T, cfg.N,
+                                             cfg.A, W_old["Wg"], W_old["Wu"], W_old["Wd"], W_old["Wo"],
+                                             want_grads=False, want_dX=False)
+            b["logp_old"] = out["logp"].clone()
+        del W_old, zeros
+        self.state = pcm.pcm_state_init(cfg.K, device)
+        self.sel_out = None
+        self.samp_out = None
+        self.act_out = {}
+        torch.cuda.synchronize()
+
+    def step(self, t, B=None):
+        cfg, pcm, b = self.cfg, self.pcm, self.batches[t % len(self.batches)]
+        B = cfg.B if B is None else B
+        self.sel_out = pcm.pcm_score_phases(b["actions"], b["phase"], b["reward"], b["n_chunks"], cfg.n_groups,
+                                            cfg.G, cfg.K, 1e-6, out=self.sel_out)
+        Cc, valid, adv, active = self.sel_out
+        p = pcm.pcm_update_keep_probs(self.state, Cc, valid, 0.1, 5)
+        if self.samp_out is not None and self.samp_out[0].shape[0] != cfg.T * min(B, cfg.N):
+            self.samp_out, self.act_out = None, {}
+        self.samp_out = pcm.pcm_sample_chunks(p, b["phase"], b["n_chunks"], active, B, cfg.seed, t, out=self.samp_out)
+        kept, off, nk = self.samp_out
+        self.act_out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], b["logp_old"], adv, kept, nk, cfg.T, cfg.N,
+                                                  cfg.A, self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"],
+                                                  0.2, 0.2, 1.0 / cfg.T, out=self.act_out)
+        return nk
+
+
+def timed_steps(wl, steps, warmup, B=None, profile=False):
+    torch = wl.torch
+    for t in range(warmup):
+        wl.step(t, B)
+    torch.cuda.synchronize()
+    if profile:
+        wl.pcm.pcm_profile_enable(True)
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        nk = wl.step(t, B)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = None
+    if profile:
+        stages = wl.pcm.pcm_profile_collect()
+        wl.pcm.pcm_profile_enable(False)
+    return dt, int(nk.item()), stages
+
+
+def cpu_baseline(wl, kept_host, sample_chunks):
+    """The CPU checker, as it stands, on a bounded sample of the same step."""
+    from oracle import pcm_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    cfg, ro = wl.cfg, wl.host[0]
+    t0 = time.perf_counter()
+    adv, active = O.advantages(ro["reward"], cfg.G)
+    C, valid = O.phase_scores(ro["actions"], ro["phase"], ro["reward"], ro["n_chunks"], cfg.n_groups, cfg.G, cfg.K)
+    p = O.KeepProbState(cfg.K).update(C, valid)
+    kept, off, nk = O.sample_chunks(p, ro["phase"], ro["n_chunks"], active, cfg.B, cfg.seed, 0)
+    t_sel = time.perf_counter() - t0
+    assert np.array_equal(kept, kept_host), "GPU and CPU selection disagree"
+    pick = kept[:sample_chunks]
+    rows = (pick[:, None].astype(np.int64) * cfg.A + np.arange(cfg.A)[None, :]).reshape(-1)
+    torch = wl.torch
+    ridx = torch.from_numpy(rows).to(wl.dev)
+    hid = wl.hidden[ridx].float().cpu().numpy()
+    tok = ro["tokens"].reshape(-1)[rows]
+    lp_old = wl.batches[0]["logp_old"][ridx].cpu().numpy()
+    W = {k: v.float().cpu().numpy() for k, v in wl.W.items()}
+    t0 = time.perf_counter()
+    O.actor_step(hid, tok, lp_old, adv[pick // cfg.N], np.arange(len(pick)), 1, cfg.A, W["Wg"], W["Wu"], W["Wd"], W["Wo"],
+                 0.2, 0.2, 1.0 / cfg.T)
+    t_act = time.perf_counter() - t0
+    rows_step = nk * cfg.A
+    est_step = t_sel + t_act * rows_step / len(rows)
+    return {"value": rows_step / est_step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"selection stages in full ({t_sel:.2f} s) + fp64 actor step on the first {len(pick)} kept chunks "
+                      f"({len(rows)} of {rows_step} rows, {t_act:.2f} s), scaled linearly in rows"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unmasked", action="store_true")
+    ap.add_argument("--cpu-sample-chunks", type=int, default=24)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures the single-GPU hot path only; run it with --gpus 1 "
+              "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from workloads import CONFIGS
+    import paper_2605_16154_amd as pcm
+    pcm.lib()                                   # raises if the HIP library has not been built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.config]
+
+    wl = Workload(cfg, dev, cfg.n_steps)
+    # step 0 from a fresh state once, to hand its kept set to the CPU baseline for cross-checking
+    nk0 = wl.step(0)
+    torch.cuda.synchronize()
+    kept_host = wl.samp_out[0].cpu().numpy()[:int(nk0.item())]
+    wl.state = pcm.pcm_state_init(cfg.K, dev)
+    dt, n_kept, stages = timed_steps(wl, args.steps, args.warmup, profile=True)
+    rows = n_kept * cfg.A
+    ms_step = dt / args.steps * 1e3
+    value = rows * args.steps / dt
+
+    flops = gemm_flops_per_launch(rows, cfg.d, cfg.ff, cfg.V)
+    per_stage = {}
+    for name, (ms, launches) in stages.items():
+        if launches == 0:
+            continue
+        per_stage[name] = {"ms_per_launch": ms / launches, "launches_per_step": launches / args.steps}
+        if name in flops:
+            per_stage[name]["tflops"] = flops[name] / (ms / launches * 1e-3) / 1e12
+    gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / args.steps
+    total_flops_step = 3.0 * (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * rows
+    dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
+    dom_ms = stages[dominant][0] / stages[dominant][1]
+    achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": f"gemm_bf16_nt ({dominant})", "achieved": achieved,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None,
+                "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
+                "all_head_gemms": {"tflops": total_flops_step / (gemm_ms_step * 1e-3) / 1e12,
+                                   "frac": total_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                   "ms_per_step": gemm_ms_step}}
+
+    result = {"metric": "kept_action_tokens_per_sec_masked_grpo_actor_step", "value": value, "unit": "tokens/s",
+              "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
+              "data": "synthetic",
+              "config": {"workload": f"{cfg.name}: {cfg.n_groups} groups x {cfg.G} rollouts, {cfg.N} chunks x {cfg.A} tokens, "
+                                     f"K={cfg.K}, B={cfg.B}, head {cfg.d}->{cfg.ff}->{cfg.d}->{cfg.V}",
+                         "kept_chunks": n_kept, "kept_rows": rows, "global_batch": cfg.T, "selection_included": True},
+              "roofline": roofline, "stages": per_stage}
+
+    if not args.no_unmasked and cfg.B < cfg.N:
+        wl.state = pcm.pcm_state_init(cfg.K, dev)
+        k_un = max(2, min(4, args.steps))
+        dt_un, n_un, _ = timed_steps(wl, k_un, 1, B=cfg.N)
+        ms_un = dt_un / k_un * 1e3
+        result["unmasked"] = {"ms_per_step": ms_un, "kept_rows": n_un * cfg.A, "tokens_per_s": n_un * cfg.A * k_un / dt_un,
+                              "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
+                              "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, kept_host, args.cpu_sample_chunks)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

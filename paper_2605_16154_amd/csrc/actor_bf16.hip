@@ -50,7 +50,9 @@ __global__ __launch_bounds__(256) void transpose_bf16(const uint16_t* __restrict
     }
 }
 
-void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t ld_dst, int mode = kPackNone) {
+void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t ld_dst, int mode = kPackNone,
+               int stage = ST_TRANSPOSE) {
+    StageTimer t(stage, s);
     dim3 grid(C / 64, R / 64);
     transpose_bf16<<<grid, 256, 0, s>>>(reinterpret_cast<const uint16_t*>(src), C,
                                         reinterpret_cast<uint16_t*>(dst), ld_dst, mode);
@@ -62,6 +64,7 @@ __global__ void fill_zero_f32(float* p, size_t n) {
 }
 
 void zero(hipStream_t s, float* p, size_t n) {
+    StageTimer t(ST_ZERO_FILL, s);
     size_t blocks = (n + 1023) / 1024;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
@@ -159,13 +162,10 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     const bf16* Wd = static_cast<const bf16*>(io.Wd);
     const bf16* Wo = static_cast<const bf16*>(io.Wo);
 
-    {
-        StageTimer t(ST_WEIGHT_LAYOUT, s);
-        transpose(s, Wg, d, ff, w.WguT, d, kPackGate);   // [d, ff] -> packed rows of [2 ff, d]
-        transpose(s, Wu, d, ff, w.WguT, d, kPackUp);
-        transpose(s, Wd, ff, d, w.WdT, ff);              // [ff, d] -> [d, ff]
-        transpose(s, Wo, d, V, w.WoT, d);                // [d, V]  -> [V, d]
-    }
+    transpose(s, Wg, d, ff, w.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);   // [d, ff] -> packed rows of [2 ff, d]
+    transpose(s, Wu, d, ff, w.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
+    transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
+    transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
     int rc = launch_gather(sh, io, 2, w.X, Mp, w.meta, s);
     if (rc != PCM_OK) return rc;
     {
@@ -191,21 +191,21 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
     }
     if (grads) {
-        StageTimer t(ST_GEMM_DWO, s);
         transpose(s, w.y, Mp, d, w.yT, Mp);
         transpose(s, w.dz, Mp, V, w.dzT, Mp);
         GemmProblem p = problem(w.yT, Mp, w.dzT, Mp, d, V, Mp);                                   // dWo = y^T dz
         p.splits = pick_splits((d / kTileM) * (V / kTileN), Mp / kTileK);
         if (p.splits > 1) zero(s, io.dWo, (size_t)d * V);
+        StageTimer t(ST_GEMM_DWO, s);
         launch_gemm(p, EpiAccumulateF32{io.dWo, V, p.splits > 1}, s);
     }
     if (grads) {
-        StageTimer t(ST_GEMM_DWD, s);
         transpose(s, w.a, Mp, ff, w.aT, Mp);
         transpose(s, w.dy, Mp, d, w.dyT, Mp);
         GemmProblem p = problem(w.aT, Mp, w.dyT, Mp, ff, d, Mp);                                  // dWd = a^T dy
         p.splits = pick_splits((ff / kTileM) * (d / kTileN), Mp / kTileK);
         if (p.splits > 1) zero(s, io.dWd, (size_t)ff * d);
+        StageTimer t(ST_GEMM_DWD, s);
         launch_gemm(p, EpiAccumulateF32{io.dWd, d, p.splits > 1}, s);
     }
     {
@@ -213,7 +213,6 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
     }
     if (grads) {
-        StageTimer t(ST_GEMM_DWG_DWU, s);
         transpose(s, w.X, Mp, d, w.XT, Mp);
         transpose(s, w.u, Mp, ff, w.duT, Mp);
         transpose(s, w.v, Mp, ff, w.dvT, Mp);
@@ -223,8 +222,12 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
             zero(s, io.dWg, (size_t)d * ff);
             zero(s, io.dWu, (size_t)d * ff);
         }
-        launch_gemm(p, EpiAccumulateF32{io.dWg, ff, p.splits > 1}, s);
+        {
+            StageTimer t(ST_GEMM_DWG_DWU, s);
+            launch_gemm(p, EpiAccumulateF32{io.dWg, ff, p.splits > 1}, s);
+        }
         p.B = w.dvT;                                                                              // dWu = X^T dv
+        StageTimer t(ST_GEMM_DWG_DWU, s);
         launch_gemm(p, EpiAccumulateF32{io.dWu, ff, p.splits > 1}, s);
     }
     if (io.dX) {
