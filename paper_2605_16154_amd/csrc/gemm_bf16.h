@@ -7,9 +7,10 @@
 //
 // Tiling: 256 x 256 x 64 per workgroup of 4 wavefronts (2 x 2), each wavefront owning 128 x 128 =
 // 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 with fp32 accumulators (256 accumulator registers per
-// lane, one wavefront per SIMD).  Operand tiles are double-buffered in LDS (2 x 64 KB); rows are
-// 128 B and the eight 16-byte pieces of a row are XOR-swizzled with the row index so that both
-// the 16-byte tile writes and the 16-byte fragment reads spread over all banks.
+// lane, one wavefront per SIMD).  Operand tiles are double-buffered in LDS (2 x 64 KB) and filled
+// by direct global-to-LDS loads (no staging registers); rows are 128 B and the eight 16-byte
+// pieces of a row are XOR-swizzled with the row index so that the 16-byte fragment reads spread
+// over all banks.
 //
 // The MFMA is issued with the B fragment as the first operand, so the accumulator tile is the
 // transpose of the usual one: a lane holds, for one output row m, runs of 4 consecutive n.
@@ -72,9 +73,17 @@ __device__ inline void tile_of_workgroup(int wg, int n_wg, int tiles_m, int tile
     tn = in_band / rows;
 }
 
+#define PCM_AS_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define PCM_AS_GLOBAL(p) ((const __attribute__((address_space(1))) void*)(p))
+
 template <class Epilogue>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, Epilogue epi) {
-    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][kTileM * kTileK];   // [stage][A|B]
+    // two stages of (A tile, B tile); separate objects so that loads into one stage are known not
+    // to alias fragment reads from the other
+    __shared__ __attribute__((aligned(1024))) __bf16 sA0[kTileM * kTileK];
+    __shared__ __attribute__((aligned(1024))) __bf16 sB0[kTileN * kTileK];
+    __shared__ __attribute__((aligned(1024))) __bf16 sA1[kTileM * kTileK];
+    __shared__ __attribute__((aligned(1024))) __bf16 sB1[kTileN * kTileK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -91,10 +100,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     const int step_begin = split * per_split;
     const int step_end = min(steps_all, step_begin + per_split);
 
-    // global -> register staging: thread owns 16-byte piece (tid & 7) of rows (tid >> 3) + 32 * r
-    const int ld_row = tid >> 3, ld_piece = tid & 7;
-    uint4 stage_a[8], stage_b[8];
-    auto load_tiles = [&](int step) {
+    // Global -> LDS without passing through registers: one wave-wide load fills 1 KB of LDS (8 tile
+    // rows), lane l landing in 16-byte slot l.  The swizzle is therefore applied on the global
+    // side: the lane that lands in slot (row, piece') fetches piece' ^ swizzle(row) of that row.
+    // Wave w fills rows [64 w, 64 w + 64) of both tiles with 8 loads each.
+    const int ld_row = wave * 64 + (lane >> 3);                 // + 8 * r for load r
+    const int ld_piece = swizzle_piece(ld_row, lane & 7);       // (row + 8 r) has the same low 3 bits
+    auto issue_loads = [&](__bf16* sa, __bf16* sb, int step) {
         const bf16 *a, *b;
         int64_t la, lb;
         int k0;
@@ -104,17 +116,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
         const bf16* bp = b + (int64_t)(n0 + ld_row) * lb + k0 + ld_piece * 8;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            stage_a[r] = *reinterpret_cast<const uint4*>(ap + (int64_t)r * 32 * la);
-            stage_b[r] = *reinterpret_cast<const uint4*>(bp + (int64_t)r * 32 * lb);
-        }
-    };
-    auto store_tiles = [&](int buf) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int row = ld_row + 32 * r;
-            const int off = row * kTileK + swizzle_piece(row, ld_piece) * 8;
-            *reinterpret_cast<uint4*>(&lds[buf][0][off]) = stage_a[r];
-            *reinterpret_cast<uint4*>(&lds[buf][1][off]) = stage_b[r];
+            __builtin_amdgcn_global_load_lds(PCM_AS_GLOBAL(ap + (int64_t)r * 8 * la),
+                                             PCM_AS_LDS(sa + (wave * 64 + r * 8) * kTileK), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(PCM_AS_GLOBAL(bp + (int64_t)r * 8 * lb),
+                                             PCM_AS_LDS(sb + (wave * 64 + r * 8) * kTileK), 16, 0, 0);
         }
     };
 
@@ -126,44 +131,49 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    if (step_begin < step_end) {
-        load_tiles(step_begin);
-        store_tiles(0);
-        if (step_begin + 1 < step_end) load_tiles(step_begin + 1);
-        __syncthreads();
-        for (int step = step_begin; step < step_end; ++step) {
-            const int buf = (step - step_begin) & 1;
-            const __bf16* sa = &lds[buf][0][0];
-            const __bf16* sb = &lds[buf][1][0];
-            // the tile fetched during the previous iteration goes to the other buffer
-            if (step + 1 < step_end) store_tiles(buf ^ 1);
-            if (step + 2 < step_end) load_tiles(step + 2);
+    auto compute = [&](const __bf16* sa, const __bf16* sb) {
 #pragma unroll
-            for (int ks = 0; ks < kTileK / 16; ++ks) {
-                bf16x8 fa[4], fb[4];
-                const int piece = ks * 2 + (lane >> 5);
+        for (int ks = 0; ks < kTileK / 16; ++ks) {
+            bf16x8 fa[4], fb[4];
+            const int piece = ks * 2 + (lane >> 5);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int row = wm * 128 + i * 32 + (lane & 31);
-                    fa[i] = *reinterpret_cast<const bf16x8*>(sa + row * kTileK + swizzle_piece(row, piece) * 8);
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int row = wn * 128 + j * 32 + (lane & 31);
-                    fb[j] = *reinterpret_cast<const bf16x8*>(sb + row * kTileK + swizzle_piece(row, piece) * 8);
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+            for (int i = 0; i < 4; ++i) {
+                const int row = wm * 128 + i * 32 + (lane & 31);
+                fa[i] = *reinterpret_cast<const bf16x8*>(sa + row * kTileK + swizzle_piece(row, piece) * 8);
             }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = wn * 128 + j * 32 + (lane & 31);
+                fb[j] = *reinterpret_cast<const bf16x8*>(sb + row * kTileK + swizzle_piece(row, piece) * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    const int n_steps = step_end - step_begin;
+    if (n_steps > 0) {
+        issue_loads(sA0, sB0, step_begin);
+        __syncthreads();
+        // two steps per trip so that each stage is a fixed LDS object; a trailing odd step follows
+        for (int pair = 0; pair < n_steps / 2; ++pair) {
+            const int step = step_begin + 2 * pair;
+            issue_loads(sA1, sB1, step + 1);
+            compute(sA0, sB0);
+            __syncthreads();
+            if (step + 2 < step_end) issue_loads(sA0, sB0, step + 2);
+            compute(sA1, sB1);
             __syncthreads();
         }
+        if (n_steps & 1) compute(sA0, sB0);
+        __syncthreads();
     }
 
     TileCoord tc{m0, n0, wm, wn, lane};
-    epi(tc, acc, reinterpret_cast<float*>(&lds[0][0][0]));
+    epi(tc, acc, reinterpret_cast<float*>(sA0));
 }
 
 // ---- epilogues -------------------------------------------------------------------------------
