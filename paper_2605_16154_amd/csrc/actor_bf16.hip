@@ -117,24 +117,16 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     return w;
 }
 
-// Reduction split for an output of `tiles` tiles and `steps` 64-wide reduction steps: the
-// smallest split whose workgroup count fills whole rounds of the chip's 256 CUs to >= 97 %.
+// Reduction split for an output of `tiles` tiles and `steps` 64-wide reduction steps.  An output
+// that already covers the 256 CUs is not split (partial sums would have to be combined with
+// atomics, which costs more than the idle tail of the last round); a small output is split so that
+// tiles * splits fills the chip, keeping at least 8 steps per workgroup.
 int pick_splits(int tiles, int steps) {
-    int max_s = steps / 8;
-    if (max_s < 1) max_s = 1;
-    if (max_s > 64) max_s = 64;
-    int best = 1;
-    double best_eff = 0.0;
-    for (int s = 1; s <= max_s; ++s) {
-        const double rounds = (double)tiles * s / 256.0;
-        const double eff = rounds / (double)(int64_t)(rounds + 0.999999);
-        if (eff > best_eff + 1e-9) {
-            best_eff = eff;
-            best = s;
-        }
-        if (eff >= 0.97) return s;
-    }
-    return best;
+    if (tiles >= 256) return 1;
+    int s = 256 / tiles;
+    const int max_s = steps / 8 > 0 ? steps / 8 : 1;
+    if (s > max_s) s = max_s;
+    return s < 1 ? 1 : s;
 }
 
 GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K) {

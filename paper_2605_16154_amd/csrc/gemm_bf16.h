@@ -17,6 +17,8 @@
 // Epilogues therefore see 4-wide row-contiguous vectors (8-byte bf16 stores).
 #pragma once
 
+#include <type_traits>
+
 #include "actor.h"
 
 namespace pcm {
@@ -29,6 +31,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
 constexpr int kGemmThreads = 256;
 constexpr int kNumXcd = 8;
+constexpr int kTouchAhead = 3;   // L2-warming distance in 64-wide steps
 
 struct GemmProblem {
     const bf16* A;    // [M, K1] row-major, leading dimension lda
@@ -55,7 +58,16 @@ __device__ inline bf16x4 to_bf16x4(float a, float b, float c, float d) {
     return r;
 }
 
-__device__ inline int swizzle_piece(int row, int piece) { return piece ^ (row & 7); }
+#ifndef PCM_SWZ
+#define PCM_SWZ 0
+#endif
+__device__ inline int swizzle_piece(int row, int piece) {
+#if PCM_SWZ == 0
+    return piece ^ (row & 7);
+#else
+    return piece ^ ((row >> 1) & 7);
+#endif
+}
 
 // Workgroup id -> (tile_m, tile_n).  Consecutive hardware workgroup ids go to different XCDs, each
 // with its own L2, so ids are first regrouped so that one XCD works on a contiguous range of
@@ -76,16 +88,40 @@ __device__ inline void tile_of_workgroup(int wg, int n_wg, int tiles_m, int tile
 #define PCM_AS_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 #define PCM_AS_GLOBAL(p) ((const __attribute__((address_space(1))) void*)(p))
 
+// One wave-wide 16-byte-per-lane load from global memory straight into LDS: lane l's 16 bytes land
+// at lds_addr + 16 l.  Written as inline assembly so that the compiler does not serialise the
+// fragment reads of one stage behind loads into the other; completion is awaited explicitly
+// (wait_direct_loads) before the barrier that publishes the stage.
+__device__ inline void direct_load_16B(const char* base, uint32_t lane_offset, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_offset), "s"(base)
+                 : "memory");
+}
+// 4 bytes per lane, landing at lds_addr + 4 l: used only to pull the touched cache lines into L2
+// ahead of the wide loads (the data is never read).
+__device__ inline void direct_load_4B(const char* base, uint32_t lane_offset, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_offset), "s"(base)
+                 : "memory");
+}
+// Direct loads retire in issue order, so waiting until at most `newest` remain outstanding
+// guarantees that all older ones have landed.
+template <int kNewest>
+__device__ inline void wait_direct_loads() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kNewest) : "memory");
+}
+
 template <class Epilogue>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, Epilogue epi) {
-    // two stages of (A tile, B tile); separate objects so that loads into one stage are known not
-    // to alias fragment reads from the other
-    __shared__ __attribute__((aligned(1024))) __bf16 sA0[kTileM * kTileK];
-    __shared__ __attribute__((aligned(1024))) __bf16 sB0[kTileN * kTileK];
-    __shared__ __attribute__((aligned(1024))) __bf16 sA1[kTileM * kTileK];
-    __shared__ __attribute__((aligned(1024))) __bf16 sB1[kTileN * kTileK];
+    constexpr int kTileElems = kTileM * kTileK;                  // per operand per stage
+    constexpr uint32_t kTileBytes = kTileElems * 2, kStageBytes = 2 * kTileBytes;
+    __shared__ __attribute__((aligned(1024))) __bf16 smem[2 * 2 * kTileElems];   // [stage][A|B][row][64]
+    __shared__ uint32_t touch_sink[kGemmThreads * 2];   // landing area of the L2-warming loads, never read
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int wm = wave >> 1, wn = wave & 1;
     const int tiles_m = p.M / kTileM, tiles_n = p.N / kTileN;
     const int n_tiles = tiles_m * tiles_n;
@@ -100,26 +136,52 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     const int step_begin = split * per_split;
     const int step_end = min(steps_all, step_begin + per_split);
 
-    // Global -> LDS without passing through registers: one wave-wide load fills 1 KB of LDS (8 tile
-    // rows), lane l landing in 16-byte slot l.  The swizzle is therefore applied on the global
-    // side: the lane that lands in slot (row, piece') fetches piece' ^ swizzle(row) of that row.
-    // Wave w fills rows [64 w, 64 w + 64) of both tiles with 8 loads each.
-    const int ld_row = wave * 64 + (lane >> 3);                 // + 8 * r for load r
-    const int ld_piece = swizzle_piece(ld_row, lane & 7);       // (row + 8 r) has the same low 3 bits
-    auto issue_loads = [&](__bf16* sa, __bf16* sb, int step) {
-        const bf16 *a, *b;
-        int64_t la, lb;
-        int k0;
-        if (step < steps1) { a = p.A; b = p.B; la = p.lda; lb = p.ldb; k0 = step * kTileK; }
-        else { a = p.A2; b = p.B2; la = p.lda2; lb = p.ldb2; k0 = (step - steps1) * kTileK; }
-        const bf16* ap = a + (int64_t)(m0 + ld_row) * la + k0 + ld_piece * 8;
-        const bf16* bp = b + (int64_t)(n0 + ld_row) * lb + k0 + ld_piece * 8;
+    // Global -> LDS: one wave-wide load fills 1 KB of LDS (8 tile rows), lane l landing in 16-byte
+    // slot l.  The swizzle is therefore applied on the global side: the lane that lands in slot
+    // (row, piece') fetches piece' ^ swizzle(row) of that row.  Wave w fills rows [64 w, 64 w + 64)
+    // of both tiles with 8 loads each; addresses are a wave-uniform base (tile origin + k offset)
+    // plus a 32-bit per-lane byte offset.
+    const uint32_t lds_base = (uint32_t)(uintptr_t)PCM_AS_LDS(smem);
+    const uint32_t ld_row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);   // + 8 r for load r
+    const uint32_t ld_piece = (uint32_t)swizzle_piece(lane >> 3, lane & 7);  // rows + 8 r share low bits
+    struct LoadCtx {
+        const char *abase, *bbase;     // wave-uniform
+        uint32_t aoff, boff, la, lb;   // per-lane byte offsets of load 0; leading dimensions
+        uint32_t dst;                  // LDS byte address of this wave's first A row in the stage
+    };
+    auto load_ctx = [&](uint32_t stage, int step) {
+        LoadCtx c;
+        const bool seg1 = step < steps1;
+        const bf16* a = seg1 ? p.A : p.A2;
+        const bf16* b = seg1 ? p.B : p.B2;
+        c.la = (uint32_t)(seg1 ? p.lda : p.lda2);
+        c.lb = (uint32_t)(seg1 ? p.ldb : p.ldb2);
+        const int k0 = (seg1 ? step : step - steps1) * kTileK;
+        c.abase = reinterpret_cast<const char*>(a + (int64_t)m0 * c.la + k0);
+        c.bbase = reinterpret_cast<const char*>(b + (int64_t)n0 * c.lb + k0);
+        c.aoff = (ld_row * c.la + ld_piece * 8u) * 2u;
+        c.boff = (ld_row * c.lb + ld_piece * 8u) * 2u;
+        c.dst = lds_base + stage * kStageBytes + (uint32_t)wave * 64u * (kTileK * 2u);
+        return c;
+    };
+    // L2 warming: thread t touches the cache line of row t of both operand tiles for `step`
+    const uint32_t sink = (uint32_t)(uintptr_t)PCM_AS_LDS(touch_sink) + (uint32_t)wave * 512u;
+    auto touch_lines = [&](int step) {
+        const bool seg1 = step < steps1;
+        const bf16* a = seg1 ? p.A : p.A2;
+        const bf16* b = seg1 ? p.B : p.B2;
+        const uint32_t la = (uint32_t)(seg1 ? p.lda : p.lda2), lb = (uint32_t)(seg1 ? p.ldb : p.ldb2);
+        const int k0 = (seg1 ? step : step - steps1) * kTileK;
+        const uint32_t row = (uint32_t)wave * 64u + (uint32_t)lane;
+        direct_load_4B(reinterpret_cast<const char*>(a + (int64_t)m0 * la + k0), row * la * 2u, sink);
+        direct_load_4B(reinterpret_cast<const char*>(b + (int64_t)n0 * lb + k0), row * lb * 2u, sink + 256u);
+    };
+    // loads r = r0 .. r0 + n - 1 of both operands (8 rows of A and 8 rows of B each)
+    auto issue_loads = [&](const LoadCtx& c, uint32_t r0, uint32_t n) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            __builtin_amdgcn_global_load_lds(PCM_AS_GLOBAL(ap + (int64_t)r * 8 * la),
-                                             PCM_AS_LDS(sa + (wave * 64 + r * 8) * kTileK), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(PCM_AS_GLOBAL(bp + (int64_t)r * 8 * lb),
-                                             PCM_AS_LDS(sb + (wave * 64 + r * 8) * kTileK), 16, 0, 0);
+        for (uint32_t r = r0; r < r0 + n; ++r) {
+            direct_load_16B(c.abase, c.aoff + r * 16u * c.la, c.dst + r * 1024u);
+            direct_load_16B(c.bbase, c.boff + r * 16u * c.lb, c.dst + kTileBytes + r * 1024u);
         }
     };
 
@@ -131,49 +193,86 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    auto compute = [&](const __bf16* sa, const __bf16* sb) {
+    // Fragment registers are double-buffered: while the 16 MFMAs of one 16-wide k-slice run, the
+    // 8 fragment reads of the next slice are in flight.  Fragment pair i = rows 32 i .. 32 i + 31 of
+    // the wavefront's A and B sub-tiles.
+    bf16x8 fa[2][4], fb[2][4];
+    const int frow_a = wm * 128 + (lane & 31), frow_b = wn * 128 + (lane & 31);
+    auto read_frag_pair = [&](int set, uint32_t stage, int ks, int i) {
+        const __bf16* sa = smem + stage * (2 * kTileElems);
+        const __bf16* sb = sa + kTileElems;
+        const int piece = ks * 2 + (lane >> 5);
+        const int ra = frow_a + i * 32, rb = frow_b + i * 32;
+        fa[set][i] = *reinterpret_cast<const bf16x8*>(sa + ra * kTileK + swizzle_piece(ra, piece) * 8);
+        fb[set][i] = *reinterpret_cast<const bf16x8*>(sb + rb * kTileK + swizzle_piece(rb, piece) * 8);
+    };
+    auto read_frags = [&](int set, uint32_t stage, int ks) {
 #pragma unroll
-        for (int ks = 0; ks < kTileK / 16; ++ks) {
-            bf16x8 fa[4], fb[4];
-            const int piece = ks * 2 + (lane >> 5);
+        for (int i = 0; i < 4; ++i) read_frag_pair(set, stage, ks, i);
+    };
+    auto mfma_row = [&](int set, int i) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = wm * 128 + i * 32 + (lane & 31);
-                fa[i] = *reinterpret_cast<const bf16x8*>(sa + row * kTileK + swizzle_piece(row, piece) * 8);
-            }
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    };
+    auto mfma_slice = [&](int set) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int row = wn * 128 + j * 32 + (lane & 31);
-                fb[j] = *reinterpret_cast<const bf16x8*>(sb + row * kTileK + swizzle_piece(row, piece) * 8);
-            }
+        for (int i = 0; i < 4; ++i) mfma_row(set, i);
+    };
+    // scheduling hint: "one LDS read, then two MFMAs", eight times
+    auto interleave_reads = [&]() {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        for (int g = 0; g < 8; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
     };
 
-    const int n_steps = step_end - step_begin;
-    if (n_steps > 0) {
-        issue_loads(sA0, sB0, step_begin);
+    if (step_begin < step_end) {
+        issue_loads(load_ctx(0, step_begin), 0, 8);
+        wait_direct_loads<0>();
         __syncthreads();
-        // two steps per trip so that each stage is a fixed LDS object; a trailing odd step follows
-        for (int pair = 0; pair < n_steps / 2; ++pair) {
-            const int step = step_begin + 2 * pair;
-            issue_loads(sA1, sB1, step + 1);
-            compute(sA0, sB0);
+        issue_loads(load_ctx(1, min(step_begin + 1, step_end - 1)), 0, 8);
+        touch_lines(min(step_begin + 2, step_end - 1));
+        read_frags(0, 0, 0);
+        // One 64-wide step per trip on stage `cur`; the other stage holds the following step (loaded
+        // one step earlier).  Fragment set 0 holds slice 0 of `cur` on entry and slice 0 of the next
+        // step on exit.  The single barrier sits before the last slice: by then every wavefront has
+        // issued all its reads of `cur`, so `cur` can be refilled for the step after next; the refill
+        // loads are issued in four groups between the MFMA rows of the last slice so that the matrix
+        // pipe keeps running while the texture path takes them.  The body is branch-free: near the end
+        // it reloads the last tile and reads fragments nobody uses.
+        uint32_t cur = 0;
+        for (int step = step_begin; step < step_end; ++step) {
+            read_frags(1, cur, 1);
+            mfma_slice(0);
+            interleave_reads();
+            touch_lines(min(step + kTouchAhead, step_end - 1));   // issued after the previous refill
+            read_frags(0, cur, 2);
+            mfma_slice(1);
+            interleave_reads();
+            read_frags(1, cur, 3);
+            mfma_slice(0);
+            interleave_reads();
+            wait_direct_loads<2>();                               // all but the two line touches
             __syncthreads();
-            if (step + 2 < step_end) issue_loads(sA0, sB0, step + 2);
-            compute(sA1, sB1);
-            __syncthreads();
+            const LoadCtx c = load_ctx(cur, min(step + 2, step_end - 1));
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                issue_loads(c, 2 * g, 2);
+                read_frag_pair(0, cur ^ 1u, 0, g);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_row(1, g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            cur ^= 1u;
         }
-        if (n_steps & 1) compute(sA0, sB0);
+        wait_direct_loads<0>();
         __syncthreads();
     }
 
     TileCoord tc{m0, n0, wm, wn, lane};
-    epi(tc, acc, reinterpret_cast<float*>(sA0));
+    epi(tc, acc, reinterpret_cast<float*>(smem));
 }
 
 // ---- epilogues -------------------------------------------------------------------------------
