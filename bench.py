@@ -48,16 +48,23 @@ class Workload:
         self.hidden = make_hidden_torch(cfg, device)
         self.W = make_head_torch(cfg, device)
         W_old = perturb_torch(cfg, self.W)
-        # old-policy log-probabilities of every action token: forward-only pass over all chunks
-        all_idx = torch.arange(cfg.T * cfg.N, dtype=torch.int32, device=device)
-        n_all = torch.tensor([cfg.T * cfg.N], dtype=torch.int32, device=device)
-        zeros = torch.zeros(cfg.T * cfg.N * cfg.A, dtype=torch.float32, device=device)
+        # old-policy log-probabilities of every action token: forward-only passes with the old weights,
+        # T*B chunks at a time (the same launch shape as the timed step)
+        per_call = cfg.T * min(cfg.B, cfg.N)
+        n_all = cfg.T * cfg.N
+        zeros = torch.zeros(n_all * cfg.A, dtype=torch.float32, device=device)
         adv0 = torch.zeros(cfg.T, dtype=torch.float32, device=device)
         for b in self.batches:
-            out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], zeros, adv0, all_idx, n_all, cfg.T, cfg.N,
-                                             cfg.A, W_old["Wg"], W_old["Wu"], W_old["Wd"], W_old["Wo"],
-                                             want_grads=False, want_dX=False)
-            b["logp_old"] = out["logp"].clone()
+            b["logp_old"] = torch.empty(n_all * cfg.A, dtype=torch.float32, device=device)
+            for c0 in range(0, n_all, per_call):
+                n = min(per_call, n_all - c0)
+                idx = torch.zeros(per_call, dtype=torch.int32, device=device)
+                idx[:n] = torch.arange(c0, c0 + n, dtype=torch.int32, device=device)
+                out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], zeros, adv0, idx,
+                                                 torch.tensor([n], dtype=torch.int32, device=device), cfg.T, cfg.N,
+                                                 cfg.A, W_old["Wg"], W_old["Wu"], W_old["Wd"], W_old["Wo"],
+                                                 want_grads=False, want_dX=False)
+                b["logp_old"][c0 * cfg.A:(c0 + n) * cfg.A] = out["logp"][:n * cfg.A]
         del W_old, zeros
         self.state = pcm.pcm_state_init(cfg.K, device)
         self.sel_out = None
@@ -144,7 +151,9 @@ def main():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unmasked", action="store_true")
-    ap.add_argument("--cpu-sample-chunks", type=int, default=24)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=192)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures the single-GPU hot path only; run it with --gpus 1 "
@@ -160,6 +169,13 @@ def main():
     cfg = CONFIGS[args.config]
 
     wl = Workload(cfg, dev, cfg.n_steps)
+    if args.copy_calibration:
+        src = torch.zeros(1 << 27, dtype=torch.float64, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)      # elementwise kernel on doubles: reads 1 GiB, writes 1 GiB per call
+        torch.cuda.synchronize()
+        del src, dst
     # step 0 from a fresh state once, to hand its kept set to the CPU baseline for cross-checking
     nk0 = wl.step(0)
     torch.cuda.synchronize()

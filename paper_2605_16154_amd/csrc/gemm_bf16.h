@@ -32,6 +32,12 @@ constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
 constexpr int kGemmThreads = 256;
 constexpr int kNumXcd = 8;
 constexpr int kTouchAhead = 3;   // L2-warming distance in 64-wide steps
+// Epilogues pass their results through LDS so that global stores are whole 128-byte lines: each
+// wavefront owns a private staging area (no workgroup barrier needed; LDS operations of one
+// wavefront execute in order).
+constexpr int kWaveStageBytes = 33792;                       // 128 rows x (256 + 8) bytes
+constexpr int kSmemBytes = 4 * kWaveStageBytes > 2 * 2 * kTileM * kTileK * 2 ? 4 * kWaveStageBytes
+                                                                             : 2 * 2 * kTileM * kTileK * 2;
 
 struct GemmProblem {
     const bf16* A;    // [M, K1] row-major, leading dimension lda
@@ -117,7 +123,8 @@ template <class Epilogue>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, Epilogue epi) {
     constexpr int kTileElems = kTileM * kTileK;                  // per operand per stage
     constexpr uint32_t kTileBytes = kTileElems * 2, kStageBytes = 2 * kTileBytes;
-    __shared__ __attribute__((aligned(1024))) __bf16 smem[2 * 2 * kTileElems];   // [stage][A|B][row][64]
+    // [stage][A|B][row][64]; the tail beyond the two stages only serves the epilogue's staging areas
+    __shared__ __attribute__((aligned(1024))) __bf16 smem[kSmemBytes / 2];
     __shared__ uint32_t touch_sink[kGemmThreads * 2];   // landing area of the L2-warming loads, never read
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -272,29 +279,52 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     }
 
     TileCoord tc{m0, n0, wm, wn, lane};
-    epi(tc, acc, reinterpret_cast<float*>(smem));
+    epi(tc, acc, reinterpret_cast<char*>(smem));
 }
 
 // ---- epilogues -------------------------------------------------------------------------------
+
+__device__ inline char* wave_stage(const TileCoord& tc, char* lds) {
+    return lds + (tc.wm * 2 + tc.wn) * kWaveStageBytes;
+}
+
+// Writes bf16(acc[i][j]) for j in [j0, j0 + nj) of tile row i into a staging area whose rows are
+// `stride` bytes apart: element (row, col) of the wavefront's sub-tile goes to
+// stage + (row - row0) * stride + col_off * 2 + (32 (j - j0) + 8 q + 4 (lane >> 5)) * 2.
+template <class F>
+__device__ inline void stage_tile_row(char* stage, int stride, int lane, int local_row, int col_off, int nj, F value) {
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        if (jj >= nj) break;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int col = col_off + jj * 32 + 8 * q + 4 * (lane >> 5);
+            *reinterpret_cast<bf16x4*>(stage + local_row * stride + col * 2) =
+                to_bf16x4(value(jj, 4 * q), value(jj, 4 * q + 1), value(jj, 4 * q + 2), value(jj, 4 * q + 3));
+        }
+    }
+}
 
 // C (bf16, row-major) = acc; rows at and beyond row_limit are not written.
 struct EpiStoreBf16 {
     bf16* C;
     int64_t ldc;
     int row_limit;
-    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], float*) const {
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        constexpr int kStride = 264;                       // 128 bf16 + 8 bytes: conflict-free 8-byte accesses
+        char* st = wave_stage(tc, lds);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = tc.row(i);
-            if (m >= row_limit) continue;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const f32x16& a = acc[i][j];
-                    *reinterpret_cast<bf16x4*>(C + (int64_t)m * ldc + tc.col(j, q)) =
-                        to_bf16x4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]);
-                }
+        for (int i = 0; i < 4; ++i)
+            stage_tile_row(st, kStride, tc.lane, i * 32 + (tc.lane & 31), 0, 4,
+                           [&](int j, int e) { return acc[i][j][e]; });
+        __builtin_amdgcn_wave_barrier();
+        const int row_base = tc.m0 + tc.wm * 128, col_base = tc.n0 + tc.wn * 128;
+#pragma unroll 8
+        for (int it = 0; it < 64; ++it) {                  // two rows of 256 bytes per pass
+            const int r = 2 * it + (tc.lane >> 5);
+            const uint2 v = *reinterpret_cast<const uint2*>(st + r * kStride + (tc.lane & 31) * 8);
+            if (row_base + r < row_limit)
+                *reinterpret_cast<uint2*>(C + (int64_t)(row_base + r) * ldc + col_base + (tc.lane & 31) * 4) = v;
         }
     }
 };
@@ -304,24 +334,44 @@ struct EpiAccumulateF32 {
     float* C;
     int64_t ldc;
     int atomic;
-    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], float*) const {
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        if (atomic) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = tc.row(i);
+            for (int i = 0; i < 4; ++i) {
+                const int m = tc.row(i);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float* c = C + (int64_t)m * ldc + tc.col(j, q);
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) atomicAdd(c + t, acc[i][j][4 * q + t]);
+                    }
+            }
+            return;
+        }
+        constexpr int kStride = 528;                       // 128 fp32 + 16 bytes: conflict-free 16-byte accesses
+        char* st = wave_stage(tc, lds);
+        const int col_base = tc.n0 + tc.wn * 128;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                      // 32 rows per pass
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    float* c = C + (int64_t)m * ldc + tc.col(j, q);
                     const f32x16& a = acc[i][j];
-                    if (atomic) {
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) atomicAdd(c + t, a[4 * q + t]);
-                    } else {
-                        f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
-                        *reinterpret_cast<f32x4*>(c) = v;
-                    }
+                    f32x4 v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+                    *reinterpret_cast<f32x4*>(st + (tc.lane & 31) * kStride + (j * 32 + 8 * q + 4 * (tc.lane >> 5)) * 4) = v;
                 }
+            __builtin_amdgcn_wave_barrier();
+            const int row_base = tc.m0 + tc.wm * 128 + i * 32;
+#pragma unroll 4
+            for (int it = 0; it < 16; ++it) {              // two rows of 512 bytes per pass
+                const int r = 2 * it + (tc.lane >> 5);
+                const f32x4 v = *reinterpret_cast<const f32x4*>(st + r * kStride + (tc.lane & 31) * 16);
+                *reinterpret_cast<f32x4*>(C + (int64_t)(row_base + r) * ldc + col_base + (tc.lane & 31) * 4) = v;
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 };
@@ -332,29 +382,39 @@ struct EpiAccumulateF32 {
 struct EpiSwigluForward {
     bf16 *u, *v, *a;
     int64_t ld;
-    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], float*) const {
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        constexpr int kStride = 392;                       // [u 64 | v 64 | a 64] bf16 + 8 bytes
+        char* st = wave_stage(tc, lds);
         const int col_base = ((tc.n0 + tc.wn * 128) / 128) * 64;
+        bf16* const outs[3] = {u, v, a};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = tc.row(i);
+        for (int half = 0; half < 2; ++half) {             // 64 rows per pass
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = col_base + j * 32 + 8 * q + 4 * (tc.lane >> 5);
-                    float uu[4], vv[4], aa[4];
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        // round u and v first: the backward pass sees the stored values
-                        uu[t] = (float)(__bf16)acc[i][j][4 * q + t];
-                        vv[t] = (float)(__bf16)acc[i][j + 2][4 * q + t];
-                        aa[t] = uu[t] / (1.f + __expf(-uu[t])) * vv[t];
-                    }
-                    const int64_t off = (int64_t)m * ld + n;
-                    *reinterpret_cast<bf16x4*>(u + off) = to_bf16x4(uu[0], uu[1], uu[2], uu[3]);
-                    *reinterpret_cast<bf16x4*>(v + off) = to_bf16x4(vv[0], vv[1], vv[2], vv[3]);
-                    *reinterpret_cast<bf16x4*>(a + off) = to_bf16x4(aa[0], aa[1], aa[2], aa[3]);
-                }
+            for (int ii = 0; ii < 2; ++ii) {
+                const int i = half * 2 + ii;
+                const int lr = ii * 32 + (tc.lane & 31);
+                // u and v are rounded first: the backward pass sees the stored values
+                auto uval = [&](int j, int e) { return (float)(__bf16)acc[i][j][e]; };
+                auto vval = [&](int j, int e) { return (float)(__bf16)acc[i][j + 2][e]; };
+                auto aval = [&](int j, int e) {
+                    const float x = uval(j, e);
+                    return x / (1.f + __expf(-x)) * vval(j, e);
+                };
+                stage_tile_row(st, kStride, tc.lane, lr, 0, 2, uval);
+                stage_tile_row(st, kStride, tc.lane, lr, 64, 2, vval);
+                stage_tile_row(st, kStride, tc.lane, lr, 128, 2, aval);
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int row_base = tc.m0 + tc.wm * 128 + half * 64;
+#pragma unroll 8
+            for (int it = 0; it < 48; ++it) {              // 64 rows x 48 eight-byte pieces
+                const int idx = it * 64 + tc.lane;
+                const int r = idx / 48, piece = idx % 48;
+                const uint2 val = *reinterpret_cast<const uint2*>(st + r * kStride + piece * 8);
+                bf16* dst = outs[piece / 16];
+                *reinterpret_cast<uint2*>(dst + (int64_t)(row_base + r) * ld + col_base + (piece % 16) * 4) = val;
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 };
@@ -363,28 +423,59 @@ struct EpiSwigluForward {
 struct EpiSwigluBackward {
     bf16 *u, *v;
     int64_t ld;
-    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], float*) const {
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        constexpr int kStride = 520;                       // [du 128 | dv 128] bf16 + 8 bytes
+        char* st = wave_stage(tc, lds);
+        const int col_base = tc.n0 + tc.wn * 128;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = tc.row(i);
+        for (int half = 0; half < 2; ++half) {             // 64 rows per pass
+            const int row_base = tc.m0 + tc.wm * 128 + half * 64;
+            // bring u, v of the 64 x 128 block in as whole lines
+#pragma unroll 8
+            for (int it = 0; it < 64; ++it) {
+                const int r = it;
+                const int piece = tc.lane;                 // 64 pieces of 8 bytes: u 32, v 32
+                const bf16* src = piece < 32 ? u : v;
+                const uint2 val = *reinterpret_cast<const uint2*>(src + (int64_t)(row_base + r) * ld + col_base +
+                                                                  (piece & 31) * 4);
+                *reinterpret_cast<uint2*>(st + r * kStride + piece * 8) = val;
+            }
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int ii = 0; ii < 2; ++ii) {
+                const int i = half * 2 + ii;
+                const int lr = ii * 32 + (tc.lane & 31);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int64_t off = (int64_t)m * ld + tc.col(j, q);
-                    const bf16x4 u4 = *reinterpret_cast<const bf16x4*>(u + off);
-                    const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(v + off);
-                    float du[4], dv[4];
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const float x = (float)u4[t], g = acc[i][j][4 * q + t];
-                        const float s = 1.f / (1.f + __expf(-x));
-                        du[t] = g * (float)v4[t] * (s * (1.f + x * (1.f - s)));
-                        dv[t] = g * (x * s);
+                    for (int q = 0; q < 4; ++q) {
+                        const int col = j * 32 + 8 * q + 4 * (tc.lane >> 5);
+                        char* pu = st + lr * kStride + col * 2;
+                        char* pv = pu + 256;
+                        const bf16x4 u4 = *reinterpret_cast<const bf16x4*>(pu);
+                        const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(pv);
+                        float du[4], dv[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float x = (float)u4[t], g = acc[i][j][4 * q + t];
+                            const float sg = 1.f / (1.f + __expf(-x));
+                            du[t] = g * (float)v4[t] * (sg * (1.f + x * (1.f - sg)));
+                            dv[t] = g * (x * sg);
+                        }
+                        *reinterpret_cast<bf16x4*>(pu) = to_bf16x4(du[0], du[1], du[2], du[3]);
+                        *reinterpret_cast<bf16x4*>(pv) = to_bf16x4(dv[0], dv[1], dv[2], dv[3]);
                     }
-                    *reinterpret_cast<bf16x4*>(u + off) = to_bf16x4(du[0], du[1], du[2], du[3]);
-                    *reinterpret_cast<bf16x4*>(v + off) = to_bf16x4(dv[0], dv[1], dv[2], dv[3]);
-                }
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll 8
+            for (int it = 0; it < 64; ++it) {
+                const int r = it;
+                const int piece = tc.lane;
+                bf16* dst = piece < 32 ? u : v;
+                const uint2 val = *reinterpret_cast<const uint2*>(st + r * kStride + piece * 8);
+                *reinterpret_cast<uint2*>(dst + (int64_t)(row_base + r) * ld + col_base + (piece & 31) * 4) = val;
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 };
@@ -401,10 +492,10 @@ struct EpiLogitsLoss {
     bf16* dz;          // [M, 256] or nullptr
     float* logp_out;   // may be nullptr
     RowOut out;
-    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], float* scratch) const {
-        // scratch (LDS, free after the main loop): [2 quantities][2 column halves][256 rows]
-        float* ex_a = scratch;
-        float* ex_b = scratch + 512;
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        // exchange area (LDS, free after the main loop): [2 quantities][2 column halves][256 rows]
+        float* ex_a = reinterpret_cast<float*>(lds);
+        float* ex_b = ex_a + 512;
         int nk = *n_kept;
         nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
         const int64_t rows_live = (int64_t)nk * A;
