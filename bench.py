@@ -25,6 +25,22 @@ GEMM_STAGES = ("gemm_gate_up", "gemm_down", "gemm_logits_loss", "gemm_dWo", "gem
                "gemm_dWg_dWu", "gemm_dX")
 
 
+def stored_traffic(name):
+    """HBM-side bytes per launch from the committed counter summary, or None if the kernel changed since."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    kv = dict(line.strip().split("=", 1) for line in open(path) if "=" in line and not line.startswith("#"))
+    from paper_2605_16154_amd.profile_summary import kernel_source_hash
+    if kv.get("source_hash") != kernel_source_hash():
+        return None
+    try:
+        return (float(kv["fetch_kib_per_launch"]) * float(kv["scale_fetch"]) +
+                float(kv["write_kib_per_launch"]) * float(kv["scale_write"])) * 1024.0
+    except (KeyError, ValueError):
+        return None
+
+
 def gemm_flops_per_launch(M, d, ff, V):
     """Algorithmic flops of one launch of each head GEMM over M token rows (2 flops per multiply-add)."""
     return {"gemm_gate_up": 2.0 * M * d * 2 * ff, "gemm_down": 2.0 * M * ff * d, "gemm_logits_loss": 2.0 * M * d * V,
@@ -201,7 +217,7 @@ def main():
     achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": f"gemm_bf16_nt ({dominant})", "achieved": achieved,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": None,
+                "traffic": stored_traffic("gemm_gate_up_cfg2_traffic.txt") if cfg.name == "cfg2" else None,
                 "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
                 "all_head_gemms": {"tflops": total_flops_step / (gemm_ms_step * 1e-3) / 1e12,
                                    "frac": total_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,

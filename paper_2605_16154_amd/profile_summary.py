@@ -2,6 +2,8 @@
 
   python -m paper_2605_16154_amd.profile_summary stats   <dir>   # --kernel-trace --stats runs
   python -m paper_2605_16154_amd.profile_summary counter <dir>   # --pmc runs (per-kernel means)
+  python -m paper_2605_16154_amd.profile_summary traffic <fetch_dir> <write_dir> <kernel substring>
+                                                                  # HBM-side bytes per launch of one kernel
 """
 from __future__ import annotations
 
@@ -46,7 +48,45 @@ def counter(path: str) -> str:
     return "\n".join(out) + "\n"
 
 
+KERNEL_SOURCES = ("gemm_bf16.h", "actor_bf16.hip")
+
+
+def kernel_source_hash() -> str:
+    """Hash of the sources of the bf16 GEMM; byte counters are only valid for the code they were taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
+    for name in KERNEL_SOURCES:
+        h.update(open(os.path.join(here, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def _mean_counter(path: str, counter_name: str, kernel_substr: str):
+    vals = []
+    for f in glob.glob(os.path.join(path, "**", "*counter_collection.csv"), recursive=True):
+        for row in csv.DictReader(open(f)):
+            if row["Counter_Name"] == counter_name and kernel_substr in row["Kernel_Name"]:
+                vals.append(float(row["Counter_Value"]))
+    return (sum(vals) / len(vals), len(vals)) if vals else (float("nan"), 0)
+
+
+def traffic(fetch_dir: str, write_dir: str, kernel_substr: str) -> str:
+    fetch, nf = _mean_counter(fetch_dir, "FETCH_SIZE", kernel_substr)
+    write, nw = _mean_counter(write_dir, "WRITE_SIZE", kernel_substr)
+    cal_f, _ = _mean_counter(fetch_dir, "FETCH_SIZE", "CUDAFunctorOnSelf_add<double>")
+    cal_w, _ = _mean_counter(write_dir, "WRITE_SIZE", "CUDAFunctorOnSelf_add<double>")
+    gib = float(1 << 20)   # KiB in 1 GiB
+    return (f"kernel={kernel_substr}\nlaunches_fetch={nf}\nlaunches_write={nw}\n"
+            f"fetch_kib_per_launch={fetch:.1f}\nwrite_kib_per_launch={write:.1f}\n"
+            f"calibration_fetch_kib_for_1GiB_read={cal_f:.1f}\ncalibration_write_kib_for_1GiB_write={cal_w:.1f}\n"
+            f"scale_fetch={gib / cal_f:.4f}\nscale_write={gib / cal_w:.4f}\n"
+            f"source_hash={kernel_source_hash()}\n")
+
+
 if __name__ == "__main__":
+    if len(sys.argv) == 5 and sys.argv[1] == "traffic":
+        sys.stdout.write(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
+        sys.exit(0)
     if len(sys.argv) != 3 or sys.argv[1] not in ("stats", "counter"):
         sys.exit(__doc__)
     sys.stdout.write(stats(sys.argv[2]) if sys.argv[1] == "stats" else counter(sys.argv[2]))
