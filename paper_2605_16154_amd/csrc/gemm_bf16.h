@@ -7,10 +7,11 @@
 //
 // Tiling: 256 x 256 x 64 per workgroup of 4 wavefronts (2 x 2), each wavefront owning 128 x 128 =
 // 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 with fp32 accumulators (256 accumulator registers per
-// lane, one wavefront per SIMD).  Operand tiles are double-buffered in LDS (2 x 64 KB) and filled
-// by direct global-to-LDS loads (no staging registers); rows are 128 B and the eight 16-byte
-// pieces of a row are XOR-swizzled with the row index so that the 16-byte fragment reads spread
-// over all banks.
+// lane, one wavefront per SIMD).  Operand tiles (32 KB each) live in a ring of five LDS slots
+// filled by direct global-to-LDS loads (no staging registers): two slots are being multiplied,
+// up to three are in flight, so the load path never drains at the per-step barrier.  Rows are
+// 128 B and the eight 16-byte pieces of a row are XOR-swizzled with the row index so that the
+// 16-byte fragment reads spread over all banks.
 //
 // The MFMA is issued with the B fragment as the first operand, so the accumulator tile is the
 // transpose of the usual one: a lane holds, for one output row m, runs of 4 consecutive n.
@@ -31,13 +32,13 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
 constexpr int kGemmThreads = 256;
 constexpr int kNumXcd = 8;
-constexpr int kTouchAhead = 3;   // L2-warming distance in 64-wide steps
+constexpr int kRingSlots = 5;    // operand tiles resident or in flight in LDS
 // Epilogues pass their results through LDS so that global stores are whole 128-byte lines: each
 // wavefront owns a private staging area (no workgroup barrier needed; LDS operations of one
 // wavefront execute in order).
 constexpr int kWaveStageBytes = 33792;                       // 128 rows x (256 + 8) bytes
-constexpr int kSmemBytes = 4 * kWaveStageBytes > 2 * 2 * kTileM * kTileK * 2 ? 4 * kWaveStageBytes
-                                                                             : 2 * 2 * kTileM * kTileK * 2;
+constexpr int kSmemBytes = kRingSlots * kTileM * kTileK * 2;   // 160 KB: the whole LDS of a CU
+static_assert(4 * kWaveStageBytes <= kSmemBytes, "epilogue staging must fit in the operand ring");
 
 struct GemmProblem {
     const bf16* A;    // [M, K1] row-major, leading dimension lda
@@ -104,14 +105,6 @@ __device__ inline void direct_load_16B(const char* base, uint32_t lane_offset, u
                  : "s"(lds_addr), "v"(lane_offset), "s"(base)
                  : "memory");
 }
-// 4 bytes per lane, landing at lds_addr + 4 l: used only to pull the touched cache lines into L2
-// ahead of the wide loads (the data is never read).
-__device__ inline void direct_load_4B(const char* base, uint32_t lane_offset, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :
-                 : "s"(lds_addr), "v"(lane_offset), "s"(base)
-                 : "memory");
-}
 // Direct loads retire in issue order, so waiting until at most `newest` remain outstanding
 // guarantees that all older ones have landed.
 template <int kNewest>
@@ -121,11 +114,10 @@ __device__ inline void wait_direct_loads() {
 
 template <class Epilogue>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, Epilogue epi) {
-    constexpr int kTileElems = kTileM * kTileK;                  // per operand per stage
-    constexpr uint32_t kTileBytes = kTileElems * 2, kStageBytes = 2 * kTileBytes;
-    // [stage][A|B][row][64]; the tail beyond the two stages only serves the epilogue's staging areas
-    __shared__ __attribute__((aligned(1024))) __bf16 smem[kSmemBytes / 2];
-    __shared__ uint32_t touch_sink[kGemmThreads * 2];   // landing area of the L2-warming loads, never read
+    constexpr int kTileElems = kTileM * kTileK;                  // one operand tile
+    constexpr uint32_t kTileBytes = kTileElems * 2;
+    constexpr int kLoadsPerTile = 8;                             // wave-wide loads per wavefront per tile
+    __shared__ __attribute__((aligned(1024))) __bf16 smem[kSmemBytes / 2];   // [slot][row][64]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
@@ -146,50 +138,32 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     // Global -> LDS: one wave-wide load fills 1 KB of LDS (8 tile rows), lane l landing in 16-byte
     // slot l.  The swizzle is therefore applied on the global side: the lane that lands in slot
     // (row, piece') fetches piece' ^ swizzle(row) of that row.  Wave w fills rows [64 w, 64 w + 64)
-    // of both tiles with 8 loads each; addresses are a wave-uniform base (tile origin + k offset)
-    // plus a 32-bit per-lane byte offset.
+    // of a tile with 8 loads; addresses are a wave-uniform base (tile origin + k offset) plus a
+    // 32-bit per-lane byte offset.
     const uint32_t lds_base = (uint32_t)(uintptr_t)PCM_AS_LDS(smem);
     const uint32_t ld_row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);   // + 8 r for load r
     const uint32_t ld_piece = (uint32_t)swizzle_piece(lane >> 3, lane & 7);  // rows + 8 r share low bits
     struct LoadCtx {
-        const char *abase, *bbase;     // wave-uniform
-        uint32_t aoff, boff, la, lb;   // per-lane byte offsets of load 0; leading dimensions
-        uint32_t dst;                  // LDS byte address of this wave's first A row in the stage
+        const char* base;     // wave-uniform
+        uint32_t off, ld;     // per-lane byte offset of load 0; leading dimension
+        uint32_t dst;         // LDS byte address of this wave's first row in the slot
     };
-    auto load_ctx = [&](uint32_t stage, int step) {
+    // operand 0 = A rows m0.., operand 1 = B rows n0..
+    auto load_ctx = [&](int operand, uint32_t slot, int step) {
         LoadCtx c;
         const bool seg1 = step < steps1;
-        const bf16* a = seg1 ? p.A : p.A2;
-        const bf16* b = seg1 ? p.B : p.B2;
-        c.la = (uint32_t)(seg1 ? p.lda : p.lda2);
-        c.lb = (uint32_t)(seg1 ? p.ldb : p.ldb2);
+        const bf16* ptr = operand == 0 ? (seg1 ? p.A : p.A2) : (seg1 ? p.B : p.B2);
+        c.ld = (uint32_t)(operand == 0 ? (seg1 ? p.lda : p.lda2) : (seg1 ? p.ldb : p.ldb2));
         const int k0 = (seg1 ? step : step - steps1) * kTileK;
-        c.abase = reinterpret_cast<const char*>(a + (int64_t)m0 * c.la + k0);
-        c.bbase = reinterpret_cast<const char*>(b + (int64_t)n0 * c.lb + k0);
-        c.aoff = (ld_row * c.la + ld_piece * 8u) * 2u;
-        c.boff = (ld_row * c.lb + ld_piece * 8u) * 2u;
-        c.dst = lds_base + stage * kStageBytes + (uint32_t)wave * 64u * (kTileK * 2u);
+        const int row0 = operand == 0 ? m0 : n0;
+        c.base = reinterpret_cast<const char*>(ptr + (int64_t)row0 * c.ld + k0);
+        c.off = (ld_row * c.ld + ld_piece * 8u) * 2u;
+        c.dst = lds_base + slot * kTileBytes + (uint32_t)wave * 64u * (kTileK * 2u);
         return c;
     };
-    // L2 warming: thread t touches the cache line of row t of both operand tiles for `step`
-    const uint32_t sink = (uint32_t)(uintptr_t)PCM_AS_LDS(touch_sink) + (uint32_t)wave * 512u;
-    auto touch_lines = [&](int step) {
-        const bool seg1 = step < steps1;
-        const bf16* a = seg1 ? p.A : p.A2;
-        const bf16* b = seg1 ? p.B : p.B2;
-        const uint32_t la = (uint32_t)(seg1 ? p.lda : p.lda2), lb = (uint32_t)(seg1 ? p.ldb : p.ldb2);
-        const int k0 = (seg1 ? step : step - steps1) * kTileK;
-        const uint32_t row = (uint32_t)wave * 64u + (uint32_t)lane;
-        direct_load_4B(reinterpret_cast<const char*>(a + (int64_t)m0 * la + k0), row * la * 2u, sink);
-        direct_load_4B(reinterpret_cast<const char*>(b + (int64_t)n0 * lb + k0), row * lb * 2u, sink + 256u);
-    };
-    // loads r = r0 .. r0 + n - 1 of both operands (8 rows of A and 8 rows of B each)
     auto issue_loads = [&](const LoadCtx& c, uint32_t r0, uint32_t n) {
 #pragma unroll
-        for (uint32_t r = r0; r < r0 + n; ++r) {
-            direct_load_16B(c.abase, c.aoff + r * 16u * c.la, c.dst + r * 1024u);
-            direct_load_16B(c.bbase, c.boff + r * 16u * c.lb, c.dst + kTileBytes + r * 1024u);
-        }
+        for (uint32_t r = r0; r < r0 + n; ++r) direct_load_16B(c.base, c.off + r * 16u * c.ld, c.dst + r * 1024u);
     };
 
     f32x16 acc[4][4];
@@ -205,17 +179,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     // the wavefront's A and B sub-tiles.
     bf16x8 fa[2][4], fb[2][4];
     const int frow_a = wm * 128 + (lane & 31), frow_b = wn * 128 + (lane & 31);
-    auto read_frag_pair = [&](int set, uint32_t stage, int ks, int i) {
-        const __bf16* sa = smem + stage * (2 * kTileElems);
-        const __bf16* sb = sa + kTileElems;
+    auto read_frag_pair = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks, int i) {
+        const __bf16* sa = smem + slot_a * kTileElems;
+        const __bf16* sb = smem + slot_b * kTileElems;
         const int piece = ks * 2 + (lane >> 5);
         const int ra = frow_a + i * 32, rb = frow_b + i * 32;
         fa[set][i] = *reinterpret_cast<const bf16x8*>(sa + ra * kTileK + swizzle_piece(ra, piece) * 8);
         fb[set][i] = *reinterpret_cast<const bf16x8*>(sb + rb * kTileK + swizzle_piece(rb, piece) * 8);
     };
-    auto read_frags = [&](int set, uint32_t stage, int ks) {
+    auto read_frags = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) read_frag_pair(set, stage, ks, i);
+        for (int i = 0; i < 4; ++i) read_frag_pair(set, slot_a, slot_b, ks, i);
     };
     auto mfma_row = [&](int set, int i) {
 #pragma unroll
@@ -234,45 +208,55 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
     };
+    auto next_slot = [](uint32_t s) { return s + 1u >= (uint32_t)kRingSlots ? s + 1u - kRingSlots : s + 1u; };
 
     if (step_begin < step_end) {
-        issue_loads(load_ctx(0, step_begin), 0, 8);
-        wait_direct_loads<0>();
+        // Operand tiles are numbered 2 s + o (o = 0 for A, 1 for B of step s) and tile t lives in ring
+        // slot t mod 5.  Prologue: tiles 0..4 (steps 0, 1 and the A tile of step 2) are requested;
+        // steps past the end re-request the last step's tiles, which nobody reads.
+        const int last = step_end - 1;
+        issue_loads(load_ctx(0, 0, step_begin), 0, 8);
+        issue_loads(load_ctx(1, 1, step_begin), 0, 8);
+        issue_loads(load_ctx(0, 2, min(step_begin + 1, last)), 0, 8);
+        issue_loads(load_ctx(1, 3, min(step_begin + 1, last)), 0, 8);
+        issue_loads(load_ctx(0, 4, min(step_begin + 2, last)), 0, 8);
+        wait_direct_loads<3 * kLoadsPerTile>();
         __syncthreads();
-        issue_loads(load_ctx(1, min(step_begin + 1, step_end - 1)), 0, 8);
-        touch_lines(min(step_begin + 2, step_end - 1));
-        read_frags(0, 0, 0);
-        // One 64-wide step per trip on stage `cur`; the other stage holds the following step (loaded
-        // one step earlier).  Fragment set 0 holds slice 0 of `cur` on entry and slice 0 of the next
-        // step on exit.  The single barrier sits before the last slice: by then every wavefront has
-        // issued all its reads of `cur`, so `cur` can be refilled for the step after next; the refill
-        // loads are issued in four groups between the MFMA rows of the last slice so that the matrix
-        // pipe keeps running while the texture path takes them.  The body is branch-free: near the end
-        // it reloads the last tile and reads fragments nobody uses.
-        uint32_t cur = 0;
+        read_frags(0, 0, 1, 0);
+        // One 64-wide step per trip.  `sa`, `sb` are the slots of this step's tiles; the next step's
+        // are the two after them in the ring.  Fragment set 0 holds slice 0 of this step on entry and
+        // slice 0 of the next step on exit.  The single barrier sits before the last slice: by then
+        // every wavefront has issued all its reads of `sa`, `sb`, so both slots are refilled (with
+        // the B tile of step + 2 and the A tile of step + 3) in four groups between the MFMA rows of
+        // the last slice.  At the barrier only the newest tile (A of step + 2) may still be in
+        // flight, which keeps the load path busy across it.  The body is branch-free.
+        uint32_t sa = 0;
         for (int step = step_begin; step < step_end; ++step) {
-            read_frags(1, cur, 1);
+            const uint32_t sb = next_slot(sa);
+            const uint32_t na = next_slot(sb), nb = next_slot(na);
+            read_frags(1, sa, sb, 1);
             mfma_slice(0);
             interleave_reads();
-            touch_lines(min(step + kTouchAhead, step_end - 1));   // issued after the previous refill
-            read_frags(0, cur, 2);
+            read_frags(0, sa, sb, 2);
             mfma_slice(1);
             interleave_reads();
-            read_frags(1, cur, 3);
+            read_frags(1, sa, sb, 3);
             mfma_slice(0);
             interleave_reads();
-            wait_direct_loads<2>();                               // all but the two line touches
+            wait_direct_loads<kLoadsPerTile>();
             __syncthreads();
-            const LoadCtx c = load_ctx(cur, min(step + 2, step_end - 1));
+            const LoadCtx cb = load_ctx(1, sa, min(step + 2, last));   // tile 2 s + 5 -> slot of tile 2 s
+            const LoadCtx ca = load_ctx(0, sb, min(step + 3, last));   // tile 2 s + 6 -> slot of tile 2 s + 1
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                issue_loads(c, 2 * g, 2);
-                read_frag_pair(0, cur ^ 1u, 0, g);
+                if (g < 2) issue_loads(cb, 4 * g, 4);
+                else issue_loads(ca, 4 * (g - 2), 4);
+                read_frag_pair(0, na, nb, 0, g);
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_row(1, g);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            cur ^= 1u;
+            sa = na;
         }
         wait_direct_loads<0>();
         __syncthreads();
