@@ -6,9 +6,10 @@
 //           overwrite u, v); weight gradients as split reductions over the row dimension with
 //           fp32 atomics; dX = du Wg^T + dv Wu^T as one GEMM over two reduction segments.
 //
-// Every GEMM runs in the "both operands reduction-contiguous" form of gemm_bf16.h; operands that
-// are stored the other way round (the [in, out] weights in the forward pass, the activations in
-// the weight-gradient products) are copied transposed by a streaming kernel first.
+// The forward and input-gradient products take both operands reduction-contiguous; for the forward
+// pass the [in, out] weights are first copied transposed (gate and up interleaved in blocks of 64
+// columns so that the activation can be fused).  The weight-gradient products reduce over the row
+// dimension and read the activations as they are, through the GEMM's LDS transpose reads.
 //
 // Rows are padded to a multiple of 256; padding rows are zero with zero advantage, so they
 // contribute nothing to any output.
@@ -50,8 +51,7 @@ __global__ __launch_bounds__(256) void transpose_bf16(const uint16_t* __restrict
     }
 }
 
-void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t ld_dst, int mode = kPackNone,
-               int stage = ST_TRANSPOSE) {
+void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t ld_dst, int mode, int stage) {
     StageTimer t(stage, s);
     dim3 grid(C / 64, R / 64);
     transpose_bf16<<<grid, 256, 0, s>>>(reinterpret_cast<const uint16_t*>(src), C,
@@ -74,7 +74,7 @@ void zero(hipStream_t s, float* p, size_t n) {
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
     bf16 *X, *u, *v, *a, *y, *dz;
-    bf16 *dy, *XT, *aT, *yT, *dzT, *dyT, *duT, *dvT;
+    bf16* dy;
     RowMeta meta;
     RowOut out;
     int64_t Mp;
@@ -104,15 +104,7 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     w.out.dlogp = c.take<float>(Mp);
     w.out.clipped = c.take<uint8_t>(Mp);
     if (bwd) w.dy = c.take<bf16>(Mp * d);
-    if (grads) {
-        w.XT = c.take<bf16>(d * Mp);
-        w.aT = c.take<bf16>(ff * Mp);
-        w.yT = c.take<bf16>(d * Mp);
-        w.dzT = c.take<bf16>(V * Mp);
-        w.dyT = c.take<bf16>(d * Mp);
-        w.duT = c.take<bf16>(ff * Mp);
-        w.dvT = c.take<bf16>(ff * Mp);
-    }
+    (void)grads;
     w.bytes = c.used();
     return w;
 }
@@ -183,32 +175,25 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
     }
     if (grads) {
-        transpose(s, w.y, Mp, d, w.yT, Mp);
-        transpose(s, w.dz, Mp, V, w.dzT, Mp);
-        GemmProblem p = problem(w.yT, Mp, w.dzT, Mp, d, V, Mp);                                   // dWo = y^T dz
+        GemmProblem p = problem(w.y, d, w.dz, V, d, V, Mp);                                       // dWo = y^T dz
         p.splits = pick_splits((d / kTileM) * (V / kTileN), Mp / kTileK);
         if (p.splits > 1) zero(s, io.dWo, (size_t)d * V);
         StageTimer t(ST_GEMM_DWO, s);
-        launch_gemm(p, EpiAccumulateF32{io.dWo, V, p.splits > 1}, s);
+        launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWo, V, p.splits > 1}, s);
     }
     if (grads) {
-        transpose(s, w.a, Mp, ff, w.aT, Mp);
-        transpose(s, w.dy, Mp, d, w.dyT, Mp);
-        GemmProblem p = problem(w.aT, Mp, w.dyT, Mp, ff, d, Mp);                                  // dWd = a^T dy
+        GemmProblem p = problem(w.a, ff, w.dy, d, ff, d, Mp);                                     // dWd = a^T dy
         p.splits = pick_splits((ff / kTileM) * (d / kTileN), Mp / kTileK);
         if (p.splits > 1) zero(s, io.dWd, (size_t)ff * d);
         StageTimer t(ST_GEMM_DWD, s);
-        launch_gemm(p, EpiAccumulateF32{io.dWd, d, p.splits > 1}, s);
+        launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWd, d, p.splits > 1}, s);
     }
     {
         StageTimer t(ST_GEMM_DA, s);
         launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
     }
     if (grads) {
-        transpose(s, w.X, Mp, d, w.XT, Mp);
-        transpose(s, w.u, Mp, ff, w.duT, Mp);
-        transpose(s, w.v, Mp, ff, w.dvT, Mp);
-        GemmProblem p = problem(w.XT, Mp, w.duT, Mp, d, ff, Mp);                                  // dWg = X^T du
+        GemmProblem p = problem(w.X, d, w.u, ff, d, ff, Mp);                                      // dWg = X^T du
         p.splits = pick_splits((d / kTileM) * (ff / kTileN), Mp / kTileK);
         if (p.splits > 1) {
             zero(s, io.dWg, (size_t)d * ff);
@@ -216,11 +201,11 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         }
         {
             StageTimer t(ST_GEMM_DWG_DWU, s);
-            launch_gemm(p, EpiAccumulateF32{io.dWg, ff, p.splits > 1}, s);
+            launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWg, ff, p.splits > 1}, s);
         }
-        p.B = w.dvT;                                                                              // dWu = X^T dv
+        p.B = w.v;                                                                                // dWu = X^T dv
         StageTimer t(ST_GEMM_DWG_DWU, s);
-        launch_gemm(p, EpiAccumulateF32{io.dWu, ff, p.splits > 1}, s);
+        launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWu, ff, p.splits > 1}, s);
     }
     if (io.dX) {
         StageTimer t(ST_GEMM_DX, s);

@@ -1,9 +1,11 @@
 // bf16 matrix-core GEMM for gfx950 with fused epilogues (internal header).
 //
-// C[m, n] = sum_k A[m, k] * B[n, k]: both operands are stored with the reduction index
-// contiguous ("NT"), which is the layout the MFMA operand registers want (each lane feeds 8
-// consecutive k of one row).  Products that are not naturally in this form get a transposed copy
-// of one operand from a separate streaming kernel.
+// C[m, n] = sum_k A(m, k) * B(n, k).  Each operand may be stored either with the reduction index
+// contiguous ([rows][K], the layout the MFMA operand registers want: a lane feeds 8 consecutive k
+// of one row, read with ds_read_b128) or with the reduction index as the slow dimension
+// ([K][rows], e.g. activations in the weight-gradient products); the latter is brought into
+// operand layout by gfx950's LDS transpose reads (ds_read_b64_tr_b16), so no operand is ever
+// copied transposed in memory.
 //
 // Tiling: 256 x 256 x 64 per workgroup of 4 wavefronts (2 x 2), each wavefront owning 128 x 128 =
 // 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 with fp32 accumulators (256 accumulator registers per
@@ -28,6 +30,14 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+// How an operand of C[m, n] = sum_k A(m, k) B(n, k) is stored.
+enum OperandLayout : int {
+    kRowsByK = 0,   // [rows][K]: element (row, k) at ptr[row * ld + k]
+    kKByRows = 1    // [K][rows]: element (row, k) at ptr[k * ld + row]
+};
 
 constexpr int kTileM = 256, kTileN = 256, kTileK = 64;
 constexpr int kGemmThreads = 256;
@@ -41,8 +51,8 @@ constexpr int kSmemBytes = kRingSlots * kTileM * kTileK * 2;   // 160 KB: the wh
 static_assert(4 * kWaveStageBytes <= kSmemBytes, "epilogue staging must fit in the operand ring");
 
 struct GemmProblem {
-    const bf16* A;    // [M, K1] row-major, leading dimension lda
-    const bf16* B;    // [N, K1] row-major, leading dimension ldb
+    const bf16* A;    // M x K1 operand, leading dimension lda (layout given by the kernel's template arguments)
+    const bf16* B;    // N x K1 operand, leading dimension ldb
     const bf16* A2;   // optional second reduction segment (same M, N), K2 columns
     const bf16* B2;
     int64_t lda, ldb, lda2, ldb2;
@@ -112,8 +122,20 @@ __device__ inline void wait_direct_loads() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kNewest) : "memory");
 }
 
-template <class Epilogue>
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, Epilogue epi) {
+// 8 bf16 of one operand row at 8 consecutive k, from a [K][rows] tile: two transpose reads of 4 k
+// each.  Within a group of 16 lanes the instruction hands lane j the j-th 16-bit element of each of
+// the four 32-byte runs addressed by lanes 4 q .. 4 q + 3 (q = 0..3); the callers point run q at
+// k-row q, so lane j receives k = 0..3 of row j.
+__device__ inline bf16x8 read_transposed_fragment(const char* lds_ptr) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_ptr));
+    const s16x4 hi =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(lds_ptr + 4 * 512));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+template <class Epilogue, int kLayA, int kLayB>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epilogue epi) {
     constexpr int kTileElems = kTileM * kTileK;                  // one operand tile
     constexpr uint32_t kTileBytes = kTileElems * 2;
     constexpr int kLoadsPerTile = 8;                             // wave-wide loads per wavefront per tile
@@ -135,35 +157,54 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     const int step_begin = split * per_split;
     const int step_end = min(steps_all, step_begin + per_split);
 
-    // Global -> LDS: one wave-wide load fills 1 KB of LDS (8 tile rows), lane l landing in 16-byte
-    // slot l.  The swizzle is therefore applied on the global side: the lane that lands in slot
-    // (row, piece') fetches piece' ^ swizzle(row) of that row.  Wave w fills rows [64 w, 64 w + 64)
-    // of a tile with 8 loads; addresses are a wave-uniform base (tile origin + k offset) plus a
-    // 32-bit per-lane byte offset.
+    // Global -> LDS: one wave-wide load fills 1 KB of LDS, lane l landing in 16-byte slot l; the
+    // swizzle is therefore applied on the global side (the lane that lands in a slot fetches the
+    // piece that belongs there).  Addresses are a wave-uniform base (tile origin + k offset) plus
+    // a 32-bit per-lane byte offset.
+    //   [rows][K] operand: the tile is [256 rows][128 B]; wave w fills rows [64 w, 64 w + 64), 8 rows
+    //     per load; piece p of row r sits in slot p ^ (r & 7).
+    //   [K][rows] operand: the tile is [64 k][512 B]; wave w fills k-rows [16 w, 16 w + 16), 2 per
+    //     load; the 32-byte unit u of k-row k sits in unit u ^ (k & 3), so the four k-rows touched
+    //     by one 16-lane transpose read fall into different banks.
     const uint32_t lds_base = (uint32_t)(uintptr_t)PCM_AS_LDS(smem);
-    const uint32_t ld_row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);   // + 8 r for load r
-    const uint32_t ld_piece = (uint32_t)swizzle_piece(lane >> 3, lane & 7);  // rows + 8 r share low bits
     struct LoadCtx {
-        const char* base;     // wave-uniform
-        uint32_t off, ld;     // per-lane byte offset of load 0; leading dimension
-        uint32_t dst;         // LDS byte address of this wave's first row in the slot
+        const char* base;        // wave-uniform
+        uint32_t off[2];         // per-lane byte offset of an even / odd load before the per-load stride
+        uint32_t stride;         // bytes between consecutive loads
+        uint32_t dst;            // LDS byte address of this wave's part of the slot
     };
     // operand 0 = A rows m0.., operand 1 = B rows n0..
     auto load_ctx = [&](int operand, uint32_t slot, int step) {
         LoadCtx c;
         const bool seg1 = step < steps1;
         const bf16* ptr = operand == 0 ? (seg1 ? p.A : p.A2) : (seg1 ? p.B : p.B2);
-        c.ld = (uint32_t)(operand == 0 ? (seg1 ? p.lda : p.lda2) : (seg1 ? p.ldb : p.ldb2));
+        const uint32_t ld = (uint32_t)(operand == 0 ? (seg1 ? p.lda : p.lda2) : (seg1 ? p.ldb : p.ldb2));
         const int k0 = (seg1 ? step : step - steps1) * kTileK;
         const int row0 = operand == 0 ? m0 : n0;
-        c.base = reinterpret_cast<const char*>(ptr + (int64_t)row0 * c.ld + k0);
-        c.off = (ld_row * c.ld + ld_piece * 8u) * 2u;
-        c.dst = lds_base + slot * kTileBytes + (uint32_t)wave * 64u * (kTileK * 2u);
+        const int layout = operand == 0 ? kLayA : kLayB;
+        if (layout == kRowsByK) {
+            const uint32_t row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);      // + 8 r for load r
+            const uint32_t piece = (uint32_t)swizzle_piece(lane >> 3, lane & 7);     // rows + 8 r share low bits
+            c.base = reinterpret_cast<const char*>(ptr + (int64_t)row0 * ld + k0);
+            c.off[0] = c.off[1] = (row * ld + piece * 8u) * 2u;
+            c.stride = 16u * ld;
+        } else {
+            const uint32_t krow = (uint32_t)wave * 16u + (uint32_t)(lane >> 5);      // + 2 r for load r
+            c.base = reinterpret_cast<const char*>(ptr + (int64_t)k0 * ld + row0);
+#pragma unroll
+            for (uint32_t odd = 0; odd < 2; ++odd) {
+                const uint32_t k_low = 2u * odd + (uint32_t)(lane >> 5);             // (k-row of the load) & 3
+                const uint32_t piece = (uint32_t)(lane & 31) ^ (2u * k_low);
+                c.off[odd] = (krow * ld + piece * 8u) * 2u;
+            }
+            c.stride = 4u * ld;
+        }
+        c.dst = lds_base + slot * kTileBytes + (uint32_t)wave * 8192u;
         return c;
     };
     auto issue_loads = [&](const LoadCtx& c, uint32_t r0, uint32_t n) {
 #pragma unroll
-        for (uint32_t r = r0; r < r0 + n; ++r) direct_load_16B(c.base, c.off + r * 16u * c.ld, c.dst + r * 1024u);
+        for (uint32_t r = r0; r < r0 + n; ++r) direct_load_16B(c.base, c.off[r & 1u] + r * c.stride, c.dst + r * 1024u);
     };
 
     f32x16 acc[4][4];
@@ -178,14 +219,25 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
     // 8 fragment reads of the next slice are in flight.  Fragment pair i = rows 32 i .. 32 i + 31 of
     // the wavefront's A and B sub-tiles.
     bf16x8 fa[2][4], fb[2][4];
-    const int frow_a = wm * 128 + (lane & 31), frow_b = wn * 128 + (lane & 31);
+    // byte offset inside a tile of this lane's fragment for row block i, slice ks
+    auto frag_offset = [&](int layout, int sub_row0, int ks, int i) -> uint32_t {
+        if (layout == kRowsByK) {
+            const int row = sub_row0 + i * 32 + (lane & 31);
+            const int piece = ks * 2 + (lane >> 5);
+            return (uint32_t)(row * (kTileK * 2) + swizzle_piece(row, piece) * 16);
+        }
+        const int g = lane >> 4, j = lane & 15;                    // 16-lane group, lane in group
+        const int col0 = sub_row0 + i * 32 + (g & 1) * 16;         // this group's 16 rows of the operand
+        const int k = ks * 16 + (g >> 1) * 8 + (j >> 2);           // k-row this lane's run starts in
+        return (uint32_t)(k * 512 + ((((col0 >> 4) ^ (j >> 2)) & 15) << 5) + ((j & 3) << 3));
+    };
     auto read_frag_pair = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks, int i) {
-        const __bf16* sa = smem + slot_a * kTileElems;
-        const __bf16* sb = smem + slot_b * kTileElems;
-        const int piece = ks * 2 + (lane >> 5);
-        const int ra = frow_a + i * 32, rb = frow_b + i * 32;
-        fa[set][i] = *reinterpret_cast<const bf16x8*>(sa + ra * kTileK + swizzle_piece(ra, piece) * 8);
-        fb[set][i] = *reinterpret_cast<const bf16x8*>(sb + rb * kTileK + swizzle_piece(rb, piece) * 8);
+        const char* sa = reinterpret_cast<const char*>(smem) + slot_a * kTileBytes + frag_offset(kLayA, wm * 128, ks, i);
+        const char* sb = reinterpret_cast<const char*>(smem) + slot_b * kTileBytes + frag_offset(kLayB, wn * 128, ks, i);
+        if (kLayA == kRowsByK) fa[set][i] = *reinterpret_cast<const bf16x8*>(sa);
+        else fa[set][i] = read_transposed_fragment(sa);
+        if (kLayB == kRowsByK) fb[set][i] = *reinterpret_cast<const bf16x8*>(sb);
+        else fb[set][i] = read_transposed_fragment(sb);
     };
     auto read_frags = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks) {
 #pragma unroll
@@ -200,11 +252,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_nt(GemmProblem p, E
 #pragma unroll
         for (int i = 0; i < 4; ++i) mfma_row(set, i);
     };
-    // scheduling hint: "one LDS read, then two MFMAs", eight times
+    // scheduling hint for one slice: LDS reads (8, 12 or 16 depending on the layouts) spread over
+    // the 16 MFMAs
     auto interleave_reads = [&]() {
+        constexpr int kReads = 4 * (1 + kLayA) + 4 * (1 + kLayB);
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, kReads / 8, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
     };
@@ -570,10 +624,10 @@ struct EpiLogitsLoss {
     }
 };
 
-template <class Epilogue>
+template <int kLayA = kRowsByK, int kLayB = kRowsByK, class Epilogue>
 inline void launch_gemm(const GemmProblem& p, const Epilogue& epi, hipStream_t s) {
     const unsigned grid = (unsigned)(p.M / kTileM) * (unsigned)(p.N / kTileN) * (unsigned)p.splits;
-    gemm_bf16_nt<Epilogue><<<grid, kGemmThreads, 0, s>>>(p, epi);
+    gemm_bf16<Epilogue, kLayA, kLayB><<<grid, kGemmThreads, 0, s>>>(p, epi);
 }
 
 }  // namespace pcm
