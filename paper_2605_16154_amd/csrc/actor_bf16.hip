@@ -121,11 +121,19 @@ int pick_splits(int tiles, int steps) {
     return s < 1 ? 1 : s;
 }
 
-GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K) {
+// Which GEMM dimension runs over the kept rows, so that work beyond the device-side count is skipped.
+struct KeptRows {
+    const int32_t* kept;
+    int kept_max, rows_per_kept;
+};
+
+GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
+                    const KeptRows& kr, int rows_role) {
     GemmProblem p{};
     p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
     p.A2 = A; p.B2 = B; p.lda2 = lda; p.ldb2 = ldb;
     p.M = M; p.N = N; p.K1 = K; p.K2 = 0; p.splits = 1;
+    p.kept = kr.kept; p.kept_max = kr.kept_max; p.rows_per_kept = kr.rows_per_kept; p.rows_role = rows_role;
     return p;
 }
 
@@ -145,6 +153,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     const bf16* Wu = static_cast<const bf16*>(io.Wu);
     const bf16* Wd = static_cast<const bf16*>(io.Wd);
     const bf16* Wo = static_cast<const bf16*>(io.Wo);
+    const KeptRows kr{io.n_kept, sh.max_chunks, sh.A};
 
     transpose(s, Wg, d, ff, w.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);   // [d, ff] -> packed rows of [2 ff, d]
     transpose(s, Wu, d, ff, w.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
@@ -154,17 +163,17 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     if (rc != PCM_OK) return rc;
     {
         StageTimer t(ST_GEMM_GATE_UP, s);
-        launch_gemm(problem(w.X, d, w.WguT, d, Mp, 2 * ff, d), EpiSwigluForward{w.u, w.v, w.a, ff}, s);
+        launch_gemm(problem(w.X, d, w.WguT, d, Mp, 2 * ff, d, kr, kRowsAreM), EpiSwigluForward{w.u, w.v, w.a, ff}, s);
     }
     {
         StageTimer t(ST_GEMM_DOWN, s);
-        launch_gemm(problem(w.a, ff, w.WdT, ff, Mp, d, ff), EpiStoreBf16{w.y, d, Mp}, s);
+        launch_gemm(problem(w.a, ff, w.WdT, ff, Mp, d, ff, kr, kRowsAreM), EpiStoreBf16{w.y, d, Mp}, s);
     }
     {
         StageTimer t(ST_GEMM_LOGITS_LOSS, s);
         EpiLogitsLoss epi{w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A,
                           io.eps_low, io.eps_high, io.loss_scale, bwd ? w.dz : nullptr, io.logp_out, w.out};
-        launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d), epi, s);
+        launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM), epi, s);
     }
     rc = launch_loss_reduce(sh, io, w.out, s);
     if (rc != PCM_OK) return rc;
@@ -172,17 +181,17 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
 
     {
         StageTimer t(ST_GEMM_DY, s);
-        launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
+        launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
     }
     if (grads) {
-        GemmProblem p = problem(w.y, d, w.dz, V, d, V, Mp);                                       // dWo = y^T dz
+        GemmProblem p = problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK);                                       // dWo = y^T dz
         p.splits = pick_splits((d / kTileM) * (V / kTileN), Mp / kTileK);
         if (p.splits > 1) zero(s, io.dWo, (size_t)d * V);
         StageTimer t(ST_GEMM_DWO, s);
         launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWo, V, p.splits > 1}, s);
     }
     if (grads) {
-        GemmProblem p = problem(w.a, ff, w.dy, d, ff, d, Mp);                                     // dWd = a^T dy
+        GemmProblem p = problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK);                                     // dWd = a^T dy
         p.splits = pick_splits((ff / kTileM) * (d / kTileN), Mp / kTileK);
         if (p.splits > 1) zero(s, io.dWd, (size_t)ff * d);
         StageTimer t(ST_GEMM_DWD, s);
@@ -190,10 +199,10 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     }
     {
         StageTimer t(ST_GEMM_DA, s);
-        launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
+        launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
     }
     if (grads) {
-        GemmProblem p = problem(w.X, d, w.u, ff, d, ff, Mp);                                      // dWg = X^T du
+        GemmProblem p = problem(w.X, d, w.u, ff, d, ff, Mp, kr, kRowsAreK);                                      // dWg = X^T du
         p.splits = pick_splits((d / kTileM) * (ff / kTileN), Mp / kTileK);
         if (p.splits > 1) {
             zero(s, io.dWg, (size_t)d * ff);
@@ -209,7 +218,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     }
     if (io.dX) {
         StageTimer t(ST_GEMM_DX, s);
-        GemmProblem p = problem(w.u, ff, Wg, ff, Mp, d, ff);                                      // dX = du Wg^T + dv Wu^T
+        GemmProblem p = problem(w.u, ff, Wg, ff, Mp, d, ff, kr, kRowsAreM);                                      // dX = du Wg^T + dv Wu^T
         p.A2 = w.v; p.B2 = Wu; p.lda2 = ff; p.ldb2 = ff; p.K2 = ff;
         launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX), d, (int)sh.rows_max()}, s);
     }

@@ -58,7 +58,14 @@ struct GemmProblem {
     int64_t lda, ldb, lda2, ldb2;
     int M, N, K1, K2;  // M, N multiples of 256; K1, K2 multiples of 64
     int splits;        // reduction split (grid multiplies by it); epilogue must combine partials
+    // Device-side row count: when `kept` is set, only the first min(*kept, kept_max) * rows_per_kept
+    // rows of the row dimension carry data.  rows_role says which GEMM dimension that is:
+    // kRowsAreM: row tiles entirely beyond the count exit at once; kRowsAreK: the reduction stops at
+    // the count rounded up to a whole step (rows up to there are valid, zero-padded).
+    const int32_t* kept;
+    int kept_max, rows_per_kept, rows_role;
 };
+enum RowsRole : int { kRowsUnused = 0, kRowsAreM = 1, kRowsAreK = 2 };
 
 // Accumulator coordinates.  For tile (i, j) of the wavefront and register e = 4 * q + t:
 //   row  m = m0 + wm * 128 + i * 32 + (lane & 31)
@@ -151,8 +158,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
     tile_of_workgroup(blockIdx.x % n_tiles, n_tiles, tiles_m, tiles_n, tm, tn);
     const int m0 = tm * kTileM, n0 = tn * kTileN;
 
+    int k1 = p.K1;
+    if (p.kept != nullptr) {
+        int nk = *p.kept;
+        nk = nk < 0 ? 0 : (nk > p.kept_max ? p.kept_max : nk);
+        const int rows = nk * p.rows_per_kept;
+        if (p.rows_role == kRowsAreM && m0 >= rows) return;      // the whole workgroup leaves, before any barrier
+        if (p.rows_role == kRowsAreK) k1 = min(k1, (rows + kTileK - 1) / kTileK * kTileK);
+    }
     // reduction range of this workgroup, in 64-wide steps over the concatenation of both segments
-    const int steps1 = p.K1 / kTileK, steps_all = steps1 + p.K2 / kTileK;
+    const int steps1 = k1 / kTileK, steps_all = steps1 + p.K2 / kTileK;
     const int per_split = (steps_all + p.splits - 1) / p.splits;
     const int step_begin = split * per_split;
     const int step_end = min(steps_all, step_begin + per_split);

@@ -187,6 +187,26 @@ def test_bf16_all_kept_and_forward_only(pcm):
         assert not zero[k].any()
 
 
+def test_bf16_short_kept_list_after_a_long_one(pcm):
+    """The kept count lives on the device: a call that keeps few chunks after one that kept many (same
+    buffers, same workspace) must not see anything the earlier call left behind in the skipped row tiles."""
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=4, N=16, K=4, B=10, d=256, ff=512, seed=14)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept_long, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, 14, 0)
+    assert len(kept_long) == 80                                  # 4480 rows = 18 row tiles
+    pr_long = make_problem(cfg, wstd=0.07, margin=0.08, kept=kept_long, old_rel=0.1)
+    ref_long, got_long = run_both(pcm, pr_long, torch_dtype=torch.bfloat16, max_kept=80)
+    check(ref_long, got_long, BF16_TOL, len(ref_long["rows"]), stats_tol=5e-2)
+    for n_short in (37, 5, 0):                                   # 9 tiles with a ragged tail, 2 tiles, none
+        pr = dict(pr_long, kept=kept_long[::2][:n_short].astype(np.int32))
+        ref, got = run_both(pcm, pr, torch_dtype=torch.bfloat16, max_kept=80)
+        if n_short:
+            check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2)
+        else:
+            assert got["loss"][0] == 0.0 and not any(got[k].any() for k in GRADS)
+
+
 @pytest.mark.timeout(900)
 def test_bf16_full_size_head_sampled_rows_and_one_group(pcm):
     """LIBERO-shaped head (d = 4096, ff = 11008) in the launch configuration the benchmark times.
