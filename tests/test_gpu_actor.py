@@ -294,3 +294,74 @@ def test_bf16_full_size_head_sampled_rows_and_one_group(pcm):
     for k in GRADS:
         assert rel(first[k], ref0[k]) <= BF16_TOL, (k, rel(first[k], ref0[k]))
     assert abs(first["loss"] - ref0["loss"]) <= BF16_TOL * max(1.0, abs(ref0["loss"]))
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
+def test_bf16_large_configs_chained_selection_and_sampled_rows(pcm, name):
+    """Larger-batch and skewed long-horizon instances at full size: the four calls chained on the GPU,
+    selection compared bit for bit, per-row outputs (logp, dX) of sampled kept chunks against the checker.
+    In the skewed instance a quarter of the groups have uniform rewards and are dropped at compaction."""
+    cfg = CONFIGS[name]
+    dv = torch.device("cuda")
+    ro = make_rollouts(cfg, 0)
+    adv_o, act_o = O.advantages(ro["reward"], cfg.G)
+    C_o, valid_o = O.phase_scores(ro["actions"], ro["phase"], ro["reward"], None, cfg.n_groups, cfg.G, cfg.K)
+    p_o = O.KeepProbState(cfg.K).update(C_o, valid_o)
+    kept_o, off_o, nk_o = O.sample_chunks(p_o, ro["phase"], None, act_o, cfg.B, cfg.seed, 0)
+    if name == "cfg5":
+        assert nk_o == (cfg.n_groups - cfg.n_groups // 4) * cfg.G * cfg.B     # collapsed groups keep nothing
+
+    phase = dev(ro["phase"])
+    C, valid, adv, act = pcm.pcm_score_phases(dev(ro["actions"]), phase, dev(ro["reward"]), None, cfg.n_groups,
+                                              cfg.G, cfg.K, 1e-6)
+    state = pcm.pcm_state_init(cfg.K, dv)
+    p = pcm.pcm_update_keep_probs(state, C, valid)
+    kept, off, nk = pcm.pcm_sample_chunks(p, phase, None, act, cfg.B, cfg.seed, 0)
+    torch.cuda.synchronize()
+    assert int(nk.item()) == nk_o and np.array_equal(kept.cpu().numpy()[:nk_o], kept_o)
+    assert np.array_equal(off.cpu().numpy(), off_o)
+
+    hidden = make_hidden_torch(cfg, dv)
+    W = make_head_torch(cfg, dv)
+    W_old = perturb_torch(cfg, W, std=0.002)
+    tokens = dev(ro["tokens"].reshape(-1))
+    args = (cfg.T, cfg.N, cfg.A)
+    zeros = torch.zeros(hidden.shape[0], device=dv)
+    old = pcm.grpo_masked_actor_step(hidden, tokens, zeros, adv, kept, nk, *args, W_old["Wg"], W_old["Wu"],
+                                     W_old["Wd"], W_old["Wo"], want_grads=False, want_dX=False)
+    rows_kept = (torch.from_numpy(kept_o.astype(np.int64))[:, None] * cfg.A + torch.arange(cfg.A)[None, :]).reshape(-1).to(dv)
+    logp_old = zeros
+    logp_old[rows_kept] = old["logp"][:nk_o * cfg.A]
+    del old
+
+    # sampled kept chunks, spread over the batch, for the checker
+    pick_pos = np.linspace(0, nk_o - 1, 8).astype(np.int64)
+    pick = kept_o[pick_pos]
+    rows_pick = (pick[:, None].astype(np.int64) * cfg.A + np.arange(cfg.A)[None, :]).reshape(-1)
+    ridx = torch.from_numpy(rows_pick).to(dv)
+    Wn = {k: v.float().cpu().numpy() for k, v in W.items()}
+    sub_hidden = hidden[ridx].float().cpu().numpy()
+    sub_tokens = ro["tokens"].reshape(-1)[rows_pick]
+    sub_adv = adv_o[pick // cfg.N]
+    lp_old = logp_old[ridx].cpu().numpy().astype(np.float64)
+    cur = O.actor_step(sub_hidden, sub_tokens, lp_old, sub_adv, np.arange(len(pick)), 1, cfg.A, Wn["Wg"], Wn["Wu"],
+                       Wn["Wd"], Wn["Wo"], want_grads=False)
+    lp_old = condition_logp_old(lp_old, cur["logp"], np.arange(len(rows_pick)), 0.2, 0.2, 0.08)
+    logp_old[ridx] = torch.from_numpy(lp_old.astype(np.float32)).to(dv)
+    lp_old = logp_old[ridx].cpu().numpy().astype(np.float64)
+
+    scale = 1.0 / cfg.T
+    out = pcm.grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept, nk, *args, W["Wg"], W["Wu"], W["Wd"], W["Wo"],
+                                     0.2, 0.2, scale)
+    torch.cuda.synchronize()
+    ref = O.actor_step(sub_hidden, sub_tokens, lp_old, sub_adv, np.arange(len(pick)), 1, cfg.A, Wn["Wg"], Wn["Wu"],
+                       Wn["Wd"], Wn["Wo"], 0.2, 0.2, scale)
+    sel = np.concatenate([np.arange(q * cfg.A, (q + 1) * cfg.A) for q in pick_pos])
+    sel_t = torch.from_numpy(sel).to(dv)
+    assert rel(out["logp"][sel_t].cpu().numpy(), ref["logp"]) <= BF16_TOL
+    assert rel(out["dX"][sel_t].float().cpu().numpy(), ref["dX"]) <= BF16_TOL
+    assert out["stats"][3].item() == nk_o * cfg.A
+    for k in GRADS:
+        g = out[k]
+        assert torch.isfinite(g).all() and g.abs().max().item() > 0
