@@ -159,6 +159,61 @@ def cpu_baseline(wl, kept_host, sample_chunks):
                       f"({len(rows)} of {rows_step} rows, {t_act:.2f} s), scaled linearly in rows"}
 
 
+def selection_only(cfg, dev, steps, warmup):
+    """Times the three selection calls alone (any configuration; no hidden states or weights needed)."""
+    import torch
+    import paper_2605_16154_amd as pcm
+    from workloads import make_rollouts
+    ro = make_rollouts(cfg, 0)
+    t = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    actions, phase, reward, n_chunks = t(ro["actions"]), t(ro["phase"]), t(ro["reward"]), t(ro["n_chunks"])
+    state = pcm.pcm_state_init(cfg.K, dev)
+    sel = samp = None
+
+    def one(step):
+        nonlocal sel, samp
+        sel = pcm.pcm_score_phases(actions, phase, reward, n_chunks, cfg.n_groups, cfg.G, cfg.K, 1e-6, out=sel)
+        p = pcm.pcm_update_keep_probs(state, sel[0], sel[1], 0.1, 5)
+        samp = pcm.pcm_sample_chunks(p, phase, n_chunks, sel[3], cfg.B, cfg.seed, step, out=samp)
+
+    for s in range(warmup):
+        one(s)
+    copy_dst = torch.empty_like(actions)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(steps):
+        copy_dst.copy_(actions)
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy_us = ev[0].elapsed_time(ev[1]) * 1e3 / steps
+    pcm.pcm_profile_enable(True)
+    t0 = time.perf_counter()
+    for s in range(warmup, warmup + steps):
+        one(s)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = pcm.pcm_profile_collect()
+    pcm.pcm_profile_enable(False)
+    n_kept = int(samp[2].item())
+    chunks = cfg.T * cfg.N
+    alg_bytes = {"score_accumulate": chunks * (cfg.A * 4 + 1) + cfg.T, "sample_compact": chunks + 4 * n_kept + 4 * cfg.T}
+    out = {}
+    for name, (ms, n) in stages.items():
+        if n == 0:
+            continue
+        us = ms / n * 1e3
+        out[name] = {"us_per_launch": us}
+        if name in alg_bytes:
+            out[name]["algorithmic_bytes"] = alg_bytes[name]
+            out[name]["GB_per_s"] = alg_bytes[name] / us / 1e3
+            out[name]["frac_of_8TBps"] = alg_bytes[name] / us / 1e3 / 8000.0
+    return {"workload": f"{cfg.name} selection only: T={cfg.T}, N={cfg.N}, K={cfg.K}, B={cfg.B}",
+            "us_per_selection_step_wall": dt / steps * 1e6, "kept_chunks": n_kept, "kernels": out,
+            "same_size_device_copy": {"bytes_each_way": actions.numel() * 4, "us": copy_us,
+                                      "GB_per_s": 2 * actions.numel() * 4 / copy_us / 1e3}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +223,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unmasked", action="store_true")
     ap.add_argument("--cpu-sample-chunks", type=int, default=192)
+    ap.add_argument("--selection-only", action="store_true",
+                    help="time only the three selection calls of --config and print their bytes and GB/s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -184,6 +241,9 @@ def main():
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
 
+    if args.selection_only:
+        print(json.dumps(selection_only(cfg, dev, max(args.steps, 50), args.warmup)))
+        return
     wl = Workload(cfg, dev, cfg.n_steps)
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.float64, device=dev)

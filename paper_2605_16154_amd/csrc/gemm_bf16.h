@@ -337,6 +337,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
 
 // ---- epilogues -------------------------------------------------------------------------------
 
+// 1 / (1 + e^-x) with the hardware exponential and reciprocal (about 1 ulp each; the results are
+// rounded to bf16 afterwards).
+__device__ inline float fast_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
+
 __device__ inline char* wave_stage(const TileCoord& tc, char* lds) {
     return lds + (tc.wm * 2 + tc.wn) * kWaveStageBytes;
 }
@@ -451,7 +455,7 @@ struct EpiSwigluForward {
                 auto vval = [&](int j, int e) { return (float)(__bf16)acc[i][j + 2][e]; };
                 auto aval = [&](int j, int e) {
                     const float x = uval(j, e);
-                    return x / (1.f + __expf(-x)) * vval(j, e);
+                    return x * fast_sigmoid(x) * vval(j, e);
                 };
                 stage_tile_row(st, kStride, tc.lane, lr, 0, 2, uval);
                 stage_tile_row(st, kStride, tc.lane, lr, 64, 2, vval);
@@ -511,7 +515,7 @@ struct EpiSwigluBackward {
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const float x = (float)u4[t], g = acc[i][j][4 * q + t];
-                            const float sg = 1.f / (1.f + __expf(-x));
+                            const float sg = fast_sigmoid(x);
                             du[t] = g * (float)v4[t] * (sg * (1.f + x * (1.f - sg)));
                             dv[t] = g * (x * sg);
                         }
