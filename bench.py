@@ -73,9 +73,9 @@ class Workload:
         for b in self.batches:
             b["logp_old"] = torch.empty(n_all * cfg.A, dtype=torch.float32, device=device)
             for c0 in range(0, n_all, per_call):
-                n = min(per_call, n_all - c0)
-                idx = torch.zeros(per_call, dtype=torch.int32, device=device)
-                idx[:n] = torch.arange(c0, c0 + n, dtype=torch.int32, device=device)
+                c0 = min(c0, n_all - per_call)          # the last call overlaps the previous one: all calls are full
+                n = per_call
+                idx = torch.arange(c0, c0 + n, dtype=torch.int32, device=device)
                 out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], zeros, adv0, idx,
                                                  torch.tensor([n], dtype=torch.int32, device=device), cfg.T, cfg.N,
                                                  cfg.A, W_old["Wg"], W_old["Wu"], W_old["Wd"], W_old["Wo"],
@@ -275,7 +275,7 @@ def main():
     dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
     dom_ms = stages[dominant][0] / stages[dominant][1]
     achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"gemm_bf16_nt ({dominant})", "achieved": achieved,
+    roofline = {"bound": "mfma", "kernel": f"gemm_bf16 ({dominant})", "achieved": achieved,
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": stored_traffic("gemm_gate_up_cfg2_traffic.txt") if cfg.name == "cfg2" else None,
                 "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,

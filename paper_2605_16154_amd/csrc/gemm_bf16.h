@@ -82,15 +82,22 @@ __device__ inline bf16x4 to_bf16x4(float a, float b, float c, float d) {
     return r;
 }
 
-#ifndef PCM_SWZ
-#define PCM_SWZ 0
-#endif
-__device__ inline int swizzle_piece(int row, int piece) {
-#if PCM_SWZ == 0
-    return piece ^ (row & 7);
-#else
-    return piece ^ ((row >> 1) & 7);
-#endif
+// LDS has 64 four-byte banks (256 B per cycle), so a 16-byte-per-lane read is served 16 lanes at a
+// time and a 128-byte tile row covers half the banks.  [rows][K] tiles: 16 consecutive rows must
+// fall on 16 different 16-byte columns of the 256-byte window, hence the XOR with row bits 1..3
+// (bit 0 already selects the half window).
+__device__ inline int swizzle_piece(int row, int piece) { return piece ^ ((row >> 1) & 7); }
+// [K][rows] tiles (512-byte k-rows, read by transpose reads of four k-rows x 32 bytes per 16 lanes,
+// 32 lanes per cycle): within a 16-lane group the four k-rows are spread by XOR with k & 3; the two
+// groups served together read the same k-rows at adjacent 32-byte units, so bits 0 and 2 of the
+// unit index are exchanged to put them in different half windows.  Self-inverse for fixed k.
+__device__ inline int swizzle_unit(int unit, int k_low2) {
+    const int swapped = ((unit & 1) << 2) | (unit & 2) | ((unit >> 2) & 1) | (unit & 8);
+    return swapped ^ k_low2;
+}
+__device__ inline int unswizzle_unit(int phys, int k_low2) {
+    const int t = phys ^ k_low2;
+    return ((t & 1) << 2) | (t & 2) | ((t >> 2) & 1) | (t & 8);
 }
 
 // Workgroup id -> (tile_m, tile_n).  Consecutive hardware workgroup ids go to different XCDs, each
@@ -177,10 +184,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
     // piece that belongs there).  Addresses are a wave-uniform base (tile origin + k offset) plus
     // a 32-bit per-lane byte offset.
     //   [rows][K] operand: the tile is [256 rows][128 B]; wave w fills rows [64 w, 64 w + 64), 8 rows
-    //     per load; piece p of row r sits in slot p ^ (r & 7).
+    //     per load; piece p of row r sits in slot swizzle_piece(r, p).
     //   [K][rows] operand: the tile is [64 k][512 B]; wave w fills k-rows [16 w, 16 w + 16), 2 per
-    //     load; the 32-byte unit u of k-row k sits in unit u ^ (k & 3), so the four k-rows touched
-    //     by one 16-lane transpose read fall into different banks.
+    //     load; the 32-byte unit u of k-row k sits in unit swizzle_unit(u, k & 3).
     const uint32_t lds_base = (uint32_t)(uintptr_t)PCM_AS_LDS(smem);
     struct LoadCtx {
         const char* base;        // wave-uniform
@@ -199,9 +205,12 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         const int layout = operand == 0 ? kLayA : kLayB;
         if (layout == kRowsByK) {
             const uint32_t row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);      // + 8 r for load r
-            const uint32_t piece = (uint32_t)swizzle_piece(lane >> 3, lane & 7);     // rows + 8 r share low bits
             c.base = reinterpret_cast<const char*>(ptr + (int64_t)row0 * ld + k0);
-            c.off[0] = c.off[1] = (row * ld + piece * 8u) * 2u;
+#pragma unroll
+            for (uint32_t odd = 0; odd < 2; ++odd) {                                 // the swizzle may use row bit 3
+                const uint32_t piece = (uint32_t)swizzle_piece((lane >> 3) + 8 * odd, lane & 7);
+                c.off[odd] = (row * ld + piece * 8u) * 2u;
+            }
             c.stride = 16u * ld;
         } else {
             const uint32_t krow = (uint32_t)wave * 16u + (uint32_t)(lane >> 5);      // + 2 r for load r
@@ -209,7 +218,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
 #pragma unroll
             for (uint32_t odd = 0; odd < 2; ++odd) {
                 const uint32_t k_low = 2u * odd + (uint32_t)(lane >> 5);             // (k-row of the load) & 3
-                const uint32_t piece = (uint32_t)(lane & 31) ^ (2u * k_low);
+                const uint32_t piece = 2u * (uint32_t)unswizzle_unit((lane & 31) >> 1, (int)k_low) + (uint32_t)(lane & 1);
                 c.off[odd] = (krow * ld + piece * 8u) * 2u;
             }
             c.stride = 4u * ld;
@@ -244,7 +253,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         const int g = lane >> 4, j = lane & 15;                    // 16-lane group, lane in group
         const int col0 = sub_row0 + i * 32 + (g & 1) * 16;         // this group's 16 rows of the operand
         const int k = ks * 16 + (g >> 1) * 8 + (j >> 2);           // k-row this lane's run starts in
-        return (uint32_t)(k * 512 + ((((col0 >> 4) ^ (j >> 2)) & 15) << 5) + ((j & 3) << 3));
+        return (uint32_t)(k * 512 + (swizzle_unit(col0 >> 4, j >> 2) << 5) + ((j & 3) << 3));
     };
     auto read_frag_pair = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks, int i) {
         const char* sa = reinterpret_cast<const char*>(smem) + slot_a * kTileBytes + frag_offset(kLayA, wm * 128, ks, i);
