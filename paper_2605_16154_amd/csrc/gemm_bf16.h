@@ -255,13 +255,19 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         const int k = ks * 16 + (g >> 1) * 8 + (j >> 2);           // k-row this lane's run starts in
         return (uint32_t)(k * 512 + (swizzle_unit(col0 >> 4, j >> 2) << 5) + ((j & 3) << 3));
     };
-    auto read_frag_pair = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks, int i) {
+    auto read_frag_a = [&](int set, uint32_t slot_a, int ks, int i) {
         const char* sa = reinterpret_cast<const char*>(smem) + slot_a * kTileBytes + frag_offset(kLayA, wm * 128, ks, i);
-        const char* sb = reinterpret_cast<const char*>(smem) + slot_b * kTileBytes + frag_offset(kLayB, wn * 128, ks, i);
         if (kLayA == kRowsByK) fa[set][i] = *reinterpret_cast<const bf16x8*>(sa);
         else fa[set][i] = read_transposed_fragment(sa);
-        if (kLayB == kRowsByK) fb[set][i] = *reinterpret_cast<const bf16x8*>(sb);
-        else fb[set][i] = read_transposed_fragment(sb);
+    };
+    auto read_frag_b = [&](int set, uint32_t slot_b, int ks, int j) {
+        const char* sb = reinterpret_cast<const char*>(smem) + slot_b * kTileBytes + frag_offset(kLayB, wn * 128, ks, j);
+        if (kLayB == kRowsByK) fb[set][j] = *reinterpret_cast<const bf16x8*>(sb);
+        else fb[set][j] = read_transposed_fragment(sb);
+    };
+    auto read_frag_pair = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks, int i) {
+        read_frag_a(set, slot_a, ks, i);
+        read_frag_b(set, slot_b, ks, i);
     };
     auto read_frags = [&](int set, uint32_t slot_a, uint32_t slot_b, int ks) {
 #pragma unroll
@@ -271,20 +277,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-    };
-    auto mfma_slice = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) mfma_row(set, i);
-    };
-    // scheduling hint for one slice: LDS reads (8, 12 or 16 depending on the layouts) spread over
-    // the 16 MFMAs
-    auto interleave_reads = [&]() {
-        constexpr int kReads = 4 * (1 + kLayA) + 4 * (1 + kLayB);
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x100, kReads / 8, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        }
     };
     auto next_slot = [](uint32_t s) { return s + 1u >= (uint32_t)kRingSlots ? s + 1u - kRingSlots : s + 1u; };
 
@@ -304,36 +296,47 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         // One 64-wide step per trip.  `sa`, `sb` are the slots of this step's tiles; the next step's
         // are the two after them in the ring.  Fragment set 0 holds slice 0 of this step on entry and
         // slice 0 of the next step on exit.  The single barrier sits before the last slice: by then
-        // every wavefront has issued all its reads of `sa`, `sb`, so both slots are refilled (with
-        // the B tile of step + 2 and the A tile of step + 3) in four groups between the MFMA rows of
-        // the last slice.  At the barrier only the newest tile (A of step + 2) may still be in
-        // flight, which keeps the load path busy across it.  The body is branch-free.
+        // every wavefront has issued all its reads of `sa`, `sb`, so both slots can be refilled, `sa`
+        // with the B tile of step + 2 and `sb` with the A tile of step + 3.  The 16 refill loads are
+        // not issued at once (four wavefronts doing so keep the texture path busy for about 1000
+        // cycles, and the MFMAs queued behind the loads wait): one load goes out per MFMA row, over
+        // the last slice of this step and the first three of the next.  At the barrier only the
+        // newest tile (the A tile) may still be in flight.  The body is branch-free: near the end it
+        // re-requests the last step's tiles, which nobody reads.
+        // One 16-wide slice: MFMA row g of fragment set `set`, and, ahead of it, one refill load and
+        // two fragment reads of the slice after (into the other set).  The B fragments come first:
+        // every row of the next slice needs all four, whereas A fragment g is only needed by its
+        // row g, so each read has at least two MFMA rows to land.
+        auto slice = [&](int set, const LoadCtx& c, uint32_t r0, uint32_t rs_a, uint32_t rs_b, int ks) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                issue_loads(c, r0 + g, 1);
+                if (g < 2) {
+                    read_frag_b(set ^ 1, rs_b, ks, 2 * g);
+                    read_frag_b(set ^ 1, rs_b, ks, 2 * g + 1);
+                } else {
+                    read_frag_a(set ^ 1, rs_a, ks, 2 * (g - 2));
+                    read_frag_a(set ^ 1, rs_a, ks, 2 * (g - 2) + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_row(set, g);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
         uint32_t sa = 0;
+        LoadCtx pend_b = load_ctx(0, 4, min(step_begin + 2, last));   // nothing pending yet: harmless re-request
+        LoadCtx pend_a = pend_b;
         for (int step = step_begin; step < step_end; ++step) {
             const uint32_t sb = next_slot(sa);
             const uint32_t na = next_slot(sb), nb = next_slot(na);
-            read_frags(1, sa, sb, 1);
-            mfma_slice(0);
-            interleave_reads();
-            read_frags(0, sa, sb, 2);
-            mfma_slice(1);
-            interleave_reads();
-            read_frags(1, sa, sb, 3);
-            mfma_slice(0);
-            interleave_reads();
+            slice(0, pend_b, 4, sa, sb, 1);
+            slice(1, pend_a, 0, sa, sb, 2);
+            slice(0, pend_a, 4, sa, sb, 3);
             wait_direct_loads<kLoadsPerTile>();
             __syncthreads();
-            const LoadCtx cb = load_ctx(1, sa, min(step + 2, last));   // tile 2 s + 5 -> slot of tile 2 s
-            const LoadCtx ca = load_ctx(0, sb, min(step + 3, last));   // tile 2 s + 6 -> slot of tile 2 s + 1
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                if (g < 2) issue_loads(cb, 4 * g, 4);
-                else issue_loads(ca, 4 * (g - 2), 4);
-                read_frag_pair(0, na, nb, 0, g);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_row(1, g);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            pend_b = load_ctx(1, sa, min(step + 2, last));   // tile 2 s + 5 -> slot of tile 2 s
+            pend_a = load_ctx(0, sb, min(step + 3, last));   // tile 2 s + 6 -> slot of tile 2 s + 1
+            slice(1, pend_b, 0, na, nb, 0);
             sa = na;
         }
         wait_direct_loads<0>();
