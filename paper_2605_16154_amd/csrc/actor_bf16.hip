@@ -131,7 +131,7 @@ GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int 
                     const KeptRows& kr, int rows_role) {
     GemmProblem p{};
     p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
-    p.A2 = A; p.B2 = B; p.lda2 = lda; p.ldb2 = ldb;
+    p.A2 = A; p.B2 = B;
     p.M = M; p.N = N; p.K1 = K; p.K2 = 0; p.splits = 1;
     p.kept = kr.kept; p.kept_max = kr.kept_max; p.rows_per_kept = kr.rows_per_kept; p.rows_role = rows_role;
     return p;
@@ -219,7 +219,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     if (io.dX) {
         StageTimer t(ST_GEMM_DX, s);
         GemmProblem p = problem(w.u, ff, Wg, ff, Mp, d, ff, kr, kRowsAreM);                                      // dX = du Wg^T + dv Wu^T
-        p.A2 = w.v; p.B2 = Wu; p.lda2 = ff; p.ldb2 = ff; p.K2 = ff;
+        p.A2 = w.v; p.B2 = Wu; p.K2 = ff;
         launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX), d, (int)sh.rows_max()}, s);
     }
     return launch_status();

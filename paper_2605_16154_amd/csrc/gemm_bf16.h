@@ -53,9 +53,9 @@ static_assert(4 * kWaveStageBytes <= kSmemBytes, "epilogue staging must fit in t
 struct GemmProblem {
     const bf16* A;    // M x K1 operand, leading dimension lda (layout given by the kernel's template arguments)
     const bf16* B;    // N x K1 operand, leading dimension ldb
-    const bf16* A2;   // optional second reduction segment (same M, N), K2 columns
-    const bf16* B2;
-    int64_t lda, ldb, lda2, ldb2;
+    const bf16* A2;   // optional second reduction segment (same M, N, layouts and leading dimensions), K2 columns;
+    const bf16* B2;   // when K2 == 0 both must still point at valid operands (A, B)
+    int64_t lda, ldb;
     int M, N, K1, K2;  // M, N multiples of 256; K1, K2 multiples of 64
     int splits;        // reduction split (grid multiplies by it); epilogue must combine partials
     // Device-side row count: when `kept` is set, only the first min(*kept, kept_max) * rows_per_kept
@@ -194,38 +194,57 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         uint32_t stride;         // bytes between consecutive loads
         uint32_t dst;            // LDS byte address of this wave's part of the slot
     };
-    // operand 0 = A rows m0.., operand 1 = B rows n0..
-    auto load_ctx = [&](int operand, uint32_t slot, int step) {
-        LoadCtx c;
-        const bool seg1 = step < steps1;
-        const bf16* ptr = operand == 0 ? (seg1 ? p.A : p.A2) : (seg1 ? p.B : p.B2);
-        const uint32_t ld = (uint32_t)(operand == 0 ? (seg1 ? p.lda : p.lda2) : (seg1 ? p.ldb : p.ldb2));
-        const int k0 = (seg1 ? step : step - steps1) * kTileK;
+    // operand 0 = A rows m0.., operand 1 = B rows n0..  Per-lane offsets do not depend on the step; the
+    // tile origin is a wave-uniform pointer that walks along k.
+    uint32_t lane_off[2][2], load_stride[2];
+    const char* seg_origin[2][2];          // [operand][segment]: this tile's bytes at k = 0 of the segment
+    int64_t k_step_bytes[2];               // distance between consecutive steps
+#pragma unroll
+    for (int operand = 0; operand < 2; ++operand) {
+        const uint32_t ld = (uint32_t)(operand == 0 ? p.lda : p.ldb);
         const int row0 = operand == 0 ? m0 : n0;
         const int layout = operand == 0 ? kLayA : kLayB;
+        const bf16* s1 = operand == 0 ? p.A : p.B;
+        const bf16* s2 = operand == 0 ? p.A2 : p.B2;
         if (layout == kRowsByK) {
             const uint32_t row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);      // + 8 r for load r
-            c.base = reinterpret_cast<const char*>(ptr + (int64_t)row0 * ld + k0);
 #pragma unroll
             for (uint32_t odd = 0; odd < 2; ++odd) {                                 // the swizzle may use row bit 3
                 const uint32_t piece = (uint32_t)swizzle_piece((lane >> 3) + 8 * odd, lane & 7);
-                c.off[odd] = (row * ld + piece * 8u) * 2u;
+                lane_off[operand][odd] = (row * ld + piece * 8u) * 2u;
             }
-            c.stride = 16u * ld;
+            load_stride[operand] = 16u * ld;
+            seg_origin[operand][0] = reinterpret_cast<const char*>(s1 + (int64_t)row0 * ld);
+            seg_origin[operand][1] = reinterpret_cast<const char*>(s2 + (int64_t)row0 * ld);
+            k_step_bytes[operand] = kTileK * 2;
         } else {
             const uint32_t krow = (uint32_t)wave * 16u + (uint32_t)(lane >> 5);      // + 2 r for load r
-            c.base = reinterpret_cast<const char*>(ptr + (int64_t)k0 * ld + row0);
 #pragma unroll
             for (uint32_t odd = 0; odd < 2; ++odd) {
                 const uint32_t k_low = 2u * odd + (uint32_t)(lane >> 5);             // (k-row of the load) & 3
                 const uint32_t piece = 2u * (uint32_t)unswizzle_unit((lane & 31) >> 1, (int)k_low) + (uint32_t)(lane & 1);
-                c.off[odd] = (krow * ld + piece * 8u) * 2u;
+                lane_off[operand][odd] = (krow * ld + piece * 8u) * 2u;
             }
-            c.stride = 4u * ld;
+            load_stride[operand] = 4u * ld;
+            seg_origin[operand][0] = reinterpret_cast<const char*>(s1 + row0);
+            seg_origin[operand][1] = reinterpret_cast<const char*>(s2 + row0);
+            k_step_bytes[operand] = (int64_t)kTileK * ld * 2;
         }
+    }
+    auto tile_origin = [&](int operand, int step) {
+        const bool seg1 = step < steps1;
+        return seg_origin[operand][seg1 ? 0 : 1] + (int64_t)(seg1 ? step : step - steps1) * k_step_bytes[operand];
+    };
+    auto load_ctx_at = [&](int operand, uint32_t slot, const char* origin) {
+        LoadCtx c;
+        c.base = origin;
+        c.off[0] = lane_off[operand][0];
+        c.off[1] = lane_off[operand][1];
+        c.stride = load_stride[operand];
         c.dst = lds_base + slot * kTileBytes + (uint32_t)wave * 8192u;
         return c;
     };
+    auto load_ctx = [&](int operand, uint32_t slot, int step) { return load_ctx_at(operand, slot, tile_origin(operand, step)); };
     auto issue_loads = [&](const LoadCtx& c, uint32_t r0, uint32_t n) {
 #pragma unroll
         for (uint32_t r = r0; r < r0 + n; ++r) direct_load_16B(c.base, c.off[r & 1u] + r * c.stride, c.dst + r * 1024u);
@@ -273,11 +292,6 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
 #pragma unroll
         for (int i = 0; i < 4; ++i) read_frag_pair(set, slot_a, slot_b, ks, i);
     };
-    auto mfma_row = [&](int set, int i) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-    };
     auto next_slot = [](uint32_t s) { return s + 1u >= (uint32_t)kRingSlots ? s + 1u - kRingSlots : s + 1u; };
 
     if (step_begin < step_end) {
@@ -297,46 +311,83 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         // are the two after them in the ring.  Fragment set 0 holds slice 0 of this step on entry and
         // slice 0 of the next step on exit.  The single barrier sits before the last slice: by then
         // every wavefront has issued all its reads of `sa`, `sb`, so both slots can be refilled, `sa`
-        // with the B tile of step + 2 and `sb` with the A tile of step + 3.  The 16 refill loads are
-        // not issued at once (four wavefronts doing so keep the texture path busy for about 1000
-        // cycles, and the MFMAs queued behind the loads wait): one load goes out per MFMA row, over
-        // the last slice of this step and the first three of the next.  At the barrier only the
+        // with the B tile of step + 2 and `sb` with the A tile of step + 3.  At the barrier only the
         // newest tile (the A tile) may still be in flight.  The body is branch-free: near the end it
-        // re-requests the last step's tiles, which nobody reads.
-        // One 16-wide slice: MFMA row g of fragment set `set`, and, ahead of it, one refill load and
-        // two fragment reads of the slice after (into the other set).  The B fragments come first:
-        // every row of the next slice needs all four, whereas A fragment g is only needed by its
-        // row g, so each read has at least two MFMA rows to land.
-        auto slice = [&](int set, const LoadCtx& c, uint32_t r0, uint32_t rs_a, uint32_t rs_b, int ks) {
+        // re-requests tiles that nobody reads.
+        //
+        // A wavefront issues in order and an MFMA keeps the matrix pipe busy for 32 cycles, so
+        // whatever is issued between two MFMAs must fit in about 28 cycles or the pipe idles.  The
+        // order is therefore fixed by hand, one memory instruction per gap: per MFMA row of a 16-wide
+        // slice, one refill load (16 per step, one per row: issued together they would hold the
+        // texture path for about 1000 cycles) and up to three fragment reads of the next slice.  The
+        // last row has no reads, so that the reads of a slot have long landed when the barrier that
+        // frees the slot waits for them; its gaps carry the scalar bookkeeping of the tile pointers.
+        auto one_mfma = [&](int set, int i, int j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+        };
+        // Reads of the next slice in the order its MFMAs need them: B0, B1, B2, A0, B3 for the first
+        // row, then A1..A3.
+        auto read_next = [&](int set, uint32_t rs_a, uint32_t rs_b, int ks, int n) {
+            if (n < 3) read_frag_b(set, rs_b, ks, n);
+            else if (n == 3) read_frag_a(set, rs_a, ks, 0);
+            else if (n == 4) read_frag_b(set, rs_b, ks, 3);
+            else if (n < 8) read_frag_a(set, rs_a, ks, n - 4);
+        };
+        auto slice = [&](int set, const LoadCtx& c, uint32_t half, uint32_t rs_a, uint32_t rs_b, int ks, auto hook) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                issue_loads(c, r0 + g, 1);
-                if (g < 2) {
-                    read_frag_b(set ^ 1, rs_b, ks, 2 * g);
-                    read_frag_b(set ^ 1, rs_b, ks, 2 * g + 1);
-                } else {
-                    read_frag_a(set ^ 1, rs_a, ks, 2 * (g - 2));
-                    read_frag_a(set ^ 1, rs_a, ks, 2 * (g - 2) + 1);
-                }
+                one_mfma(set, g, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_row(set, g);
+                issue_loads(c, half * 4 + g, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                one_mfma(set, g, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g < 3) read_next(set ^ 1, rs_a, rs_b, ks, 3 * g);
+                __builtin_amdgcn_sched_barrier(0);
+                one_mfma(set, g, 2);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g < 3) read_next(set ^ 1, rs_a, rs_b, ks, 3 * g + 1);
+                else hook(0);
+                __builtin_amdgcn_sched_barrier(0);
+                one_mfma(set, g, 3);
+                __builtin_amdgcn_sched_barrier(0);
+                if (g < 3) read_next(set ^ 1, rs_a, rs_b, ks, 3 * g + 2);
+                else hook(1);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         uint32_t sa = 0;
         LoadCtx pend_b = load_ctx(0, 4, min(step_begin + 2, last));   // nothing pending yet: harmless re-request
         LoadCtx pend_a = pend_b;
+        // tile streams: origin of the newest tile requested so far of each operand, and its step
+        int at_a = min(step_begin + 2, last), at_b = min(step_begin + 1, last);
+        const char* origin_a = tile_origin(0, at_a);
+        const char* origin_b = tile_origin(1, at_b);
+        auto no_hook = [](int) {};
+        // The step counters run on past `last` (the origin then stands still, or lands once on the
+        // start of the second segment, which is valid memory whether or not that segment is used).
+        auto advance = [&](int operand) {
+            if (operand == 0) {
+                at_a += 1;
+                origin_a += at_a <= last ? k_step_bytes[0] : (int64_t)0;
+                origin_a = at_a == steps1 ? seg_origin[0][1] : origin_a;
+            } else {
+                at_b += 1;
+                origin_b += at_b <= last ? k_step_bytes[1] : (int64_t)0;
+                origin_b = at_b == steps1 ? seg_origin[1][1] : origin_b;
+            }
+        };
         for (int step = step_begin; step < step_end; ++step) {
             const uint32_t sb = next_slot(sa);
             const uint32_t na = next_slot(sb), nb = next_slot(na);
-            slice(0, pend_b, 4, sa, sb, 1);
-            slice(1, pend_a, 0, sa, sb, 2);
-            slice(0, pend_a, 4, sa, sb, 3);
+            slice(0, pend_b, 1, sa, sb, 1, no_hook);
+            slice(1, pend_a, 0, sa, sb, 2, no_hook);
+            slice(0, pend_a, 1, sa, sb, 3, advance);
             wait_direct_loads<kLoadsPerTile>();
             __syncthreads();
-            pend_b = load_ctx(1, sa, min(step + 2, last));   // tile 2 s + 5 -> slot of tile 2 s
-            pend_a = load_ctx(0, sb, min(step + 3, last));   // tile 2 s + 6 -> slot of tile 2 s + 1
-            slice(1, pend_b, 0, na, nb, 0);
+            pend_b = load_ctx_at(1, sa, origin_b);   // tile 2 s + 5 -> slot of tile 2 s
+            pend_a = load_ctx_at(0, sb, origin_a);   // tile 2 s + 6 -> slot of tile 2 s + 1
+            slice(1, pend_b, 0, na, nb, 0, no_hook);
             sa = na;
         }
         wait_direct_loads<0>();
@@ -374,6 +425,52 @@ __device__ inline void stage_tile_row(char* stage, int stride, int lane, int loc
     }
 }
 
+// Staging area -> global memory, 16 bytes per lane: kRowBytes / 16 lanes cover one row, so a pass moves
+// 1024 / kRowBytes rows and a 16-lane group writes whole 128-byte lines.  `dst` is this lane's address
+// in row 0; rows at and beyond n_rows (wave-uniform) are not written.  Staging rows are 8-byte aligned
+// only (their stride keeps the 8-byte writes of stage_tile_row conflict-free), hence two 8-byte reads.
+template <int kRows, int kRowBytes>
+__device__ inline void copy_rows_out(const char* st, int stride, char* dst, int64_t ld_bytes, int n_rows, int lane) {
+    constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
+    const char* src = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+    char* out = dst + (lane / kLanesPerRow) * ld_bytes + (lane % kLanesPerRow) * 16;
+    const int64_t out_step = kRowsPerPass * ld_bytes;
+    if (n_rows >= kRows) {
+#pragma unroll 8
+        for (int pass = 0; pass < kRows / kRowsPerPass; ++pass) {
+            const uint2 lo = *reinterpret_cast<const uint2*>(src), hi = *reinterpret_cast<const uint2*>(src + 8);
+            *reinterpret_cast<uint4*>(out) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            src += kRowsPerPass * stride;
+            out += out_step;
+        }
+    } else {
+        int r = lane / kLanesPerRow;
+        for (int pass = 0; pass < kRows / kRowsPerPass && pass * kRowsPerPass < n_rows; ++pass) {
+            const uint2 lo = *reinterpret_cast<const uint2*>(src), hi = *reinterpret_cast<const uint2*>(src + 8);
+            if (r < n_rows) *reinterpret_cast<uint4*>(out) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            src += kRowsPerPass * stride;
+            out += out_step;
+            r += kRowsPerPass;
+        }
+    }
+}
+// Global memory -> staging area, the mirror image of copy_rows_out (all kRows rows).
+template <int kRows, int kRowBytes>
+__device__ inline void copy_rows_in(char* st, int stride, const char* src_row0, int64_t ld_bytes, int lane) {
+    constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
+    char* dst = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+    const char* in = src_row0 + (lane / kLanesPerRow) * ld_bytes + (lane % kLanesPerRow) * 16;
+    const int64_t in_step = kRowsPerPass * ld_bytes;
+#pragma unroll 8
+    for (int pass = 0; pass < kRows / kRowsPerPass; ++pass) {
+        const uint4 v = *reinterpret_cast<const uint4*>(in);
+        *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.y);
+        *reinterpret_cast<uint2*>(dst + 8) = make_uint2(v.z, v.w);
+        dst += kRowsPerPass * stride;
+        in += in_step;
+    }
+}
+
 // C (bf16, row-major) = acc; rows at and beyond row_limit are not written.
 struct EpiStoreBf16 {
     bf16* C;
@@ -388,13 +485,8 @@ struct EpiStoreBf16 {
                            [&](int j, int e) { return acc[i][j][e]; });
         __builtin_amdgcn_wave_barrier();
         const int row_base = tc.m0 + tc.wm * 128, col_base = tc.n0 + tc.wn * 128;
-#pragma unroll 8
-        for (int it = 0; it < 64; ++it) {                  // two rows of 256 bytes per pass
-            const int r = 2 * it + (tc.lane >> 5);
-            const uint2 v = *reinterpret_cast<const uint2*>(st + r * kStride + (tc.lane & 31) * 8);
-            if (row_base + r < row_limit)
-                *reinterpret_cast<uint2*>(C + (int64_t)(row_base + r) * ldc + col_base + (tc.lane & 31) * 4) = v;
-        }
+        copy_rows_out<128, 256>(st, kStride, reinterpret_cast<char*>(C + (int64_t)row_base * ldc + col_base), ldc * 2,
+                                row_limit - row_base, tc.lane);
     }
 };
 
@@ -434,12 +526,7 @@ struct EpiAccumulateF32 {
                 }
             __builtin_amdgcn_wave_barrier();
             const int row_base = tc.m0 + tc.wm * 128 + i * 32;
-#pragma unroll 4
-            for (int it = 0; it < 16; ++it) {              // two rows of 512 bytes per pass
-                const int r = 2 * it + (tc.lane >> 5);
-                const f32x4 v = *reinterpret_cast<const f32x4*>(st + r * kStride + (tc.lane & 31) * 16);
-                *reinterpret_cast<f32x4*>(C + (int64_t)(row_base + r) * ldc + col_base + (tc.lane & 31) * 4) = v;
-            }
+            copy_rows_out<32, 512>(st, kStride, reinterpret_cast<char*>(C + (int64_t)row_base * ldc + col_base), ldc * 4, 32, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
@@ -475,14 +562,10 @@ struct EpiSwigluForward {
             }
             __builtin_amdgcn_wave_barrier();
             const int row_base = tc.m0 + tc.wm * 128 + half * 64;
-#pragma unroll 8
-            for (int it = 0; it < 48; ++it) {              // 64 rows x 48 eight-byte pieces
-                const int idx = it * 64 + tc.lane;
-                const int r = idx / 48, piece = idx % 48;
-                const uint2 val = *reinterpret_cast<const uint2*>(st + r * kStride + piece * 8);
-                bf16* dst = outs[piece / 16];
-                *reinterpret_cast<uint2*>(dst + (int64_t)(row_base + r) * ld + col_base + (piece % 16) * 4) = val;
-            }
+#pragma unroll
+            for (int o = 0; o < 3; ++o)                    // 64 rows x 128 bytes of each output
+                copy_rows_out<64, 128>(st + o * 128, kStride, reinterpret_cast<char*>(outs[o] + (int64_t)row_base * ld + col_base),
+                                       ld * 2, 64, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
@@ -500,15 +583,8 @@ struct EpiSwigluBackward {
         for (int half = 0; half < 2; ++half) {             // 64 rows per pass
             const int row_base = tc.m0 + tc.wm * 128 + half * 64;
             // bring u, v of the 64 x 128 block in as whole lines
-#pragma unroll 8
-            for (int it = 0; it < 64; ++it) {
-                const int r = it;
-                const int piece = tc.lane;                 // 64 pieces of 8 bytes: u 32, v 32
-                const bf16* src = piece < 32 ? u : v;
-                const uint2 val = *reinterpret_cast<const uint2*>(src + (int64_t)(row_base + r) * ld + col_base +
-                                                                  (piece & 31) * 4);
-                *reinterpret_cast<uint2*>(st + r * kStride + piece * 8) = val;
-            }
+            copy_rows_in<64, 256>(st, kStride, reinterpret_cast<const char*>(u + (int64_t)row_base * ld + col_base), ld * 2, tc.lane);
+            copy_rows_in<64, 256>(st + 256, kStride, reinterpret_cast<const char*>(v + (int64_t)row_base * ld + col_base), ld * 2, tc.lane);
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii) {
@@ -536,14 +612,8 @@ struct EpiSwigluBackward {
                     }
             }
             __builtin_amdgcn_wave_barrier();
-#pragma unroll 8
-            for (int it = 0; it < 64; ++it) {
-                const int r = it;
-                const int piece = tc.lane;
-                bf16* dst = piece < 32 ? u : v;
-                const uint2 val = *reinterpret_cast<const uint2*>(st + r * kStride + piece * 8);
-                *reinterpret_cast<uint2*>(dst + (int64_t)(row_base + r) * ld + col_base + (piece & 31) * 4) = val;
-            }
+            copy_rows_out<64, 256>(st, kStride, reinterpret_cast<char*>(u + (int64_t)row_base * ld + col_base), ld * 2, 64, tc.lane);
+            copy_rows_out<64, 256>(st + 256, kStride, reinterpret_cast<char*>(v + (int64_t)row_base * ld + col_base), ld * 2, 64, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
