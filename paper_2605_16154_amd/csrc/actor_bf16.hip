@@ -3,8 +3,9 @@
 // Forward:  X -> [gate|up] GEMM with silu(u)*v fused -> down GEMM -> logit GEMM with the
 //           log-softmax / ratio / clipped surrogate / dz fused.
 // Backward: dy = dz Wo^T; da = dy Wd^T with the gated-activation derivative fused (du, dv
-//           overwrite u, v); weight gradients as split reductions over the row dimension with
-//           fp32 atomics; dX = du Wg^T + dv Wu^T as one GEMM over two reduction segments.
+//           overwrite u, v); weight gradients reduce over the row dimension (a small output, dWo,
+//           as partial products over slices of the rows, summed afterwards: no atomics);
+//           dX = du Wg^T + dv Wu^T as one GEMM over two reduction segments.
 //
 // The forward and input-gradient products take both operands reduction-contiguous; for the forward
 // pass the [in, out] weights are first copied transposed (gate and up interleaved in blocks of 64
@@ -19,6 +20,7 @@ namespace pcm {
 namespace {
 
 constexpr int kPackNone = 0, kPackGate = 1, kPackUp = 2;
+constexpr size_t kMaxSplitTiles = 256;   // tiles x parts of a split reduction: one workgroup per CU
 
 __device__ inline int packed_row(int c, int mode) {
     if (mode == kPackNone) return c;
@@ -58,23 +60,24 @@ void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t 
                                         reinterpret_cast<uint16_t*>(dst), ld_dst, mode);
 }
 
-__global__ void fill_zero_f32(float* p, size_t n) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
-}
-
-void zero(hipStream_t s, float* p, size_t n) {
-    StageTimer t(ST_ZERO_FILL, s);
-    size_t blocks = (n + 1023) / 1024;
-    if (blocks > 4096) blocks = 4096;
-    if (blocks < 1) blocks = 1;
-    fill_zero_f32<<<(unsigned)blocks, 256, 0, s>>>(p, n);
+// out[i] = sum over the parts of a split reduction (n is a multiple of 4; parts are n floats apart).
+__global__ void sum_parts_f32(const float* parts, int n_parts, size_t n, float* out) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+        float4 acc = *reinterpret_cast<const float4*>(parts + i);
+        for (int s = 1; s < n_parts; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(parts + (size_t)s * n + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(out + i) = acc;
+    }
 }
 
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
     bf16 *X, *u, *v, *a, *y, *dz;
     bf16* dy;
+    float* parts;   // partial products of split reductions
     RowMeta meta;
     RowOut out;
     int64_t Mp;
@@ -104,18 +107,18 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     w.out.dlogp = c.take<float>(Mp);
     w.out.clipped = c.take<uint8_t>(Mp);
     if (bwd) w.dy = c.take<bf16>(Mp * d);
-    (void)grads;
+    if (grads) w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
     w.bytes = c.used();
     return w;
 }
 
 // Reduction split for an output of `tiles` tiles and `steps` 64-wide reduction steps.  An output
-// that already covers the 256 CUs is not split (partial sums would have to be combined with
-// atomics, which costs more than the idle tail of the last round); a small output is split so that
-// tiles * splits fills the chip, keeping at least 8 steps per workgroup.
+// that already covers the 256 CUs is not split; a small output is split so that tiles * splits
+// fills the chip (and never exceeds kMaxSplitTiles, which sizes the buffer of partial products),
+// keeping at least 8 steps per workgroup.
 int pick_splits(int tiles, int steps) {
     if (tiles >= 256) return 1;
-    int s = 256 / tiles;
+    int s = (int)kMaxSplitTiles / tiles;
     const int max_s = steps / 8 > 0 ? steps / 8 : 1;
     if (s > max_s) s = max_s;
     return s < 1 ? 1 : s;
@@ -126,6 +129,22 @@ struct KeptRows {
     const int32_t* kept;
     int kept_max, rows_per_kept;
 };
+
+// Weight gradient C[M, N] (fp32) = A^T B over the kept rows, both operands stored [rows][features].  A small
+// output is computed as several partial products over slices of the rows, summed by a second kernel.
+void launch_weight_grad(GemmProblem p, float* C, float* parts, int stage, hipStream_t s) {
+    p.splits = pick_splits((p.M / kTileM) * (p.N / kTileN), p.K1 / kTileK);
+    StageTimer t(stage, s);
+    if (p.splits == 1) {
+        launch_gemm<kKByRows, kKByRows>(p, EpiStoreF32{C, p.N, 0}, s);
+        return;
+    }
+    const size_t n = (size_t)p.M * p.N;
+    launch_gemm<kKByRows, kKByRows>(p, EpiStoreF32{parts, p.N, (int64_t)n}, s);
+    size_t blocks = (n / 4 + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    sum_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C);
+}
 
 GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
                     const KeptRows& kr, int rows_role) {
@@ -184,37 +203,16 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
     }
     if (grads) {
-        GemmProblem p = problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK);                                       // dWo = y^T dz
-        p.splits = pick_splits((d / kTileM) * (V / kTileN), Mp / kTileK);
-        if (p.splits > 1) zero(s, io.dWo, (size_t)d * V);
-        StageTimer t(ST_GEMM_DWO, s);
-        launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWo, V, p.splits > 1}, s);
-    }
-    if (grads) {
-        GemmProblem p = problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK);                                     // dWd = a^T dy
-        p.splits = pick_splits((ff / kTileM) * (d / kTileN), Mp / kTileK);
-        if (p.splits > 1) zero(s, io.dWd, (size_t)ff * d);
-        StageTimer t(ST_GEMM_DWD, s);
-        launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWd, d, p.splits > 1}, s);
+        launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, ST_GEMM_DWO, s);   // dWo = y^T dz
+        launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, ST_GEMM_DWD, s); // dWd = a^T dy
     }
     {
         StageTimer t(ST_GEMM_DA, s);
         launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
     }
     if (grads) {
-        GemmProblem p = problem(w.X, d, w.u, ff, d, ff, Mp, kr, kRowsAreK);                                      // dWg = X^T du
-        p.splits = pick_splits((d / kTileM) * (ff / kTileN), Mp / kTileK);
-        if (p.splits > 1) {
-            zero(s, io.dWg, (size_t)d * ff);
-            zero(s, io.dWu, (size_t)d * ff);
-        }
-        {
-            StageTimer t(ST_GEMM_DWG_DWU, s);
-            launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWg, ff, p.splits > 1}, s);
-        }
-        p.B = w.v;                                                                                // dWu = X^T dv
-        StageTimer t(ST_GEMM_DWG_DWU, s);
-        launch_gemm<kKByRows, kKByRows>(p, EpiAccumulateF32{io.dWu, ff, p.splits > 1}, s);
+        launch_weight_grad(problem(w.X, d, w.u, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, ST_GEMM_DWG_DWU, s);   // dWg = X^T du
+        launch_weight_grad(problem(w.X, d, w.v, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, ST_GEMM_DWG_DWU, s);   // dWu = X^T dv
     }
     if (io.dX) {
         StageTimer t(ST_GEMM_DX, s);

@@ -72,6 +72,7 @@ enum RowsRole : int { kRowsUnused = 0, kRowsAreM = 1, kRowsAreK = 2 };
 //   col  n = n0 + wn * 128 + j * 32 + 8 * q + 4 * (lane >> 5) + t
 struct TileCoord {
     int m0, n0, wm, wn, lane;
+    int split;   // which part of a split reduction this workgroup computed
     __device__ int row(int i) const { return m0 + wm * 128 + i * 32 + (lane & 31); }
     __device__ int col(int j, int q) const { return n0 + wn * 128 + j * 32 + 8 * q + 4 * (lane >> 5); }
 };
@@ -394,7 +395,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         __syncthreads();
     }
 
-    TileCoord tc{m0, n0, wm, wn, lane};
+    TileCoord tc{m0, n0, wm, wn, lane, split};
     epi(tc, acc, reinterpret_cast<char*>(smem));
 }
 
@@ -454,22 +455,27 @@ __device__ inline void copy_rows_out(const char* st, int stride, char* dst, int6
         }
     }
 }
-// Global memory -> staging area, the mirror image of copy_rows_out (all kRows rows).
+// Global memory -> staging area, the mirror image of copy_rows_out (all kRows rows), in two halves so
+// that the loads can be in flight while other work runs: fetch_rows issues them into registers,
+// stash_rows writes the registers to the staging area.
 template <int kRows, int kRowBytes>
-__device__ inline void copy_rows_in(char* st, int stride, const char* src_row0, int64_t ld_bytes, int lane) {
-    constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
-    char* dst = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
-    const char* in = src_row0 + (lane / kLanesPerRow) * ld_bytes + (lane % kLanesPerRow) * 16;
-    const int64_t in_step = kRowsPerPass * ld_bytes;
-#pragma unroll 8
-    for (int pass = 0; pass < kRows / kRowsPerPass; ++pass) {
-        const uint4 v = *reinterpret_cast<const uint4*>(in);
-        *reinterpret_cast<uint2*>(dst) = make_uint2(v.x, v.y);
-        *reinterpret_cast<uint2*>(dst + 8) = make_uint2(v.z, v.w);
-        dst += kRowsPerPass * stride;
-        in += in_step;
+struct RowFetch {
+    static constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow, kPasses = kRows / kRowsPerPass;
+    uint4 r[kPasses];
+    __device__ void fetch_rows(const char* src_row0, int64_t ld_bytes, int lane) {
+        const char* in = src_row0 + (lane / kLanesPerRow) * ld_bytes + (lane % kLanesPerRow) * 16;
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass) r[pass] = *reinterpret_cast<const uint4*>(in + pass * kRowsPerPass * ld_bytes);
     }
-}
+    __device__ void stash_rows(char* st, int stride, int lane) const {
+        char* dst = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass) {
+            *reinterpret_cast<uint2*>(dst + pass * kRowsPerPass * stride) = make_uint2(r[pass].x, r[pass].y);
+            *reinterpret_cast<uint2*>(dst + pass * kRowsPerPass * stride + 8) = make_uint2(r[pass].z, r[pass].w);
+        }
+    }
+};
 
 // C (bf16, row-major) = acc; rows at and beyond row_limit are not written.
 struct EpiStoreBf16 {
@@ -490,27 +496,14 @@ struct EpiStoreBf16 {
     }
 };
 
-// C (fp32, row-major) += acc with atomics (partials of a split reduction) or = acc.
-struct EpiAccumulateF32 {
+// C (fp32, row-major) = acc.  With a split reduction, part s goes to C + s * split_stride (its own
+// M x N matrix; the caller sums the parts), so no atomics are needed and the sum is reproducible.
+struct EpiStoreF32 {
     float* C;
     int64_t ldc;
-    int atomic;
+    int64_t split_stride;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
-        if (atomic) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int m = tc.row(i);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        float* c = C + (int64_t)m * ldc + tc.col(j, q);
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) atomicAdd(c + t, acc[i][j][4 * q + t]);
-                    }
-            }
-            return;
-        }
+        float* const C = this->C + tc.split * split_stride;
         constexpr int kStride = 528;                       // 128 fp32 + 16 bytes: conflict-free 16-byte accesses
         char* st = wave_stage(tc, lds);
         const int col_base = tc.n0 + tc.wn * 128;
@@ -542,7 +535,6 @@ struct EpiSwigluForward {
         constexpr int kStride = 392;                       // [u 64 | v 64 | a 64] bf16 + 8 bytes
         char* st = wave_stage(tc, lds);
         const int col_base = ((tc.n0 + tc.wn * 128) / 128) * 64;
-        bf16* const outs[3] = {u, v, a};
 #pragma unroll
         for (int half = 0; half < 2; ++half) {             // 64 rows per pass
 #pragma unroll
@@ -562,16 +554,18 @@ struct EpiSwigluForward {
             }
             __builtin_amdgcn_wave_barrier();
             const int row_base = tc.m0 + tc.wm * 128 + half * 64;
-#pragma unroll
-            for (int o = 0; o < 3; ++o)                    // 64 rows x 128 bytes of each output
-                copy_rows_out<64, 128>(st + o * 128, kStride, reinterpret_cast<char*>(outs[o] + (int64_t)row_base * ld + col_base),
-                                       ld * 2, 64, tc.lane);
+            const int64_t at = (int64_t)row_base * ld + col_base;     // 64 rows x 128 bytes of each output
+            copy_rows_out<64, 128>(st, kStride, reinterpret_cast<char*>(u + at), ld * 2, 64, tc.lane);
+            copy_rows_out<64, 128>(st + 128, kStride, reinterpret_cast<char*>(v + at), ld * 2, 64, tc.lane);
+            copy_rows_out<64, 128>(st + 256, kStride, reinterpret_cast<char*>(a + at), ld * 2, 64, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
 };
 
 // acc = da.  In place: u <- du = da * v * silu'(u), v <- dv = da * silu(u)  (bf16, [M, ff]).
+// Works through the wavefront's 128 x 128 block in four passes of 32 rows; the u, v rows of the
+// next pass are fetched into registers while the current pass is computed.
 struct EpiSwigluBackward {
     bf16 *u, *v;
     int64_t ld;
@@ -579,41 +573,45 @@ struct EpiSwigluBackward {
         constexpr int kStride = 520;                       // [du 128 | dv 128] bf16 + 8 bytes
         char* st = wave_stage(tc, lds);
         const int col_base = tc.n0 + tc.wn * 128;
+        const int64_t ld_bytes = ld * 2;
+        char* const u0 = reinterpret_cast<char*>(u + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
+        char* const v0 = reinterpret_cast<char*>(v + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
+        RowFetch<32, 256> fu, fv;
+        fu.fetch_rows(u0, ld_bytes, tc.lane);
+        fv.fetch_rows(v0, ld_bytes, tc.lane);
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {             // 64 rows per pass
-            const int row_base = tc.m0 + tc.wm * 128 + half * 64;
-            // bring u, v of the 64 x 128 block in as whole lines
-            copy_rows_in<64, 256>(st, kStride, reinterpret_cast<const char*>(u + (int64_t)row_base * ld + col_base), ld * 2, tc.lane);
-            copy_rows_in<64, 256>(st + 256, kStride, reinterpret_cast<const char*>(v + (int64_t)row_base * ld + col_base), ld * 2, tc.lane);
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int ii = 0; ii < 2; ++ii) {
-                const int i = half * 2 + ii;
-                const int lr = ii * 32 + (tc.lane & 31);
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int col = j * 32 + 8 * q + 4 * (tc.lane >> 5);
-                        char* pu = st + lr * kStride + col * 2;
-                        char* pv = pu + 256;
-                        const bf16x4 u4 = *reinterpret_cast<const bf16x4*>(pu);
-                        const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(pv);
-                        float du[4], dv[4];
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const float x = (float)u4[t], g = acc[i][j][4 * q + t];
-                            const float sg = fast_sigmoid(x);
-                            du[t] = g * (float)v4[t] * (sg * (1.f + x * (1.f - sg)));
-                            dv[t] = g * (x * sg);
-                        }
-                        *reinterpret_cast<bf16x4*>(pu) = to_bf16x4(du[0], du[1], du[2], du[3]);
-                        *reinterpret_cast<bf16x4*>(pv) = to_bf16x4(dv[0], dv[1], dv[2], dv[3]);
-                    }
+        for (int i = 0; i < 4; ++i) {                      // 32 rows per pass
+            fu.stash_rows(st, kStride, tc.lane);
+            fv.stash_rows(st + 256, kStride, tc.lane);
+            if (i < 3) {
+                fu.fetch_rows(u0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
+                fv.fetch_rows(v0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
             }
             __builtin_amdgcn_wave_barrier();
-            copy_rows_out<64, 256>(st, kStride, reinterpret_cast<char*>(u + (int64_t)row_base * ld + col_base), ld * 2, 64, tc.lane);
-            copy_rows_out<64, 256>(st + 256, kStride, reinterpret_cast<char*>(v + (int64_t)row_base * ld + col_base), ld * 2, 64, tc.lane);
+            const int lr = tc.lane & 31;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = j * 32 + 8 * q + 4 * (tc.lane >> 5);
+                    char* pu = st + lr * kStride + col * 2;
+                    char* pv = pu + 256;
+                    const bf16x4 u4 = *reinterpret_cast<const bf16x4*>(pu);
+                    const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(pv);
+                    float du[4], dv[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const float x = (float)u4[t], g = acc[i][j][4 * q + t];
+                        const float sg = fast_sigmoid(x);
+                        du[t] = g * (float)v4[t] * (sg * (1.f + x * (1.f - sg)));
+                        dv[t] = g * (x * sg);
+                    }
+                    *reinterpret_cast<bf16x4*>(pu) = to_bf16x4(du[0], du[1], du[2], du[3]);
+                    *reinterpret_cast<bf16x4*>(pv) = to_bf16x4(dv[0], dv[1], dv[2], dv[3]);
+                }
+            __builtin_amdgcn_wave_barrier();
+            copy_rows_out<32, 256>(st, kStride, u0 + i * 32 * ld_bytes, ld_bytes, 32, tc.lane);
+            copy_rows_out<32, 256>(st + 256, kStride, v0 + i * 32 * ld_bytes, ld_bytes, 32, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
