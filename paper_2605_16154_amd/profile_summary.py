@@ -4,6 +4,8 @@
   python -m paper_2605_16154_amd.profile_summary counter <dir>   # --pmc runs (per-kernel means)
   python -m paper_2605_16154_amd.profile_summary traffic <fetch_dir> <write_dir> <kernel substring>
                                                                   # HBM-side bytes per launch of one kernel
+  python -m paper_2605_16154_amd.profile_summary tail <dir> <kernel substring> <n>
+                                                                  # mean duration of a kernel's last n launches
 """
 from __future__ import annotations
 
@@ -48,6 +50,24 @@ def counter(path: str) -> str:
     return "\n".join(out) + "\n"
 
 
+def tail(path: str, kernel_substr: str, n: int) -> str:
+    """Mean duration of the last n dispatches of a kernel in a --kernel-trace run (e.g. the timed steps of a
+    benchmark whose set-up launches the same kernel)."""
+    rows = []
+    for f in glob.glob(os.path.join(path, "**", "*kernel_trace.csv"), recursive=True):
+        for row in csv.DictReader(open(f)):
+            if kernel_substr in row["Kernel_Name"]:
+                rows.append((int(row["Start_Timestamp"]), int(row["End_Timestamp"])))
+    rows.sort()
+    if not rows:
+        return "no matching dispatch found\n"
+    last = rows[-n:]
+    mean_all = sum(e - b for b, e in rows) / len(rows)
+    mean_last = sum(e - b for b, e in last) / len(last)
+    return (f"kernel={kernel_substr}\nlaunches={len(rows)}\navg_us_all={mean_all / 1e3:.2f}\n"
+            f"last_n={len(last)}\navg_us_last_n={mean_last / 1e3:.2f}\n")
+
+
 KERNEL_SOURCES = ("gemm_bf16.h", "actor_bf16.hip")
 
 
@@ -86,6 +106,9 @@ def traffic(fetch_dir: str, write_dir: str, kernel_substr: str) -> str:
 if __name__ == "__main__":
     if len(sys.argv) == 5 and sys.argv[1] == "traffic":
         sys.stdout.write(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
+        sys.exit(0)
+    if len(sys.argv) == 5 and sys.argv[1] == "tail":
+        sys.stdout.write(tail(sys.argv[2], sys.argv[3], int(sys.argv[4])))
         sys.exit(0)
     if len(sys.argv) != 3 or sys.argv[1] not in ("stats", "counter"):
         sys.exit(__doc__)
