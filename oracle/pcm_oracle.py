@@ -20,6 +20,9 @@ Parity status of each function (what pins it is in tests/test_oracle_*.py):
   actor_step          pinned by invariants only (finite differences, all-kept = unmasked,
                       zero gradient for uniform rewards, rho = 1 reduces to A * grad log pi);
                       no value printed in the paper fixes the head numerics.
+  clip_grad_norm,     pinned: closed forms (first step moves every weight by lr * g / (|g| + eps),
+  adamw_step          norm after clipping, decoupled decay with zero gradient) and agreement with
+                      torch.optim.AdamW + torch.nn.utils.clip_grad_norm_ run in fp64 on the CPU
 """
 from __future__ import annotations
 
@@ -383,3 +386,52 @@ def actor_step(hidden, tokens, logp_old, adv, kept_idx, N, A, Wg, Wu, Wd, Wo,
     dX = du @ Wg.T + dv @ Wu.T
     out.update(dz=dz, dWg=dWg, dWu=dWu, dWd=dWd, dWo=dWo, dX=dX)
     return out
+
+
+# ----------------------------------------------------------------------------------------
+# App. D (training details) -- the optimizer step that follows the actor gradients
+# ----------------------------------------------------------------------------------------
+
+def clip_grad_norm(grads, max_norm, eps=1e-6):
+    """Global-norm gradient clipping (App. D: "gradient clipping at 2.0").
+
+    The norm is the Euclidean norm over all gradient tensors taken together; the gradients
+    are multiplied by min(1, max_norm / (norm + eps)).  The paper gives the threshold only;
+    the joint 2-norm and eps = 1e-6 are the convention of the pipeline it builds on.
+    Returns (scaled gradients, norm before clipping).
+    """
+    total = F64(0.0)
+    for g in grads:
+        g = np.asarray(g, dtype=F64)
+        total += np.sum(g * g)
+    norm = np.sqrt(total)
+    scale = min(F64(1.0), F64(max_norm) / (norm + F64(eps)))
+    return [np.asarray(g, dtype=F64) * scale for g in grads], norm
+
+
+def adamw_step(params, grads, m, v, t, lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+               max_grad_norm=2.0):
+    """One AdamW update after global-norm clipping (App. D: lr 1e-5, betas (0.9, 0.999),
+    weight decay 0, clipping at 2.0; eps is not stated, 1e-8 is the usual default).
+
+    For every tensor, with g the clipped gradient and t >= 1 the step number:
+        m <- beta1 m + (1 - beta1) g            v <- beta2 v + (1 - beta2) g^2
+        theta <- theta (1 - lr wd)              (decoupled decay)
+        theta <- theta - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+    Returns (params, m, v, grad_norm), all new fp64 arrays.
+    """
+    assert t >= 1
+    g_clipped, norm = clip_grad_norm(grads, max_grad_norm)
+    bc1 = F64(1.0) - F64(beta1) ** t
+    bc2 = F64(1.0) - F64(beta2) ** t
+    new_p, new_m, new_v = [], [], []
+    for theta, g, m_i, v_i in zip(params, g_clipped, m, v):
+        theta = np.asarray(theta, dtype=F64)
+        m_n = F64(beta1) * np.asarray(m_i, dtype=F64) + (F64(1.0) - F64(beta1)) * g
+        v_n = F64(beta2) * np.asarray(v_i, dtype=F64) + (F64(1.0) - F64(beta2)) * g * g
+        theta_n = theta * (F64(1.0) - F64(lr) * F64(weight_decay))
+        theta_n = theta_n - F64(lr) * (m_n / bc1) / (np.sqrt(v_n / bc2) + F64(eps))
+        new_p.append(theta_n)
+        new_m.append(m_n)
+        new_v.append(v_n)
+    return new_p, new_m, new_v, norm
