@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 import numpy as np
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+HBM_PEAK_GBPS = 8000.0              # MI355X HBM3E peak
 GEMM_STAGES = ("gemm_gate_up", "gemm_down", "gemm_logits_loss", "gemm_dWo", "gemm_dy", "gemm_dWd", "gemm_da",
                "gemm_dWg_dWu", "gemm_dX")
 
@@ -214,6 +215,35 @@ def selection_only(cfg, dev, steps, warmup):
                                       "GB_per_s": 2 * actions.numel() * 4 / copy_us / 1e3}}
 
 
+def optimizer_step_timing(wl, iters=10):
+    """The optimizer step that would follow the actor gradients (App. D: clipping at 2.0 + AdamW), timed on
+    the head's real tensors: not part of `value`, reported beside it.  HBM-bound: per parameter the norm pass
+    reads 4 B, the update pass reads 16 B (g, m, v, w) and writes 14 B (m, v, w, bf16 copy)."""
+    torch, pcm = wl.torch, wl.pcm
+    names = ("Wg", "Wu", "Wd", "Wo")
+    grads = [wl.act_out["d" + n].reshape(-1) for n in names]
+    lowp = [wl.W[n].clone().reshape(-1) for n in names]
+    master = [w.float() for w in lowp]
+    m = [torch.zeros_like(w) for w in master]
+    v = [torch.zeros_like(w) for w in master]
+    for t in range(1, 3):
+        pcm.pcm_adamw_clip_step(grads, master, m, v, t, weights_bf16=lowp)
+    torch.cuda.synchronize()
+    pcm.pcm_profile_enable(True)
+    for t in range(3, 3 + iters):
+        norm = pcm.pcm_adamw_clip_step(grads, master, m, v, t, weights_bf16=lowp)
+    torch.cuda.synchronize()
+    st = pcm.pcm_profile_collect()
+    pcm.pcm_profile_enable(False)
+    n_param = sum(w.numel() for w in master)
+    ms_norm = st["opt_grad_norm"][0] / iters
+    ms_upd = st["opt_adamw"][0] / iters
+    return {"parameters": n_param, "grad_norm": float(norm.item()), "ms_per_step": ms_norm + ms_upd,
+            "grad_norm_pass": {"ms": ms_norm, "bytes": 4 * n_param, "GB_per_s": 4 * n_param / ms_norm / 1e6},
+            "adamw_pass": {"ms": ms_upd, "bytes": 30 * n_param, "GB_per_s": 30 * n_param / ms_upd / 1e6,
+                           "frac_of_hbm_peak": 30 * n_param / ms_upd / 1e6 / HBM_PEAK_GBPS}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -300,6 +330,9 @@ def main():
         result["unmasked"] = {"ms_per_step": ms_un, "kept_rows": n_un * cfg.A, "tokens_per_s": n_un * cfg.A * k_un / dt_un,
                               "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
                               "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
+    if cfg.dtype == "bf16":
+        wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
+        result["optimizer_step"] = optimizer_step_timing(wl)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, kept_host, args.cpu_sample_chunks)
     print(json.dumps(result))

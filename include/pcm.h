@@ -11,6 +11,8 @@
  *   grpo_masked_actor_step  gather of the kept chunks, action-head forward, clipped GRPO
  *                           surrogate (Eq. 11; Eq. 2 when every chunk is kept) and backward
  *
+ * and, to complete the actor update, pcm_adamw_clip_step applies the gradients (App. D).
+ *
  * Conventions common to every entry point
  *   - Return value: PCM_OK or a negative pcm_status.  Nothing throws, aborts or prints.
  *   - "device" pointers are HIP device memory owned by the caller; they must stay valid until
@@ -59,6 +61,7 @@ typedef enum { PCM_F32 = 0, PCM_BF16 = 1 } pcm_dtype;
 /* Limits of the kernels (host-checked). */
 #define PCM_MAX_PHASES 64        /* K */
 #define PCM_MAX_CHUNK_SLOTS 4096 /* N */
+#define PCM_MAX_OPT_TENSORS 8    /* tensors per optimizer call */
 
 /* Library version string (host). */
 PCM_API const char* pcm_version(void);
@@ -183,6 +186,37 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
                            float* loss_out, float* logp_out, float* dWg, float* dWu, float* dWd,
                            float* dWo, void* dX, float* stats_out, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * pcm_adamw_clip_step -- the optimizer step that follows the actor gradients (App. D, training
+ * details: AdamW, constant learning rate 1e-5, betas (0.9, 0.999), weight decay 0, gradient
+ * clipping at 2.0).
+ *
+ * With g the gradients of all n_tensors tensors taken together: norm = ||g||_2,
+ * g <- g * min(1, max_grad_norm / (norm + 1e-6)); then per element, t = step (1 for the first
+ * update):  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ * w <- w (1 - lr weight_decay) - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).
+ * The norm is accumulated in fp64 (in a fixed order: the result does not vary from run to run);
+ * the update is fp32 arithmetic on fp32 state.
+ *
+ *   n_tensors     1 .. PCM_MAX_OPT_TENSORS
+ *   numel         host i64 [n_tensors], each >= 1
+ *   grads         host array of n_tensors device pointers, f32 [numel[i]]; read only
+ *   weights, m, v host arrays of device pointers, f32 [numel[i]]; updated in place
+ *   weights_bf16  NULL, or a host array of device pointers (entries may be NULL) to bf16
+ *                 [numel[i]] that receive the new weights rounded to nearest even
+ *   f32 pointers must be 16-byte aligned, bf16 pointers 8-byte aligned
+ *   grad_norm_out device f32 [1] or NULL: the norm before clipping
+ * Errors: PCM_EINVAL for a null or misaligned pointer or a hyper-parameter out of range (step < 1,
+ * beta outside [0, 1), eps <= 0, negative lr / weight decay, max_grad_norm <= 0).
+ * ------------------------------------------------------------------------------------------ */
+PCM_API size_t pcm_adamw_clip_step_workspace_bytes(int n_tensors, const int64_t* numel);
+PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float* const* grads,
+                                float* const* weights, float* const* m, float* const* v,
+                                void* const* weights_bf16, int64_t step, double lr, double beta1,
+                                double beta2, double eps, double weight_decay, double max_grad_norm,
+                                float* grad_norm_out, void* workspace, size_t workspace_bytes,
+                                void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Stage timing (measurement aid, host side).  When enabled, grpo_masked_actor_step and the

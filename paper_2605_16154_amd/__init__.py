@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     grpo_masked_actor_step_workspace_bytes,
     lib,
     library_path,
+    pcm_adamw_clip_step,
     pcm_profile_collect,
     pcm_profile_enable,
     pcm_sample_chunks,

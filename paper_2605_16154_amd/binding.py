@@ -52,6 +52,10 @@ def lib() -> C.CDLL:
     _sig(L.grpo_masked_actor_step, i32,
          [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, f32,
           vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp])
+    _sig(L.pcm_adamw_clip_step_workspace_bytes, sz, [i32, C.POINTER(i64)])
+    _sig(L.pcm_adamw_clip_step, i32,
+         [i32, C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i64,
+          f64, f64, f64, f64, f64, f64, vp, vp, sz, vp])
     _sig(L.pcm_profile_enable, i32, [i32])
     _sig(L.pcm_profile_stage_count, i32, [])
     _sig(L.pcm_profile_stage_name, C.c_char_p, [i32])
@@ -226,6 +230,42 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
         _ptr(stats, torch.float32, "stats"), ws, ws_bytes, _stream())
     _check(rc, "grpo_masked_actor_step")
     return out
+
+
+def pcm_adamw_clip_step(grads, weights, m, v, step: int, lr: float = 1e-5, beta1: float = 0.9, beta2: float = 0.999,
+                        eps: float = 1e-8, weight_decay: float = 0.0, max_grad_norm: float = 2.0, weights_bf16=None,
+                        grad_norm_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Global-norm clipping + AdamW over lists of fp32 tensors (updated in place); -> grad norm f32[1].
+
+    `weights_bf16`, if given, is a list (entries may be None) of bf16 tensors that receive the new weights.
+    """
+    n = len(grads)
+    if not (len(weights) == len(m) == len(v) == n) or (weights_bf16 is not None and len(weights_bf16) != n):
+        raise PcmError("pcm_adamw_clip_step: lists must have equal length")
+    dev = grads[0].device
+    for g, w, mi, vi in zip(grads, weights, m, v):
+        if not (g.numel() == w.numel() == mi.numel() == vi.numel()):
+            raise PcmError("pcm_adamw_clip_step: gradient, weight and moment tensors must have equal sizes")
+    numel = (C.c_int64 * n)(*[g.numel() for g in grads])
+    arr = lambda ts, dt, name: (C.c_void_p * n)(*[_ptr(t, dt, name) for t in ts])
+    lowp = None
+    if weights_bf16 is not None:
+        for w, b in zip(weights, weights_bf16):
+            if b is not None and b.numel() != w.numel():
+                raise PcmError("pcm_adamw_clip_step: bf16 copy must have the size of its weight tensor")
+        lowp = arr(weights_bf16, torch.bfloat16, "weights_bf16")
+    if grad_norm_out is None:
+        grad_norm_out = torch.empty(1, dtype=torch.float32, device=dev)
+    need = lib().pcm_adamw_clip_step_workspace_bytes(n, numel)
+    if need == 0:
+        raise PcmError("pcm_adamw_clip_step: bad tensor list")
+    ws, ws_bytes = _workspace(need, dev)
+    rc = lib().pcm_adamw_clip_step(n, numel, arr(grads, torch.float32, "grads"), arr(weights, torch.float32, "weights"),
+                                   arr(m, torch.float32, "m"), arr(v, torch.float32, "v"), lowp, step, lr, beta1,
+                                   beta2, eps, weight_decay, max_grad_norm, _ptr(grad_norm_out, torch.float32, "norm"),
+                                   ws, ws_bytes, _stream())
+    _check(rc, "pcm_adamw_clip_step")
+    return grad_norm_out
 
 
 def pcm_profile_enable(on: bool) -> None:

@@ -59,6 +59,8 @@ enum Stage : int {
     ST_F32_FORWARD,
     ST_F32_LOSS,
     ST_F32_BACKWARD,
+    ST_OPT_NORM,
+    ST_OPT_ADAMW,
     ST_COUNT
 };
 

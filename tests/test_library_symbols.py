@@ -65,6 +65,18 @@ def test_null_and_range_arguments_are_rejected_on_the_host(cdll):
                                   None, None, None, None, ctypes.c_size_t(0), None) == -1
 
 
+def test_optimizer_entry_validates_on_the_host(cdll):
+    q = cdll.pcm_adamw_clip_step_workspace_bytes
+    q.restype = ctypes.c_size_t
+    numel = (ctypes.c_int64 * 2)(4096 * 3 + 1, 5)
+    assert q(2, numel) >= 5 * 8                     # one fp64 partial per 4096-element chunk
+    assert q(0, numel) == 0 and q(9, numel) == 0
+    d = ctypes.c_double
+    step = cdll.pcm_adamw_clip_step
+    assert step(2, numel, None, None, None, None, None, ctypes.c_int64(1), d(1e-5), d(0.9), d(0.999), d(1e-8), d(0.0),
+                d(2.0), None, None, ctypes.c_size_t(0), None) == -1
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     import paper_2605_16154_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
