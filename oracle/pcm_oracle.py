@@ -331,7 +331,8 @@ def log_softmax_rows(z):
 
 
 def actor_step(hidden, tokens, logp_old, adv, kept_idx, N, A, Wg, Wu, Wd, Wo,
-               eps_low=0.2, eps_high=0.2, loss_scale=1.0, want_grads=True):
+               eps_low=0.2, eps_high=0.2, loss_scale=1.0, want_grads=True,
+               token_mean=False, entropy_coef=0.0, chunk_ratio=False, chunk_weight=None):
     """Masked GRPO actor step over the kept chunks (Eq. 11; Eq. 2 when every chunk is kept).
 
     Rows: the A action tokens of each kept chunk, in kept order.  For a row with
@@ -343,9 +344,20 @@ def actor_step(hidden, tokens, logp_old, adv, kept_idx, N, A, Wg, Wu, Wd, Wo,
     probability being the sum of its tokens'.  With rho = 1 the gradient is that of
     -loss_scale * sum A_i log pi.  A ratio exactly on a clip boundary counts as unclipped.
 
+    Variants of the training loss (App. D, and the estimator discussed under Eq. 11):
+      token_mean    the sums are divided by the number of kept rows (scale = loss_scale / M);
+      entropy_coef  subtracts entropy_coef * scale * sum over rows of the entropy of softmax(z)
+                    (App. D: entropy coefficient 1e-3);
+      chunk_ratio   one ratio per chunk, the ratio of the chunk's probabilities
+                    rho_c = exp(sum over its A tokens of (l - l0)), one clipped term per chunk
+                    (Eq. 2 is written per chunk; the per-token form above is the default);
+      chunk_weight  f64 [len(kept_idx)], multiplies each chunk's term(s): the importance weights
+                    N_c / b_c of the unbiased estimator (App. C) or any other reweighting.
+
     hidden [T*N*A, d], tokens [T*N*A], logp_old [T*N*A], adv [T], kept_idx: global chunk ids.
-    Returns a dict with loss, logp (per kept row), ratio, dz, and (if want_grads)
-    dWg, dWu, dWd, dWo, dX plus stats = [clipped fraction, mean ratio, mean(l0 - l), rows].
+    Returns a dict with loss, logp (per kept row), ratio (per row), dz, and (if want_grads)
+    dWg, dWu, dWd, dWo, dX plus stats = [fraction of rows whose policy-gradient term is clipped
+    away, mean ratio, mean(l0 - l), rows, mean row entropy].
     """
     kept_idx = np.asarray(kept_idx, dtype=np.int64)
     rows = (kept_idx[:, None] * A + np.arange(A)[None, :]).reshape(-1)
@@ -353,28 +365,47 @@ def actor_step(hidden, tokens, logp_old, adv, kept_idx, N, A, Wg, Wu, Wd, Wo,
     tok = np.asarray(tokens)[rows].astype(np.int64)
     l0 = np.asarray(logp_old)[rows].astype(F64)
     adv_row = np.repeat(np.asarray(adv, dtype=F64)[kept_idx // N], A)
+    if chunk_weight is None:
+        w_row = np.ones(rows.shape[0], dtype=F64)
+    else:
+        w_row = np.repeat(np.asarray(chunk_weight, dtype=F64), A)
     Wg, Wu, Wd, Wo = (np.asarray(w).astype(F64) for w in (Wg, Wu, Wd, Wo))
     M = X.shape[0]
+    scale = F64(loss_scale)
+    if token_mean:
+        scale = scale / F64(M) if M else F64(0.0)
 
     u, v, s, su, a, y, z = head_forward(X, Wg, Wu, Wd, Wo)
     logsm, sm = log_softmax_rows(z)
     lp = logsm[np.arange(M), tok]
-    rho = np.exp(lp - l0)
-    clipped = np.clip(rho, 1.0 - eps_low, 1.0 + eps_high)
-    term = np.minimum(rho * adv_row, clipped * adv_row)
-    loss = -F64(loss_scale) * term.sum()
-    flows = ((adv_row >= 0) & (rho <= 1.0 + eps_high)) | ((adv_row < 0) & (rho >= 1.0 - eps_low))
-    out = {"loss": loss, "logp": lp, "ratio": rho, "rows": rows}
-    if M:
-        out["stats"] = np.array([1.0 - flows.mean(), rho.mean(), (l0 - lp).mean(), float(M)])
+    delta = lp - l0
+    if chunk_ratio:
+        rho = np.repeat(np.exp(delta.reshape(-1, A).sum(axis=1)), A)
     else:
-        out["stats"] = np.array([0.0, 0.0, 0.0, 0.0])
+        rho = np.exp(delta)
+    clipped = np.clip(rho, 1.0 - eps_low, 1.0 + eps_high)
+    term = w_row * np.minimum(rho * adv_row, clipped * adv_row)
+    if chunk_ratio:
+        term_sum = term.reshape(-1, A)[:, 0].sum()          # one term per chunk
+    else:
+        term_sum = term.sum()
+    entropy = -(sm * logsm).sum(axis=1)
+    loss = -scale * term_sum - F64(entropy_coef) * scale * entropy.sum()
+    flows = ((adv_row >= 0) & (rho <= 1.0 + eps_high)) | ((adv_row < 0) & (rho >= 1.0 - eps_low))
+    out = {"loss": loss, "logp": lp, "ratio": rho, "rows": rows, "entropy": entropy}
+    if M:
+        out["stats"] = np.array([1.0 - flows.mean(), rho.mean(), (l0 - lp).mean(), float(M), entropy.mean()])
+    else:
+        out["stats"] = np.array([0.0, 0.0, 0.0, 0.0, 0.0])
     if not want_grads:
         return out
-    gcoef = np.where(flows, rho * adv_row, 0.0)
+    # d(term)/d(l) of a row: rho * A_i where the unclipped branch is the active one; with a chunk ratio
+    # every row of the chunk sees the chunk's term through rho_c, whose derivative in each l is rho_c
+    gcoef = np.where(flows, w_row * rho * adv_row, 0.0)
     onehot = np.zeros_like(z)
     onehot[np.arange(M), tok] = 1.0
-    dz = (-F64(loss_scale) * gcoef)[:, None] * (onehot - sm)
+    dz = (-scale * gcoef)[:, None] * (onehot - sm)
+    dz = dz + F64(entropy_coef) * scale * sm * (logsm + entropy[:, None])
     dWo = y.T @ dz
     dy = dz @ Wo.T
     dWd = a.T @ dy

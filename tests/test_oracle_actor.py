@@ -177,3 +177,138 @@ def test_dropping_zero_advantage_trajectories_changes_nothing():
     assert a["loss"] == b["loss"]
     for k in ("dWg", "dWu", "dWd", "dWo"):
         assert np.allclose(a[k], b[k], rtol=1e-13, atol=1e-16)
+
+
+# ---- variants of the training loss (App. D: entropy bonus, token mean; per-chunk ratio; chunk weights) ----
+
+def _fd_check(p, kept, logp_old, kw, r, names=("Wg", "Wd", "Wo", "hidden"), n=4):
+    ref = _call(p, kept, logp_old, **kw)
+    h = 1e-6
+    for name in names:
+        W = p[name]
+        for _ in range(n):
+            if name == "hidden":
+                kr = int(r.integers(0, len(ref["rows"])))
+                idx = (int(ref["rows"][kr]), int(r.integers(0, W.shape[1])))
+                analytic = ref["dX"][kr, idx[1]]
+            else:
+                idx = tuple(int(r.integers(0, s)) for s in W.shape)
+                analytic = ref["d" + name][idx]
+            keep = W[idx]
+            W[idx] = keep + h
+            lp = _call(p, kept, logp_old, want_grads=False, **kw)["loss"]
+            W[idx] = keep - h
+            lm = _call(p, kept, logp_old, want_grads=False, **kw)["loss"]
+            W[idx] = keep
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - analytic) <= 2e-6 * max(1.0, abs(analytic)) + 1e-8, (name, idx, fd, analytic)
+    return ref
+
+
+@pytest.mark.parametrize("kw", [
+    dict(entropy_coef=0.05),
+    dict(token_mean=True),
+    dict(chunk_ratio=True),
+    dict(chunk_weight="random"),
+    dict(entropy_coef=1e-3, token_mean=True, chunk_ratio=True, chunk_weight="random", eps_low=0.2, eps_high=0.4),
+])
+def test_variant_gradients_match_finite_differences(kw):
+    p = _problem(seed=11)
+    r = np.random.default_rng(12)
+    old = {k: p[k] + 0.05 * r.standard_normal(p[k].shape) for k in ("Wg", "Wu", "Wd", "Wo")}
+    logp_old = _logp_all(p, old)
+    kept = np.array([1, 2, 5, 8, 9, 13, 17, 19])
+    kw = dict(kw)
+    if isinstance(kw.get("chunk_weight"), str):
+        kw["chunk_weight"] = r.uniform(0.5, 4.0, size=len(kept))
+    kw.setdefault("loss_scale", 0.25)
+    ref = _fd_check(p, kept, logp_old, kw, r)
+    if kw.get("chunk_ratio"):
+        flows_frac = 1 - ref["stats"][0]
+        assert 0.05 < flows_frac < 0.95                   # per-chunk ratios do reach both clip branches here
+
+
+def test_entropy_of_uniform_logits_is_log_V_and_enters_with_a_minus_sign():
+    p = _problem(seed=13)
+    p["Wo"] = np.zeros_like(p["Wo"])                       # z = 0: uniform distribution over V bins
+    V = p["Wo"].shape[1]
+    kept = np.array([0, 4, 6])
+    lp_all = _logp_all(p)
+    assert np.allclose(lp_all, -np.log(V))
+    base = _call(p, kept, lp_all, loss_scale=0.5, want_grads=False)
+    ent = _call(p, kept, lp_all, loss_scale=0.5, entropy_coef=0.1, want_grads=False)
+    M = len(kept) * p["A"]
+    assert np.allclose(ent["entropy"], np.log(V), rtol=1e-14)
+    assert np.isclose(base["loss"] - ent["loss"], 0.1 * 0.5 * M * np.log(V), rtol=1e-13)
+    assert np.isclose(ent["stats"][4], np.log(V), rtol=1e-14)
+    # entropy is maximal at the uniform distribution: its gradient in the logits vanishes there
+    full = _call(p, kept, lp_all, loss_scale=0.5, entropy_coef=0.1)
+    plain = _call(p, kept, lp_all, loss_scale=0.5)
+    assert np.allclose(full["dz"], plain["dz"], atol=1e-16)
+
+
+def test_entropy_matches_scipy_on_random_logits():
+    from scipy.stats import entropy as scipy_entropy
+    p = _problem(seed=14)
+    kept = np.array([2, 3, 10])
+    out = _call(p, kept, _logp_all(p), entropy_coef=1.0, want_grads=False)
+    rows = out["rows"]
+    *_, z = O.head_forward(p["hidden"][rows], p["Wg"], p["Wu"], p["Wd"], p["Wo"])
+    pr = np.exp(z - logsumexp(z, axis=1, keepdims=True))
+    assert np.allclose(out["entropy"], scipy_entropy(pr, axis=1), rtol=1e-12)
+
+
+def test_token_mean_is_the_sum_divided_by_the_number_of_kept_rows():
+    p = _problem(seed=15)
+    r = np.random.default_rng(16)
+    logp_old = _logp_all(p) + 0.1 * r.standard_normal(p["hidden"].shape[0])
+    kept = np.array([0, 1, 7, 12, 13])
+    M = len(kept) * p["A"]
+    a = _call(p, kept, logp_old, loss_scale=2.0, token_mean=True, entropy_coef=0.01)
+    b = _call(p, kept, logp_old, loss_scale=2.0 / M, entropy_coef=0.01)
+    assert np.isclose(a["loss"], b["loss"], rtol=1e-14)
+    for k in ("dWg", "dWo", "dX"):
+        assert np.allclose(a[k], b[k], rtol=1e-13, atol=1e-18)
+    empty = _call(p, np.array([], dtype=np.int64), logp_old, token_mean=True)
+    assert empty["loss"] == 0.0
+
+
+def test_chunk_ratio_is_the_ratio_of_chunk_probabilities():
+    p = _problem(seed=17)
+    r = np.random.default_rng(18)
+    logp_old = _logp_all(p) + 0.05 * r.standard_normal(p["hidden"].shape[0])
+    kept = np.array([3, 4, 9, 15])
+    A = p["A"]
+    out = _call(p, kept, logp_old, chunk_ratio=True, eps_low=0.2, eps_high=0.4, loss_scale=1.0)
+    lp = _logp_all(p)
+    total = 0.0
+    for j, c in enumerate(kept):
+        rows = np.arange(c * A, (c + 1) * A)
+        ratio = np.exp(lp[rows].sum()) / np.exp(logp_old[rows].sum())     # pi(chunk) / pi_old(chunk)
+        assert np.allclose(out["ratio"][j * A:(j + 1) * A], ratio, rtol=1e-12)
+        adv = p["adv"][c // p["N"]]
+        total += min(ratio * adv, np.clip(ratio, 0.8, 1.4) * adv)
+    assert np.isclose(out["loss"], -total, rtol=1e-12)
+    # with one token per chunk the two forms coincide
+    q = _problem(seed=19, A=1)
+    lo = _logp_all(q) + 0.1 * r.standard_normal(q["hidden"].shape[0])
+    k1 = np.array([0, 2, 5, 11])
+    a = _call(q, k1, lo, chunk_ratio=True)
+    b = _call(q, k1, lo)
+    assert np.isclose(a["loss"], b["loss"], rtol=1e-14) and np.allclose(a["dWo"], b["dWo"], rtol=1e-13, atol=1e-18)
+
+
+def test_chunk_weights_reweight_each_chunks_contribution():
+    p = _problem(seed=20)
+    r = np.random.default_rng(21)
+    logp_old = _logp_all(p) + 0.05 * r.standard_normal(p["hidden"].shape[0])
+    kept = np.array([1, 6, 14])
+    ones = _call(p, kept, logp_old, chunk_weight=np.ones(3))
+    none = _call(p, kept, logp_old)
+    assert ones["loss"] == none["loss"] and np.array_equal(ones["dWg"], none["dWg"])
+    # the weighted objective is the weighted sum of the single-chunk objectives
+    w = np.array([0.5, 2.0, 3.5])
+    whole = _call(p, kept, logp_old, chunk_weight=w)
+    parts = [_call(p, kept[j:j + 1], logp_old) for j in range(3)]
+    assert np.isclose(whole["loss"], sum(wj * pj["loss"] for wj, pj in zip(w, parts)), rtol=1e-13)
+    assert np.allclose(whole["dWd"], sum(wj * pj["dWd"] for wj, pj in zip(w, parts)), rtol=1e-12, atol=1e-16)
