@@ -89,7 +89,7 @@ class Workload:
         self.act_out = {}
         torch.cuda.synchronize()
 
-    def step(self, t, B=None):
+    def step(self, t, B=None, **loss_variants):
         cfg, pcm, b = self.cfg, self.pcm, self.batches[t % len(self.batches)]
         B = cfg.B if B is None else B
         self.sel_out = pcm.pcm_score_phases(b["actions"], b["phase"], b["reward"], b["n_chunks"], cfg.n_groups,
@@ -102,20 +102,20 @@ class Workload:
         kept, off, nk = self.samp_out
         self.act_out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], b["logp_old"], adv, kept, nk, cfg.T, cfg.N,
                                                   cfg.A, self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"],
-                                                  0.2, 0.2, 1.0 / cfg.T, out=self.act_out)
+                                                  0.2, 0.4, 1.0 / cfg.T, out=self.act_out, **loss_variants)
         return nk
 
 
-def timed_steps(wl, steps, warmup, B=None, profile=False):
+def timed_steps(wl, steps, warmup, B=None, profile=False, **loss_variants):
     torch = wl.torch
     for t in range(warmup):
-        wl.step(t, B)
+        wl.step(t, B, **loss_variants)
     torch.cuda.synchronize()
     if profile:
         wl.pcm.pcm_profile_enable(True)
     t0 = time.perf_counter()
     for t in range(warmup, warmup + steps):
-        nk = wl.step(t, B)
+        nk = wl.step(t, B, **loss_variants)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     stages = None
@@ -151,7 +151,7 @@ def cpu_baseline(wl, kept_host, sample_chunks):
     W = {k: v.float().cpu().numpy() for k, v in wl.W.items()}
     t0 = time.perf_counter()
     O.actor_step(hid, tok, lp_old, adv[pick // cfg.N], np.arange(len(pick)), 1, cfg.A, W["Wg"], W["Wu"], W["Wd"], W["Wo"],
-                 0.2, 0.2, 1.0 / cfg.T)
+                 0.2, 0.4, 1.0 / cfg.T)
     t_act = time.perf_counter() - t0
     rows_step = nk * cfg.A
     est_step = t_sel + t_act * rows_step / len(rows)
@@ -331,6 +331,14 @@ def main():
                               "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
                               "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
     if cfg.dtype == "bf16":
+        # the same step with the loss of App. D (entropy bonus 1e-3, token-mean normalisation) and with one
+        # ratio per chunk: extended entry point, same kernels plus two small ones in the per-chunk case
+        wl.state = pcm.pcm_state_init(cfg.K, dev)
+        k_v = max(2, min(5, args.steps))
+        dt_v, _, _ = timed_steps(wl, k_v, 1, entropy_coef=1e-3, token_mean=True)
+        dt_c, _, _ = timed_steps(wl, k_v, 1, entropy_coef=1e-3, token_mean=True, chunk_ratio=True)
+        result["loss_variants"] = {"entropy_bonus_token_mean_ms_per_step": dt_v / k_v * 1e3,
+                                   "with_per_chunk_ratio_ms_per_step": dt_c / k_v * 1e3}
         wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
         result["optimizer_step"] = optimizer_step_timing(wl)
     if not args.no_cpu_baseline:

@@ -188,6 +188,49 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
                            size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * grpo_masked_actor_step_ex -- the same step with the variants of the training loss (App. D,
+ * training details: asymmetric clipping (0.2, 0.4), entropy coefficient 1e-3; App. C: the
+ * importance-weighted unbiased estimator).  All other arguments as grpo_masked_actor_step.
+ *
+ * With M = (*n_kept) * A live rows, scale = loss_scale (PCM_NORM_SCALE) or loss_scale / M
+ * (PCM_NORM_TOKEN_MEAN; 0 when M = 0), w_c = chunk_weight[c] for the c-th kept chunk (1 if NULL),
+ * H_r the entropy of row r's distribution over the V bins:
+ *   PCM_RATIO_TOKEN  rho_r = exp(l_r - logp_old_r);   T = sum over rows of w_c min(rho_r A_i, clip(rho_r) A_i)
+ *   PCM_RATIO_CHUNK  rho_c = exp(sum over the chunk's A rows of (l_r - logp_old_r)), the ratio of
+ *                    the chunk's probabilities (Eq. 2 is written per chunk);
+ *                    T = sum over chunks of w_c min(rho_c A_i, clip(rho_c) A_i)
+ *   loss = -scale * T - entropy_coef * scale * sum over rows of H_r
+ * Gradients are those of that loss.
+ *
+ *   options    host pointer, read during the call only
+ *   options->chunk_weight  device f32 [max_kept_chunks] or NULL (e.g. N_c / b_c: chunks of the
+ *              chunk's phase in its trajectory over those kept)
+ *   stats_out  device f32 [5] or NULL: as grpo_masked_actor_step (with a per-chunk ratio, entries 0
+ *              and 1 use the chunk's ratio for each of its rows), then the mean row entropy
+ * Errors: PCM_EINVAL also for options == NULL, an unknown normalisation or ratio_level, NaN
+ * coefficients.
+ * ------------------------------------------------------------------------------------------ */
+typedef enum { PCM_NORM_SCALE = 0, PCM_NORM_TOKEN_MEAN = 1 } pcm_normalisation;
+typedef enum { PCM_RATIO_TOKEN = 0, PCM_RATIO_CHUNK = 1 } pcm_ratio_level;
+typedef struct {
+    float eps_low, eps_high;    /* clip thresholds (App. D: 0.2, 0.4) */
+    float loss_scale;
+    float entropy_coef;         /* App. D: 1e-3; 0 disables */
+    int normalisation;          /* pcm_normalisation */
+    int ratio_level;            /* pcm_ratio_level */
+    const float* chunk_weight;  /* device, or NULL */
+} pcm_loss_options;
+
+PCM_API int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* tokens, const float* logp_old,
+                              const float* adv, const int32_t* kept_idx, const int32_t* n_kept,
+                              int max_kept_chunks, int T, int N, int A, int d, int ff, int V,
+                              int dtype, const void* Wg, const void* Wu, const void* Wd,
+                              const void* Wo, const pcm_loss_options* options, float* loss_out,
+                              float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo,
+                              void* dX, float* stats_out, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * pcm_adamw_clip_step -- the optimizer step that follows the actor gradients (App. D, training
  * details: AdamW, constant learning rate 1e-5, betas (0.9, 0.999), weight decay 0, gradient
  * clipping at 2.0).

@@ -24,6 +24,13 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+class LossOptions(C.Structure):
+    """pcm_loss_options of include/pcm.h."""
+    _fields_ = [("eps_low", C.c_float), ("eps_high", C.c_float), ("loss_scale", C.c_float),
+                ("entropy_coef", C.c_float), ("normalisation", C.c_int), ("ratio_level", C.c_int),
+                ("chunk_weight", C.c_void_p)]
+
+
 def _sig(fn, res, args):
     fn.restype = res
     fn.argtypes = args
@@ -51,6 +58,9 @@ def lib() -> C.CDLL:
     _sig(L.grpo_masked_actor_step_workspace_bytes, sz, [i32] * 7)
     _sig(L.grpo_masked_actor_step, i32,
          [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, f32,
+          vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp])
+    _sig(L.grpo_masked_actor_step_ex, i32,
+         [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, C.POINTER(LossOptions),
           vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp])
     _sig(L.pcm_adamw_clip_step_workspace_bytes, sz, [i32, C.POINTER(i64)])
     _sig(L.pcm_adamw_clip_step, i32,
@@ -175,10 +185,14 @@ def grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, 
 def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: int, N: int, A: int,
                            Wg, Wu, Wd, Wo, eps_low: float = 0.2, eps_high: float = 0.2, loss_scale: float = 1.0,
                            want_grads: bool = True, want_dX: bool = True, max_kept_chunks: Optional[int] = None,
-                           out: Optional[Dict[str, torch.Tensor]] = None) -> Dict[str, torch.Tensor]:
-    """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[4], and if requested dWg, dWu, dWd, dWo, dX).
+                           out: Optional[Dict[str, torch.Tensor]] = None, token_mean: bool = False,
+                           entropy_coef: float = 0.0, chunk_ratio: bool = False,
+                           chunk_weight: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[5], and if requested dWg, dWu, dWd, dWo, dX).
 
-    `out` may carry preallocated tensors under those names (they are reused, not reallocated).
+    `out` may carry preallocated tensors under those names (they are reused, not reallocated).  With none of
+    token_mean, entropy_coef, chunk_ratio, chunk_weight set this is grpo_masked_actor_step (stats[4] stays 0);
+    otherwise grpo_masked_actor_step_ex.
     """
     dev = hidden.device
     d, ff = Wg.shape
@@ -211,7 +225,9 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
 
     loss = buf("loss", (1,), torch.float32)
     logp = buf("logp", (rows,), torch.float32)
-    stats = buf("stats", (4,), torch.float32)
+    if "stats" not in out:
+        out["stats"] = torch.zeros(5, dtype=torch.float32, device=dev)
+    stats = buf("stats", (5,), torch.float32)
     grads = [None] * 4
     if want_grads:
         grads = [buf("dWg", (d, ff), torch.float32), buf("dWu", (d, ff), torch.float32),
@@ -221,14 +237,23 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
     if need == 0:
         raise PcmError("grpo_masked_actor_step: unsupported shape or dtype for this path")
     ws, ws_bytes = _workspace(need, dev)
-    rc = lib().grpo_masked_actor_step(
-        _ptr(hidden, None, "hidden"), _ptr(tokens, torch.uint8, "tokens"), _ptr(logp_old, torch.float32, "logp_old"),
-        _ptr(adv, torch.float32, "adv"), _ptr(kept_idx, torch.int32, "kept_idx"), _ptr(n_kept, torch.int32, "n_kept"),
-        max_kept_chunks, T, N, A, d, ff, V, dtype, _ptr(Wg, None, "Wg"), _ptr(Wu, None, "Wu"), _ptr(Wd, None, "Wd"),
-        _ptr(Wo, None, "Wo"), eps_low, eps_high, loss_scale, _ptr(loss, torch.float32, "loss"),
-        _ptr(logp, torch.float32, "logp"), *[_ptr(g, torch.float32, "dW") for g in grads], _ptr(dX, None, "dX"),
-        _ptr(stats, torch.float32, "stats"), ws, ws_bytes, _stream())
-    _check(rc, "grpo_masked_actor_step")
+    head = (_ptr(hidden, None, "hidden"), _ptr(tokens, torch.uint8, "tokens"), _ptr(logp_old, torch.float32, "logp_old"),
+            _ptr(adv, torch.float32, "adv"), _ptr(kept_idx, torch.int32, "kept_idx"), _ptr(n_kept, torch.int32, "n_kept"),
+            max_kept_chunks, T, N, A, d, ff, V, dtype, _ptr(Wg, None, "Wg"), _ptr(Wu, None, "Wu"), _ptr(Wd, None, "Wd"),
+            _ptr(Wo, None, "Wo"))
+    tail = (_ptr(loss, torch.float32, "loss"), _ptr(logp, torch.float32, "logp"),
+            *[_ptr(g, torch.float32, "dW") for g in grads], _ptr(dX, None, "dX"), _ptr(stats, torch.float32, "stats"),
+            ws, ws_bytes, _stream())
+    if token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None:
+        if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
+            raise PcmError("chunk_weight is shorter than max_kept_chunks")
+        opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
+                          _ptr(chunk_weight, torch.float32, "chunk_weight"))
+        rc = lib().grpo_masked_actor_step_ex(*head, C.byref(opt), *tail)
+        _check(rc, "grpo_masked_actor_step_ex")
+    else:
+        rc = lib().grpo_masked_actor_step(*head, eps_low, eps_high, loss_scale, *tail)
+        _check(rc, "grpo_masked_actor_step")
     return out
 
 

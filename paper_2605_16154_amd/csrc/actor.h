@@ -18,6 +18,16 @@ struct ActorShape {
     int64_t rows_max() const { return (int64_t)max_chunks * A; }
 };
 
+// How the objective is assembled from the rows (Eq. 11 plus the training details of App. D).
+struct LossOptions {
+    float eps_low, eps_high;     // clip thresholds
+    float loss_scale;            // multiplies the summed objective
+    float entropy_coef;          // subtracts entropy_coef * scale * sum of row entropies
+    int token_mean;              // scale = loss_scale / (kept rows) instead of loss_scale
+    int chunk_ratio;             // one ratio (and one clipped term) per chunk instead of per token
+    const float* chunk_weight;   // device [max_chunks] or null: multiplies the terms of a chunk
+};
+
 struct ActorIO {
     const void* hidden;
     const uint8_t* tokens;
@@ -26,12 +36,13 @@ struct ActorIO {
     const int32_t* kept_idx;
     const int32_t* n_kept;
     const void *Wg, *Wu, *Wd, *Wo;
-    float eps_low, eps_high, loss_scale;
+    LossOptions opt;
     float* loss_out;
     float* logp_out;
     float *dWg, *dWu, *dWd, *dWo;
     void* dX;
     float* stats_out;
+    int n_stats;      // 4, or 5 when the mean row entropy is reported too
     bool want_grads() const { return dWg != nullptr; }
 };
 
@@ -48,6 +59,8 @@ struct RowOut {
     float* ratio;      // [rows_pad]
     float* dlogp;      // [rows_pad] logp_old - logp
     uint8_t* clipped;  // [rows_pad] 1 if the row's gradient is cut by the clip
+    float* entropy;    // [rows_pad] entropy of the row's distribution over the V bins
+    float* coef;       // [rows_pad] per-chunk ratio only: factor of (onehot - softmax) in dz
 };
 
 // gather.hip ---------------------------------------------------------------------------------
@@ -59,23 +72,51 @@ int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void*
 // Sums the per-row loss terms and statistics in a fixed order (one workgroup, fp64 accumulators).
 int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipStream_t s);
 
-// Row-wise loss math shared by both paths (device).  Returns the coefficient c such that
-// dz = c * (onehot - softmax): c = -loss_scale * rho * A when the gradient flows, else 0.
+// Per-chunk ratio: from the per-row dlogp, one ratio, one clipped term and one dz factor per chunk
+// (written to every row of the chunk; the term only to its first row).
+int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t rows_pad,
+                       hipStream_t s);
+
+// dz[r, :] = coef[r] * dz[r, :] (+ extra[r, :] if extra is given), rows [0, rows_pad) of V columns;
+// elem_bytes is 2 (bf16) or 4 (fp32).
+int launch_scale_rows(void* dz, const void* extra, const float* coef, int64_t rows_pad, int V, int elem_bytes,
+                      hipStream_t s);
+
+// Number of live rows from the device-side kept count.
+__device__ inline int64_t live_rows(const int32_t* n_kept, int max_chunks, int A) {
+    int nk = *n_kept;
+    nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
+    return (int64_t)nk * A;
+}
+// Factor in front of the summed objective.
+__device__ inline float objective_scale(const LossOptions& o, int64_t rows_live) {
+    if (!o.token_mean) return o.loss_scale;
+    return rows_live > 0 ? o.loss_scale / (float)rows_live : 0.f;
+}
+
+// Clipped-surrogate math of one ratio (device), shared by both paths and both ratio levels.
+// term = weight * min(rho A, clip(rho) A); coef is the factor c in dz = c * (onehot - softmax):
+// c = -scale * weight * rho * A where the gradient flows, else 0.
 struct LossRow {
     float term, ratio, dlogp, coef;
     uint8_t clipped;
 };
-__device__ inline LossRow loss_row(float logp, float logp_old, float adv, float eps_low, float eps_high,
-                                   float loss_scale) {
+__device__ inline LossRow loss_from_ratio(float ratio, float adv, float weight, const LossOptions& o, float scale) {
     LossRow r;
-    r.dlogp = logp_old - logp;
-    r.ratio = expf(logp - logp_old);
-    const float lo = 1.f - eps_low, hi = 1.f + eps_high;
-    const float clipped_ratio = fminf(fmaxf(r.ratio, lo), hi);
-    r.term = fminf(r.ratio * adv, clipped_ratio * adv);
-    const bool flows = (adv >= 0.f && r.ratio <= hi) || (adv < 0.f && r.ratio >= lo);
+    r.dlogp = 0.f;
+    r.ratio = ratio;
+    const float lo = 1.f - o.eps_low, hi = 1.f + o.eps_high;
+    const float clipped_ratio = fminf(fmaxf(ratio, lo), hi);
+    r.term = weight * fminf(ratio * adv, clipped_ratio * adv);
+    const bool flows = (adv >= 0.f && ratio <= hi) || (adv < 0.f && ratio >= lo);
     r.clipped = flows ? 0 : 1;
-    r.coef = flows ? -loss_scale * r.ratio * adv : 0.f;
+    r.coef = flows ? -scale * weight * ratio * adv : 0.f;
+    return r;
+}
+__device__ inline LossRow loss_row(float logp, float logp_old, float adv, float weight, const LossOptions& o,
+                                   float scale) {
+    LossRow r = loss_from_ratio(expf(logp - logp_old), adv, weight, o, scale);
+    r.dlogp = logp_old - logp;
     return r;
 }
 

@@ -26,6 +26,36 @@ extern "C" size_t grpo_masked_actor_step_workspace_bytes(int max_kept_chunks, in
                             : actor_bf16_workspace_bytes(sh, want_grads != 0);
 }
 
+namespace {
+
+int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_old, const float* adv,
+                   const int32_t* kept_idx, const int32_t* n_kept, int max_kept_chunks, int T, int N, int A, int d, int ff,
+                   int V, int dtype, const void* Wg, const void* Wu, const void* Wd, const void* Wo, const LossOptions& opt,
+                   float* loss_out, float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
+                   float* stats_out, int n_stats, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!hidden || !tokens || !logp_old || !adv || !kept_idx || !n_kept || !Wg || !Wu || !Wd || !Wo || !loss_out)
+        return PCM_EINVAL;
+    const int n_grad = (dWg != nullptr) + (dWu != nullptr) + (dWd != nullptr) + (dWo != nullptr);
+    if (n_grad != 0 && n_grad != 4) return PCM_EINVAL;
+    ActorShape sh{max_kept_chunks, T, N, A, d, ff, V};
+    if (!shape_valid(sh) || T < 1 || N < 1 || (int64_t)T * N >= (int64_t)1 << 31) return PCM_EINVAL;
+    if (!(opt.eps_low >= 0.f) || !(opt.eps_high >= 0.f) || opt.loss_scale != opt.loss_scale ||
+        opt.entropy_coef != opt.entropy_coef)
+        return PCM_EINVAL;
+    if (dtype != PCM_F32 && dtype != PCM_BF16) return PCM_EINVAL;
+    if (!shape_supported(sh, dtype)) return PCM_EUNSUPPORTED;
+    const bool bwd = n_grad == 4 || dX != nullptr;
+    const size_t need = dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd);
+    if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
+
+    ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, opt,
+               loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, n_stats};
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return dtype == PCM_F32 ? actor_f32_run(sh, io, workspace, s) : actor_bf16_run(sh, io, workspace, s);
+}
+
+}  // namespace
+
 extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_old,
                                       const float* adv, const int32_t* kept_idx, const int32_t* n_kept,
                                       int max_kept_chunks, int T, int N, int A, int d, int ff, int V, int dtype,
@@ -33,21 +63,27 @@ extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens,
                                       float eps_low, float eps_high, float loss_scale, float* loss_out,
                                       float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
                                       float* stats_out, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!hidden || !tokens || !logp_old || !adv || !kept_idx || !n_kept || !Wg || !Wu || !Wd || !Wo || !loss_out)
-        return PCM_EINVAL;
-    const int n_grad = (dWg != nullptr) + (dWu != nullptr) + (dWd != nullptr) + (dWo != nullptr);
-    if (n_grad != 0 && n_grad != 4) return PCM_EINVAL;
-    ActorShape sh{max_kept_chunks, T, N, A, d, ff, V};
-    if (!shape_valid(sh) || T < 1 || N < 1 || (int64_t)T * N >= (int64_t)1 << 31) return PCM_EINVAL;
-    if (!(eps_low >= 0.f) || !(eps_high >= 0.f) || loss_scale != loss_scale) return PCM_EINVAL;
-    if (dtype != PCM_F32 && dtype != PCM_BF16) return PCM_EINVAL;
-    if (!shape_supported(sh, dtype)) return PCM_EUNSUPPORTED;
-    const bool bwd = n_grad == 4 || dX != nullptr;
-    const size_t need = dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd);
-    if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
+    const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr};
+    return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
+                          Wu, Wd, Wo, opt, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 4, workspace,
+                          workspace_bytes, stream);
+}
 
-    ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, eps_low, eps_high, loss_scale,
-               loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out};
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    return dtype == PCM_F32 ? actor_f32_run(sh, io, workspace, s) : actor_bf16_run(sh, io, workspace, s);
+extern "C" int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* tokens, const float* logp_old,
+                                         const float* adv, const int32_t* kept_idx, const int32_t* n_kept,
+                                         int max_kept_chunks, int T, int N, int A, int d, int ff, int V, int dtype,
+                                         const void* Wg, const void* Wu, const void* Wd, const void* Wo,
+                                         const pcm_loss_options* options, float* loss_out, float* logp_out, float* dWg,
+                                         float* dWu, float* dWd, float* dWo, void* dX, float* stats_out,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (!options) return PCM_EINVAL;
+    if ((options->normalisation != PCM_NORM_SCALE && options->normalisation != PCM_NORM_TOKEN_MEAN) ||
+        (options->ratio_level != PCM_RATIO_TOKEN && options->ratio_level != PCM_RATIO_CHUNK))
+        return PCM_EINVAL;
+    const LossOptions opt{options->eps_low, options->eps_high, options->loss_scale, options->entropy_coef,
+                          options->normalisation == PCM_NORM_TOKEN_MEAN, options->ratio_level == PCM_RATIO_CHUNK,
+                          options->chunk_weight};
+    return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
+                          Wu, Wd, Wo, opt, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 5, workspace,
+                          workspace_bytes, stream);
 }

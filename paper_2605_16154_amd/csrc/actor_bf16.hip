@@ -75,7 +75,7 @@ __global__ void sum_parts_f32(const float* parts, int n_parts, size_t n, float* 
 
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
-    bf16 *X, *u, *v, *a, *y, *dz;
+    bf16 *X, *u, *v, *a, *y, *dz, *dz_extra;
     bf16* dy;
     float* parts;   // partial products of split reductions
     RowMeta meta;
@@ -106,6 +106,9 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     w.out.ratio = c.take<float>(Mp);
     w.out.dlogp = c.take<float>(Mp);
     w.out.clipped = c.take<uint8_t>(Mp);
+    w.out.entropy = c.take<float>(Mp);
+    w.out.coef = c.take<float>(Mp);
+    if (bwd) w.dz_extra = c.take<bf16>(Mp * V);
     if (bwd) w.dy = c.take<bf16>(Mp * d);
     if (grads) w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
     w.bytes = c.used();
@@ -191,8 +194,16 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     {
         StageTimer t(ST_GEMM_LOGITS_LOSS, s);
         EpiLogitsLoss epi{w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A,
-                          io.eps_low, io.eps_high, io.loss_scale, bwd ? w.dz : nullptr, io.logp_out, w.out};
+                          io.opt, bwd ? w.dz : nullptr, w.dz_extra, io.logp_out, w.out};
         launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM), epi, s);
+    }
+    if (io.opt.chunk_ratio) {
+        rc = launch_chunk_ratio(sh, io, w.meta, w.out, Mp, s);
+        if (rc != PCM_OK) return rc;
+        if (bwd) {
+            rc = launch_scale_rows(w.dz, io.opt.entropy_coef != 0.f ? w.dz_extra : nullptr, w.out.coef, Mp, V, 2, s);
+            if (rc != PCM_OK) return rc;
+        }
     }
     rc = launch_loss_reduce(sh, io, w.out, s);
     if (rc != PCM_OK) return rc;

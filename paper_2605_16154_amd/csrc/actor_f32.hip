@@ -111,50 +111,71 @@ __device__ inline float wave_sum(float x) {
     return x;
 }
 
-// One wavefront per row: log-softmax at the target bin, ratio, clipped surrogate, and (in place)
-// z <- dz = coef * (onehot - softmax).
-__global__ __launch_bounds__(kThreads) void loss_rows(float* __restrict__ z, int V, const uint8_t* __restrict__ token,
+// One wavefront per row: log-softmax at the target bin, entropy, ratio, clipped surrogate, and (in
+// place) z <- dz = coef * (onehot - softmax) + entropy part.  With a per-chunk ratio the factor is
+// not known yet: z <- onehot - softmax and the entropy part goes to `extra`; the rows are scaled
+// once the chunk ratios are known.
+__global__ __launch_bounds__(kThreads) void loss_rows(float* __restrict__ z, float* __restrict__ extra, int V,
+                                                      const uint8_t* __restrict__ token,
                                                       const float* __restrict__ logp_old,
                                                       const float* __restrict__ adv_row,
                                                       const int32_t* __restrict__ n_kept, int max_chunks, int A,
-                                                      int64_t rows_total, float eps_low, float eps_high,
-                                                      float loss_scale, int write_dz, float* logp_out, float* term,
-                                                      float* ratio, float* dlogp, uint8_t* clipped) {
+                                                      int64_t rows_total, LossOptions opt, int write_dz,
+                                                      float* logp_out, RowOut out) {
     const int lane = threadIdx.x % kWave;
     const int64_t r = (int64_t)blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
     if (r >= rows_total) return;
-    int nk = *n_kept;
-    nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
-    const bool live = r < (int64_t)nk * A;
+    const int64_t rows = live_rows(n_kept, max_chunks, A);
+    const bool live = r < rows;
+    const float scale = objective_scale(opt, rows);
     float* zr = z + r * V;
     float mx = -INFINITY;
     for (int j = lane; j < V; j += kWave) mx = fmaxf(mx, zr[j]);
     mx = wave_max(mx);
-    float se = 0.f;
-    for (int j = lane; j < V; j += kWave) se += expf(zr[j] - mx);
+    float se = 0.f, sz = 0.f;
+    for (int j = lane; j < V; j += kWave) {
+        const float e = expf(zr[j] - mx);
+        se += e;
+        sz += e * zr[j];
+    }
     se = wave_sum(se);
+    sz = wave_sum(sz);
     const int b = token[r];
     const float lse = mx + logf(se);
     const float lp = zr[b] - lse;
-    const LossRow lr = loss_row(lp, logp_old[r], adv_row[r], eps_low, eps_high, loss_scale);
+    const float H = lse - sz / se;                      // -sum p log p
+    const float w = (opt.chunk_weight && live) ? opt.chunk_weight[r / A] : 1.f;
+    const LossRow lr = loss_row(lp, logp_old[r], adv_row[r], w, opt, scale);
     if (lane == 0) {
-        term[r] = live ? lr.term : 0.f;
-        ratio[r] = lr.ratio;
-        dlogp[r] = lr.dlogp;
-        clipped[r] = lr.clipped;
+        out.dlogp[r] = lr.dlogp;
+        out.entropy[r] = live ? H : 0.f;
+        if (!opt.chunk_ratio) {
+            out.term[r] = live ? lr.term : 0.f;
+            out.ratio[r] = lr.ratio;
+            out.clipped[r] = lr.clipped;
+        }
         if (logp_out && live) logp_out[r] = lp;
     }
     if (write_dz) {
-        const float coef = live ? lr.coef : 0.f;
+        const float coef = opt.chunk_ratio ? (live ? 1.f : 0.f) : (live ? lr.coef : 0.f);
+        const float ec = live ? opt.entropy_coef * scale : 0.f;
         for (int j = lane; j < V; j += kWave) {
-            const float p = expf(zr[j] - lse);
-            zr[j] = coef * ((j == b ? 1.f : 0.f) - p);
+            const float zj = zr[j];
+            const float p = expf(zj - lse);
+            const float pg = coef * ((j == b ? 1.f : 0.f) - p);
+            const float ent = ec * p * (zj - lse + H);
+            if (opt.chunk_ratio) {
+                zr[j] = pg;
+                extra[r * V + j] = ent;
+            } else {
+                zr[j] = pg + ent;
+            }
         }
     }
 }
 
 struct F32Workspace {
-    float *X, *u, *v, *a, *y, *z, *dy, *da;
+    float *X, *u, *v, *a, *y, *z, *z_extra, *dy, *da;
     RowMeta meta;
     RowOut out;
     size_t bytes;
@@ -177,7 +198,10 @@ F32Workspace carve(void* ws, const ActorShape& sh, bool grads) {
     w.out.ratio = c.take<float>(M);
     w.out.dlogp = c.take<float>(M);
     w.out.clipped = c.take<uint8_t>(M);
+    w.out.entropy = c.take<float>(M);
+    w.out.coef = c.take<float>(M);
     if (grads) {
+        w.z_extra = c.take<float>(M * sh.V);
         w.dy = c.take<float>(M * sh.d);
         w.da = c.take<float>(M * sh.ff);
     }
@@ -244,9 +268,16 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
     {
         StageTimer t(ST_F32_LOSS, s);
         loss_rows<<<(unsigned)ceil_div64(M, kThreads / kWave), kThreads, 0, s>>>(
-            w.z, V, w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A, M, io.eps_low,
-            io.eps_high, io.loss_scale, bwd ? 1 : 0, io.logp_out, w.out.term, w.out.ratio,
-            w.out.dlogp, w.out.clipped);
+            w.z, w.z_extra, V, w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A, M, io.opt,
+            bwd ? 1 : 0, io.logp_out, w.out);
+    }
+    if (io.opt.chunk_ratio) {
+        rc = launch_chunk_ratio(sh, io, w.meta, w.out, M, s);
+        if (rc != PCM_OK) return rc;
+        if (bwd) {
+            rc = launch_scale_rows(w.z, io.opt.entropy_coef != 0.f ? w.z_extra : nullptr, w.out.coef, M, V, 4, s);
+            if (rc != PCM_OK) return rc;
+        }
     }
     rc = launch_loss_reduce(sh, io, w.out, s);
     if (rc != PCM_OK) return rc;

@@ -87,35 +87,92 @@ __global__ __launch_bounds__(1024) void loss_reduce(const float* __restrict__ te
                                                      const float* __restrict__ ratio,
                                                      const float* __restrict__ dlogp,
                                                      const uint8_t* __restrict__ clipped,
+                                                     const float* __restrict__ entropy,
                                                      const int32_t* __restrict__ n_kept, int max_chunks, int A,
-                                                     float loss_scale, float* loss_out, float* stats_out) {
-    __shared__ double red[4][1024];
-    int nk = *n_kept;
-    nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
-    const int64_t rows = (int64_t)nk * A;
-    double acc[4] = {0, 0, 0, 0};
+                                                     LossOptions opt, float* loss_out, float* stats_out, int n_stats) {
+    __shared__ double red[5][1024];
+    const int64_t rows = live_rows(n_kept, max_chunks, A);
+    double acc[5] = {0, 0, 0, 0, 0};
     for (int64_t r = threadIdx.x; r < rows; r += 1024) {
         acc[0] += (double)term[r];
         acc[1] += (double)ratio[r];
         acc[2] += (double)dlogp[r];
         acc[3] += (double)clipped[r];
+        acc[4] += (double)entropy[r];
     }
-    for (int q = 0; q < 4; ++q) red[q][threadIdx.x] = acc[q];
+    for (int q = 0; q < 5; ++q) red[q][threadIdx.x] = acc[q];
     __syncthreads();
     for (int half = 512; half > 0; half >>= 1) {
         if ((int)threadIdx.x < half)
-            for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + half];
+            for (int q = 0; q < 5; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + half];
         __syncthreads();
     }
     if (threadIdx.x == 0) {
-        *loss_out = (float)(-(double)loss_scale * red[0][0]);
+        const double scale = (double)objective_scale(opt, rows);
+        *loss_out = (float)(-scale * red[0][0] - (double)opt.entropy_coef * scale * red[4][0]);
         if (stats_out) {
             const double n = rows > 0 ? (double)rows : 1.0;
             stats_out[0] = (float)(red[3][0] / n);
             stats_out[1] = (float)(red[1][0] / n);
             stats_out[2] = (float)(red[2][0] / n);
             stats_out[3] = (float)rows;
+            if (n_stats > 4) stats_out[4] = (float)(red[4][0] / n);
         }
+    }
+}
+
+// One lane per chunk slot.  rho_c = exp(sum over the chunk's tokens of (logp - logp_old)).
+__global__ __launch_bounds__(256) void chunk_ratio_rows(const float* __restrict__ dlogp,
+                                                        const float* __restrict__ adv_row,
+                                                        const int32_t* __restrict__ n_kept, int max_chunks, int A,
+                                                        int64_t rows_pad, LossOptions opt, float* __restrict__ term,
+                                                        float* __restrict__ ratio, uint8_t* __restrict__ clipped,
+                                                        float* __restrict__ coef) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r0 = c * A;
+    if (r0 >= rows_pad) return;
+    const int64_t rows = live_rows(n_kept, max_chunks, A);
+    const int64_t r1 = r0 + A < rows_pad ? r0 + A : rows_pad;
+    if (r0 >= rows) {                                   // padding rows: no contribution
+        for (int64_t r = r0; r < r1; ++r) {
+            term[r] = 0.f;
+            coef[r] = 0.f;
+        }
+        return;
+    }
+    float sum = 0.f;
+    for (int64_t r = r0; r < r1; ++r) sum -= dlogp[r];
+    const float w = opt.chunk_weight ? opt.chunk_weight[c] : 1.f;
+    const LossRow lr = loss_from_ratio(expf(sum), adv_row[r0], w, opt, objective_scale(opt, rows));
+    for (int64_t r = r0; r < r1; ++r) {
+        term[r] = r == r0 ? lr.term : 0.f;
+        ratio[r] = lr.ratio;
+        clipped[r] = lr.clipped;
+        coef[r] = lr.coef;
+    }
+}
+
+template <typename T>
+__device__ inline float to_f32(T x);
+template <>
+__device__ inline float to_f32<float>(float x) { return x; }
+template <>
+__device__ inline float to_f32<bf16>(bf16 x) { return __bfloat162float(x); }
+template <typename T>
+__device__ inline T from_f32(float x);
+template <>
+__device__ inline float from_f32<float>(float x) { return x; }
+template <>
+__device__ inline bf16 from_f32<bf16>(float x) { return __float2bfloat16(x); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void scale_rows(T* __restrict__ dz, const T* __restrict__ extra,
+                                                   const float* __restrict__ coef, int64_t n, int V) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float x = coef[i / V] * to_f32<T>(dz[i]);
+        if (extra) x += to_f32<T>(extra[i]);
+        dz[i] = from_f32<T>(x);
     }
 }
 
@@ -143,8 +200,30 @@ int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void*
 
 int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipStream_t s) {
     StageTimer t(ST_REDUCE, s);
-    loss_reduce<<<1, 1024, 0, s>>>(out.term, out.ratio, out.dlogp, out.clipped, io.n_kept, sh.max_chunks,
-                                   sh.A, io.loss_scale, io.loss_out, io.stats_out);
+    loss_reduce<<<1, 1024, 0, s>>>(out.term, out.ratio, out.dlogp, out.clipped, out.entropy, io.n_kept,
+                                   sh.max_chunks, sh.A, io.opt, io.loss_out, io.stats_out, io.n_stats);
+    return launch_status();
+}
+
+int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t rows_pad,
+                       hipStream_t s) {
+    StageTimer t(ST_REDUCE, s);
+    const int64_t slots = ceil_div64(rows_pad, sh.A);
+    chunk_ratio_rows<<<(unsigned)ceil_div64(slots, 256), 256, 0, s>>>(out.dlogp, meta.adv, io.n_kept, sh.max_chunks,
+                                                                      sh.A, rows_pad, io.opt, out.term, out.ratio,
+                                                                      out.clipped, out.coef);
+    return launch_status();
+}
+
+int launch_scale_rows(void* dz, const void* extra, const float* coef, int64_t rows_pad, int V, int elem_bytes,
+                      hipStream_t s) {
+    StageTimer t(ST_REDUCE, s);
+    const int64_t n = rows_pad * V;
+    unsigned blocks = (unsigned)(ceil_div64(n, 256) < 4096 ? ceil_div64(n, 256) : 4096);
+    if (elem_bytes == 2)
+        scale_rows<bf16><<<blocks, 256, 0, s>>>(static_cast<bf16*>(dz), static_cast<const bf16*>(extra), coef, n, V);
+    else
+        scale_rows<float><<<blocks, 256, 0, s>>>(static_cast<float*>(dz), static_cast<const float*>(extra), coef, n, V);
     return launch_status();
 }
 

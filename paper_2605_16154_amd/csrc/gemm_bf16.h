@@ -618,24 +618,28 @@ struct EpiSwigluBackward {
 };
 
 // Logit projection (N = V = 256 = one tile, so a workgroup holds whole rows) with the loss fused:
-// log-softmax at the target bin, ratio, clipped surrogate, dz = coef * (onehot - softmax) as bf16.
+// log-softmax at the target bin, row entropy, ratio, clipped surrogate and
+// dz = coef * (onehot - softmax) + entropy_coef * scale * softmax * (log softmax + H) as bf16.
+// With a per-chunk ratio the factor is not known yet: dz <- onehot - softmax, the entropy part goes
+// to dz_extra, and the rows are scaled once the chunk ratios are known.
 struct EpiLogitsLoss {
     const uint8_t* token;
     const float* logp_old;
     const float* adv_row;
     const int32_t* n_kept;
     int max_chunks, A;
-    float eps_low, eps_high, loss_scale;
+    LossOptions opt;
     bf16* dz;          // [M, 256] or nullptr
+    bf16* dz_extra;    // [M, 256]: entropy part, per-chunk ratio only
     float* logp_out;   // may be nullptr
     RowOut out;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
-        // exchange area (LDS, free after the main loop): [2 quantities][2 column halves][256 rows]
+        // exchange area (LDS, free after the main loop): [3 quantities][2 column halves][256 rows]
         float* ex_a = reinterpret_cast<float*>(lds);
         float* ex_b = ex_a + 512;
-        int nk = *n_kept;
-        nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
-        const int64_t rows_live = (int64_t)nk * A;
+        float* ex_c = ex_b + 512;
+        const int64_t rows_live = live_rows(n_kept, max_chunks, A);
+        const float scale = objective_scale(opt, rows_live);
         const int lrow_base = tc.wm * 128 + (tc.lane & 31);
 
         float mx[4];
@@ -655,12 +659,12 @@ struct EpiLogitsLoss {
         for (int i = 0; i < 4; ++i) mx[i] = fmaxf(mx[i], ex_a[(tc.wn ^ 1) * 256 + lrow_base + i * 32]);
         __syncthreads();
 
-        float lse[4], ztok[4];
+        float lse[4], ztok[4], ent[4];
         int tok[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             tok[i] = token[tc.row(i)];
-            float se = 0.f, zt = 0.f;
+            float se = 0.f, sz = 0.f, zt = 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -669,25 +673,32 @@ struct EpiLogitsLoss {
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const float z = acc[i][j][4 * q + t];
-                        se += __expf(z - mx[i]);
+                        const float e = __expf(z - mx[i]);
+                        se += e;
+                        sz += e * z;
                         zt += (n + t == tok[i]) ? z : 0.f;
                     }
                 }
             se += __shfl_xor(se, 32, 64);
+            sz += __shfl_xor(sz, 32, 64);
             zt += __shfl_xor(zt, 32, 64);
             lse[i] = se;
+            ent[i] = sz;
             ztok[i] = zt;
             if (tc.lane < 32) {
                 ex_a[tc.wn * 256 + lrow_base + i * 32] = se;
                 ex_b[tc.wn * 256 + lrow_base + i * 32] = zt;
+                ex_c[tc.wn * 256 + lrow_base + i * 32] = sz;
             }
         }
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int other = (tc.wn ^ 1) * 256 + lrow_base + i * 32;
-            lse[i] = mx[i] + __logf(lse[i] + ex_a[other]);
+            const float se = lse[i] + ex_a[other];
+            lse[i] = mx[i] + __logf(se);
             ztok[i] += ex_b[other];
+            ent[i] = lse[i] - (ent[i] + ex_c[other]) / se;      // H = -sum p log p
         }
 
 #pragma unroll
@@ -695,28 +706,41 @@ struct EpiLogitsLoss {
             const int m = tc.row(i);
             const bool live = m < rows_live;
             const float lp = ztok[i] - lse[i];
-            const LossRow lr = loss_row(lp, logp_old[m], adv_row[m], eps_low, eps_high, loss_scale);
+            const float w = (opt.chunk_weight && live) ? opt.chunk_weight[m / A] : 1.f;
+            const LossRow lr = loss_row(lp, logp_old[m], adv_row[m], w, opt, scale);
             if (tc.wn == 0 && tc.lane < 32) {
-                out.term[m] = live ? lr.term : 0.f;
-                out.ratio[m] = lr.ratio;
                 out.dlogp[m] = lr.dlogp;
-                out.clipped[m] = lr.clipped;
+                out.entropy[m] = live ? ent[i] : 0.f;
+                if (!opt.chunk_ratio) {
+                    out.term[m] = live ? lr.term : 0.f;
+                    out.ratio[m] = lr.ratio;
+                    out.clipped[m] = lr.clipped;
+                }
                 if (logp_out && live) logp_out[m] = lp;
             }
             if (dz) {
-                const float coef = live ? lr.coef : 0.f;
+                const float coef = opt.chunk_ratio ? (live ? 1.f : 0.f) : (live ? lr.coef : 0.f);
+                const float ec = live ? opt.entropy_coef * scale : 0.f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int n = tc.col(j, q);
-                        float g[4];
+                        float g[4], h[4];
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
-                            const float pr = __expf(acc[i][j][4 * q + t] - lse[i]);
+                            const float lpj = acc[i][j][4 * q + t] - lse[i];
+                            const float pr = __expf(lpj);
                             g[t] = coef * (((n + t == tok[i]) ? 1.f : 0.f) - pr);
+                            h[t] = ec * pr * (lpj + ent[i]);
                         }
-                        *reinterpret_cast<bf16x4*>(dz + (int64_t)m * 256 + n) = to_bf16x4(g[0], g[1], g[2], g[3]);
+                        if (opt.chunk_ratio) {
+                            *reinterpret_cast<bf16x4*>(dz + (int64_t)m * 256 + n) = to_bf16x4(g[0], g[1], g[2], g[3]);
+                            *reinterpret_cast<bf16x4*>(dz_extra + (int64_t)m * 256 + n) = to_bf16x4(h[0], h[1], h[2], h[3]);
+                        } else {
+                            *reinterpret_cast<bf16x4*>(dz + (int64_t)m * 256 + n) =
+                                to_bf16x4(g[0] + h[0], g[1] + h[1], g[2] + h[2], g[3] + h[3]);
+                        }
                     }
             }
         }

@@ -77,15 +77,23 @@ def make_problem(cfg, wstd=0.02, margin=0.0, kept=None, seed_step=0, eps=(0.2, 0
     return dict(cfg=cfg, hidden=hidden, tokens=tokens, adv=adv, kept=kept.astype(np.int32), W=W, logp_old=logp_old)
 
 
-def run_both(pcm, pr, eps=(0.2, 0.2), scale=None, torch_dtype=torch.float32, max_kept=None, **kw):
+def run_both(pcm, pr, eps=(0.2, 0.2), scale=None, torch_dtype=torch.float32, max_kept=None, variants=None, **kw):
+    """The same step through the checker and through the library.  `variants`: loss options given to both
+    (token_mean, entropy_coef, chunk_ratio, chunk_weight as a numpy array over the kept chunks)."""
     cfg, W = pr["cfg"], pr["W"]
     scale = 1.0 / cfg.T if scale is None else scale
+    variants = dict(variants or {})
     ref = O.actor_step(pr["hidden"], pr["tokens"], pr["logp_old"], pr["adv"], pr["kept"], cfg.N, cfg.A,
-                       W["Wg"], W["Wu"], W["Wd"], W["Wo"], eps[0], eps[1], scale)
+                       W["Wg"], W["Wu"], W["Wd"], W["Wo"], eps[0], eps[1], scale, **variants)
     kept = pr["kept"]
     max_kept = len(kept) if max_kept is None else max_kept
     kept_buf = np.full(max_kept, -7, dtype=np.int32)       # tail entries are garbage on purpose
     kept_buf[:len(kept)] = kept
+    if variants.get("chunk_weight") is not None:
+        wbuf = np.full(max_kept, 1e30, dtype=np.float32)   # so are the weights beyond the kept count
+        wbuf[:len(kept)] = variants["chunk_weight"]
+        variants["chunk_weight"] = dev(wbuf)
+    kw.update(variants)
     out = pcm.grpo_masked_actor_step(
         dev(pr["hidden"], torch_dtype), dev(pr["tokens"]), dev(pr["logp_old"]), dev(pr["adv"].astype(np.float32)),
         dev(kept_buf), dev(np.array([len(kept)], np.int32)), cfg.T, cfg.N, cfg.A,
@@ -95,14 +103,15 @@ def run_both(pcm, pr, eps=(0.2, 0.2), scale=None, torch_dtype=torch.float32, max
     return ref, {k: v.float().cpu().numpy() for k, v in out.items()}
 
 
-def check(ref, got, tol, n_rows, stats_tol=None):
+def check(ref, got, tol, n_rows, stats_tol=None, n_stats=4):
     stats_tol = max(tol, 1e-5) if stats_tol is None else stats_tol
     assert abs(got["loss"][0] - ref["loss"]) <= tol * max(1.0, abs(ref["loss"])), (got["loss"], ref["loss"])
     assert rel(got["logp"][:n_rows], ref["logp"]) <= tol
     for k in GRADS:
         assert rel(got[k], ref[k]) <= tol, (k, rel(got[k], ref[k]))
     assert rel(got["dX"][:n_rows], ref["dX"]) <= tol, rel(got["dX"][:n_rows], ref["dX"])
-    assert np.allclose(got["stats"], ref["stats"], rtol=stats_tol, atol=stats_tol), (got["stats"], ref["stats"])
+    assert np.allclose(got["stats"][:n_stats], ref["stats"][:n_stats], rtol=stats_tol, atol=stats_tol), \
+        (got["stats"], ref["stats"])
 
 
 # ------------------------------------------------------------------------------------------ fp32
