@@ -17,6 +17,8 @@ Parity status of each function (what pins it is in tests/test_oracle_*.py):
   philox4x32_10       pinned: published known-answer vectors of the generator
   sample_chunks       pinned: brute-force Plackett-Luce enumeration on tiny inputs
   compact / sample    pinned: set properties (|K_i| = min(B, N_i), ascending, unique)
+  selectors, weights  pinned: uniform inclusion frequencies of "random", phase purity and counts of
+                      "top_phase", sum of N_c / b_c over a phase's kept chunks = N_c, hand example
   actor_step          pinned by invariants only (finite differences, all-kept = unmasked,
                       zero gradient for uniform rewards, rho = 1 reduces to A * grad log pi);
                       no value printed in the paper fixes the head numerics.
@@ -273,8 +275,15 @@ def sample_trajectory(weights, m, seed, step, traj):
     return picks
 
 
-def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step):
+def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step, selector="pcm"):
     """Kept set per trajectory and its compaction (Eq. 10; Algorithm 1 inner loop; Sec. 4.5).
+
+    selector (Sec. 5.2, RQ4: the two ablations that bracket the method):
+      "pcm"        weights = the phases' keep probabilities (the method);
+      "random"     every chunk has the same weight: min(B, N_i) chunks uniformly at random;
+      "top_phase"  only chunks of the single phase with the largest keep probability (lowest
+                   index on ties) are eligible, with equal weights; a trajectory keeps
+                   min(B, number of its chunks in that phase) of them (none if it has none).
 
     Every chunk inherits its phase's keep probability as weight (Sec. 4.4); each
     active trajectory keeps min(B, N_i) chunks; trajectories of collapsed groups
@@ -286,7 +295,20 @@ def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step):
     """
     phase = np.asarray(phase)
     T, N = phase.shape
-    q = quantise_keep_probs(keep_probs)
+    K = len(keep_probs)
+    if selector == "pcm":
+        q = quantise_keep_probs(keep_probs)
+    elif selector == "random":
+        q = np.ones(K, dtype=np.int64)
+    elif selector == "top_phase":
+        best = 0
+        for c in range(1, K):
+            if keep_probs[c] > keep_probs[best]:
+                best = c
+        q = np.zeros(K, dtype=np.int64)
+        q[best] = 1
+    else:
+        raise ValueError(selector)
     n_chunks = np.full(T, N, dtype=np.int64) if n_chunks is None else np.asarray(n_chunks, dtype=np.int64)
     kept = []
     offsets = np.zeros(T + 1, dtype=np.int32)
@@ -295,12 +317,35 @@ def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step):
         if (active is not None and not active[i]) or Ni == 0:
             offsets[i + 1] = offsets[i]
             continue
-        m = min(B, Ni)
-        w = [int(q[int(phase[i, k])]) for k in range(Ni)]
+        w = [int(q[min(int(phase[i, k]), K - 1)]) for k in range(Ni)]
+        m = min(B, sum(1 for x in w if x > 0))
         picks = sorted(sample_trajectory(w, m, seed, step, i))
         kept.extend(i * N + k for k in picks)
         offsets[i + 1] = offsets[i] + m
     return np.asarray(kept, dtype=np.int32), offsets, int(offsets[T])
+
+
+def importance_weights(phase, n_chunks, kept_idx, K):
+    """Weights N_c / b_c of the ratio estimator (App. C, the unbiased alternative to Eq. 11).
+
+    For a kept chunk of trajectory i and phase c: N_c = number of the trajectory's (valid) chunks
+    in phase c, b_c = number of its kept chunks in phase c.  Summed over the kept chunks of one
+    (trajectory, phase) the weights give back N_c.  Returns f32 [len(kept_idx)], the quotient
+    of the two counts rounded once to single precision.
+    """
+    phase = np.asarray(phase)
+    T, N = phase.shape
+    n_chunks = np.full(T, N, dtype=np.int64) if n_chunks is None else np.asarray(n_chunks, dtype=np.int64)
+    kept_idx = np.asarray(kept_idx, dtype=np.int64)
+    out = np.zeros(len(kept_idx), dtype=np.float32)
+    for j, g in enumerate(kept_idx):
+        i, k = int(g) // N, int(g) % N
+        c = min(int(phase[i, k]), K - 1)
+        in_phase = [kk for kk in range(int(n_chunks[i])) if min(int(phase[i, kk]), K - 1) == c]
+        kept_here = [int(x) % N for x in kept_idx if int(x) // N == i]
+        b = sum(1 for kk in kept_here if min(int(phase[i, kk]), K - 1) == c)
+        out[j] = np.float32(len(in_phase)) / np.float32(b)
+    return out
 
 
 # ----------------------------------------------------------------------------------------

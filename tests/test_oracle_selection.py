@@ -332,3 +332,64 @@ def test_allocation_tracks_weight_times_phase_size():
     # budget is ~19% of the chunks, so without-replacement saturation flattens the allocation a little
     assert np.argmax(counts) == np.argmax(pred)
     assert np.all(np.abs(counts / n_kept - pred) < 0.12)
+
+
+# --------------------------------------------------------------------------- ablation selectors (Sec. 5.2, RQ4)
+
+def test_random_selector_keeps_every_chunk_equally_often():
+    # uniform sampling of m of N items without replacement includes each item with probability m / N
+    T, N, K, B = 4, 10, 3, 4
+    phase = np.array([[0] * 3 + [1] * 5 + [2] * 2] * T, dtype=np.uint8)
+    p = np.array([1.0, 0.1, 0.4])
+    counts = np.zeros(N)
+    steps = 1500
+    for s in range(steps):
+        kept, off, nk = O.sample_chunks(p, phase, None, None, B, 99, s, selector="random")
+        assert nk == T * B
+        counts += np.bincount(kept % N, minlength=N)
+    freq = counts / (steps * T)
+    sigma = math.sqrt(0.4 * 0.6 / (steps * T))
+    assert np.all(np.abs(freq - B / N) < 5 * sigma), freq
+    # and it ignores the keep probabilities altogether
+    a = O.sample_chunks(p, phase, None, None, B, 7, 3, selector="random")[0]
+    b = O.sample_chunks(p[::-1].copy(), phase, None, None, B, 7, 3, selector="random")[0]
+    assert np.array_equal(a, b)
+
+
+def test_top_phase_selector_keeps_only_the_highest_phase():
+    T, N, K, B = 3, 12, 4, 5
+    phase = np.array([[0, 0, 1, 1, 1, 1, 1, 1, 2, 2, 3, 3],        # 6 chunks of phase 1 -> keeps 5
+                      [1, 0, 0, 0, 2, 2, 2, 3, 3, 3, 1, 0],        # 2 chunks of phase 1 -> keeps both
+                      [0, 0, 0, 2, 2, 2, 3, 3, 3, 3, 0, 0]],       # none -> keeps nothing
+                     dtype=np.uint8)
+    p = np.array([0.3, 1.0, 1.0, 0.1])                             # tie between phases 1 and 2: lowest index wins
+    kept, off, nk = O.sample_chunks(p, phase, None, None, B, 5, 0, selector="top_phase")
+    assert list(np.diff(off)) == [5, 2, 0] and nk == 7
+    assert all(phase[g // N, g % N] == 1 for g in kept)
+    assert sorted(kept[5:] % N) == [0, 10]
+    # a ragged trajectory: chunks beyond n_chunks are not eligible
+    kept, off, nk = O.sample_chunks(p, phase, np.array([4, 12, 12]), None, B, 5, 0, selector="top_phase")
+    assert list(np.diff(off)) == [2, 2, 0] and sorted(kept[:2]) == [2, 3]
+
+
+def test_importance_weights_hand_example_and_phase_totals():
+    N, K = 8, 3
+    phase = np.array([[0, 0, 0, 1, 1, 2, 2, 2], [2, 2, 2, 2, 0, 0, 1, 1]], dtype=np.uint8)
+    kept = np.array([0, 3, 4, 7, 8 + 0, 8 + 1, 8 + 6])             # traj 0: phases 0,1,1,2; traj 1: 2,2,1
+    w = O.importance_weights(phase, None, kept, K)
+    assert np.array_equal(w, np.array([3 / 1, 2 / 2, 2 / 2, 3 / 1, 4 / 2, 4 / 2, 2 / 1], dtype=np.float32))
+    # unbiasedness identity of the ratio estimator: over a phase's kept chunks the weights add up to N_c
+    cfg = CONFIGS["cfg2"]
+    ro = make_rollouts(cfg, 1)
+    nch = ragged_n_chunks(cfg, 1)
+    p = np.array([1.0, 0.1, 0.5, 0.2, 0.7])
+    kept, off, nk = O.sample_chunks(p, ro["phase"], nch, None, cfg.B, cfg.seed, 1)
+    w = O.importance_weights(ro["phase"], nch, kept, cfg.K).astype(np.float64)
+    for i in range(0, cfg.T, 7):
+        mine = kept[off[i]:off[i + 1]]
+        wi = w[off[i]:off[i + 1]]
+        for c in range(cfg.K):
+            sel = ro["phase"][i, mine % cfg.N] == c
+            if sel.any():
+                n_c = int((ro["phase"][i, :nch[i]] == c).sum())
+                assert abs(wi[sel].sum() - n_c) < 1e-4 * n_c
