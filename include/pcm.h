@@ -149,6 +149,31 @@ PCM_API int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, co
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * pcm_sample_chunks_ex -- pcm_sample_chunks with a choice of selector: the method, or one of the
+ * two ablations that bracket it (Sec. 5.2, RQ4).  All other arguments as pcm_sample_chunks.
+ *   PCM_SELECT_PCM        weights = the phases' keep probabilities (the method, Eq. 10)
+ *   PCM_SELECT_RANDOM     equal weights: min(B, N_i) chunks uniformly at random; keep_probs is
+ *                         not used for the weights (it must still point at K doubles)
+ *   PCM_SELECT_TOP_PHASE  only chunks of the one phase with the largest keep probability (lowest
+ *                         index on ties) are eligible, with equal weights; a trajectory keeps
+ *                         min(B, its chunks in that phase), possibly none
+ *
+ * pcm_importance_weights -- the weights N_c / b_c of the ratio estimator (App. C, the unbiased
+ * alternative to Eq. 11), one per kept chunk, for grpo_masked_actor_step_ex's chunk_weight:
+ * N_c = valid chunks of the kept chunk's phase in its trajectory, b_c = kept ones among them.
+ *   kept_idx, kept_offsets  device, as written by pcm_sample_chunks
+ *   weights   device f32 [kept_offsets[T]]: entry j belongs to kept_idx[j]
+ * ------------------------------------------------------------------------------------------ */
+typedef enum { PCM_SELECT_PCM = 0, PCM_SELECT_RANDOM = 1, PCM_SELECT_TOP_PHASE = 2 } pcm_selector;
+PCM_API int pcm_sample_chunks_ex(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
+                         const uint8_t* active, int T, int N, int K, int B, int selector,
+                         uint64_t seed, uint64_t step, int32_t* kept_idx, int32_t* kept_offsets,
+                         int32_t* n_kept, void* workspace, size_t workspace_bytes, void* stream);
+PCM_API int pcm_importance_weights(const uint8_t* phase, const int32_t* n_chunks, const int32_t* kept_idx,
+                           const int32_t* kept_offsets, int T, int N, int K, float* weights,
+                           void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * grpo_masked_actor_step -- Eq. 11 (Eq. 2 when kept_idx lists every chunk), with the PPO
  * clipping the paper leaves out of Eq. 2 for clarity (thresholds as in App. D).
  *

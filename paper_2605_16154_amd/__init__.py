@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     lib,
     library_path,
     pcm_adamw_clip_step,
+    pcm_importance_weights,
     pcm_profile_collect,
     pcm_profile_enable,
     pcm_sample_chunks,

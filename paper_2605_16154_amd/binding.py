@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
     _sig(L.pcm_update_keep_probs, i32, [vp, vp, vp, i32, f64, i32, vp, vp])
     _sig(L.pcm_sample_chunks_workspace_bytes, sz, [i32] * 4)
     _sig(L.pcm_sample_chunks, i32, [vp, vp, vp, vp, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, sz, vp])
+    _sig(L.pcm_sample_chunks_ex, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, sz, vp])
+    _sig(L.pcm_importance_weights, i32, [vp, vp, vp, vp, i32, i32, i32, vp, vp])
     _sig(L.grpo_masked_actor_step_workspace_bytes, sz, [i32] * 7)
     _sig(L.grpo_masked_actor_step, i32,
          [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, f32,
@@ -158,8 +160,17 @@ def pcm_update_keep_probs(state, Cc, valid, p_min: float = 0.1, T_rc: int = 5, k
     return keep_probs_out
 
 
-def pcm_sample_chunks(keep_probs, phase, n_chunks, active, B: int, seed: int, step: int, out=None):
-    """-> (kept_idx i32[T*min(B,N)], kept_offsets i32[T+1], n_kept i32[1])."""
+SELECTORS = {"pcm": 0, "random": 1, "top_phase": 2}
+
+
+def pcm_sample_chunks(keep_probs, phase, n_chunks, active, B: int, seed: int, step: int, out=None,
+                      selector: str = "pcm"):
+    """-> (kept_idx i32[T*min(B,N)], kept_offsets i32[T+1], n_kept i32[1]).
+
+    selector "pcm" calls pcm_sample_chunks; "random" and "top_phase" (the ablations) pcm_sample_chunks_ex.
+    """
+    if selector not in SELECTORS:
+        raise PcmError(f"unknown selector {selector!r}")
     T, N = phase.shape
     K = keep_probs.shape[0]
     dev = phase.device
@@ -169,12 +180,27 @@ def pcm_sample_chunks(keep_probs, phase, n_chunks, active, B: int, seed: int, st
     kept_idx, kept_offsets, n_kept = out
     need = lib().pcm_sample_chunks_workspace_bytes(T, N, K, B)
     ws, ws_bytes = _workspace(need, dev)
-    rc = lib().pcm_sample_chunks(_ptr(keep_probs, torch.float64, "keep_probs"), _ptr(phase, torch.uint8, "phase"),
-                                 _ptr(n_chunks, torch.int32, "n_chunks"), _ptr(active, torch.uint8, "active"),
-                                 T, N, K, B, seed & 0xFFFFFFFFFFFFFFFF, step & 0xFFFFFFFFFFFFFFFF,
-                                 _ptr(kept_idx, torch.int32, "kept_idx"), _ptr(kept_offsets, torch.int32, "kept_offsets"),
-                                 _ptr(n_kept, torch.int32, "n_kept"), ws, ws_bytes, _stream())
-    _check(rc, "pcm_sample_chunks")
+    head = (_ptr(keep_probs, torch.float64, "keep_probs"), _ptr(phase, torch.uint8, "phase"),
+            _ptr(n_chunks, torch.int32, "n_chunks"), _ptr(active, torch.uint8, "active"), T, N, K, B)
+    tail = (seed & 0xFFFFFFFFFFFFFFFF, step & 0xFFFFFFFFFFFFFFFF, _ptr(kept_idx, torch.int32, "kept_idx"),
+            _ptr(kept_offsets, torch.int32, "kept_offsets"), _ptr(n_kept, torch.int32, "n_kept"), ws, ws_bytes, _stream())
+    if selector == "pcm":
+        _check(lib().pcm_sample_chunks(*head, *tail), "pcm_sample_chunks")
+    else:
+        _check(lib().pcm_sample_chunks_ex(*head, SELECTORS[selector], *tail), "pcm_sample_chunks_ex")
+    return out
+
+
+def pcm_importance_weights(phase, n_chunks, kept_idx, kept_offsets, K: int, out=None):
+    """-> f32 [len(kept_idx)]: N_c / b_c per kept chunk (entries beyond the kept count are left as they are)."""
+    T, N = phase.shape
+    if out is None:
+        out = torch.zeros(kept_idx.shape[0], dtype=torch.float32, device=phase.device)
+    rc = lib().pcm_importance_weights(_ptr(phase, torch.uint8, "phase"), _ptr(n_chunks, torch.int32, "n_chunks"),
+                                      _ptr(kept_idx, torch.int32, "kept_idx"),
+                                      _ptr(kept_offsets, torch.int32, "kept_offsets"), T, N, K,
+                                      _ptr(out, torch.float32, "weights"), _stream())
+    _check(rc, "pcm_importance_weights")
     return out
 
 

@@ -36,10 +36,32 @@ __device__ inline uint64_t philox_bits(uint32_t c0, uint32_t c1, uint32_t c2, ui
     return (uint64_t)c0 | ((uint64_t)c1 << 32);
 }
 
-__device__ inline int kept_count(const int32_t* n_chunks, const uint8_t* active, int i, int N, int B) {
+// Index of the largest keep probability, lowest index on ties (the one phase the "top phase"
+// selector draws from).
+__device__ inline int top_phase(const double* keep_probs, int K) {
+    int best = 0;
+    for (int c = 1; c < K; ++c)
+        if (keep_probs[c] > keep_probs[best]) best = c;
+    return best;
+}
+
+// Chunks a trajectory keeps: min(B, eligible chunks), 0 if inactive.  Every valid chunk is eligible
+// except under the top-phase selector, where only chunks of phase `only` (>= 0) are.
+__device__ inline int kept_count(const int32_t* n_chunks, const uint8_t* active, const uint8_t* phase, int i, int N,
+                                 int K, int B, int only) {
     if (active && !active[i]) return 0;
     int Ni = n_chunks ? n_chunks[i] : N;
     Ni = Ni < 0 ? 0 : (Ni > N ? N : Ni);
+    if (only >= 0) {
+        const uint8_t* ph = phase + (size_t)i * N;
+        int n = 0;
+        for (int k = 0; k < Ni; ++k) {
+            int c = ph[k];
+            c = c < K ? c : K - 1;
+            n += c == only;
+        }
+        Ni = n;
+    }
     return Ni < B ? Ni : B;
 }
 
@@ -52,15 +74,18 @@ __device__ inline int wave_inclusive_scan(int v, int lane) {
     return v;
 }
 
-__global__ __launch_bounds__(kThreads) void sample_scan(const int32_t* __restrict__ n_chunks,
-                                                        const uint8_t* __restrict__ active, int T, int N,
-                                                        int B, int32_t* kept_offsets, int32_t* n_kept) {
+__global__ __launch_bounds__(kThreads) void sample_scan(const double* __restrict__ keep_probs,
+                                                        const uint8_t* __restrict__ phase,
+                                                        const int32_t* __restrict__ n_chunks,
+                                                        const uint8_t* __restrict__ active, int T, int N, int K,
+                                                        int B, int selector, int32_t* kept_offsets, int32_t* n_kept) {
     __shared__ int wave_total[kWavesPerBlock];
     const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+    const int only = selector == PCM_SELECT_TOP_PHASE ? top_phase(keep_probs, K) : -1;
     int carry = 0;
     for (int base = 0; base < T; base += kThreads) {
         const int i = base + tid;
-        const int cnt = i < T ? kept_count(n_chunks, active, i, N, B) : 0;
+        const int cnt = i < T ? kept_count(n_chunks, active, phase, i, N, K, B, only) : 0;
         const int incl = wave_inclusive_scan(cnt, lane);
         if (lane == kWave - 1) wave_total[wv] = incl;
         __syncthreads();
@@ -84,25 +109,30 @@ __global__ __launch_bounds__(kThreads) void sample_scan(const int32_t* __restric
 __global__ __launch_bounds__(kThreads) void sample_compact(
     const double* __restrict__ keep_probs, const uint8_t* __restrict__ phase,
     const int32_t* __restrict__ n_chunks, const uint8_t* __restrict__ active, int T, int N, int K, int B,
-    uint64_t seed, uint64_t step, const int32_t* __restrict__ kept_offsets, int32_t* kept_idx) {
+    int selector, uint64_t seed, uint64_t step, const int32_t* __restrict__ kept_offsets, int32_t* kept_idx) {
     extern __shared__ uint32_t lds[];
     uint32_t* qtab = lds;
     const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
     uint32_t* w = lds + PCM_MAX_PHASES + (size_t)wv * N;
 
     const int waves_per_block = blockDim.x / kWave;
+    const int only = selector == PCM_SELECT_TOP_PHASE ? top_phase(keep_probs, K) : -1;
     for (int c = tid; c < K; c += blockDim.x) {
-        const double x = keep_probs[c] * 65536.0 + 0.5;
-        uint32_t q = 1u;
-        if (x >= 65536.0) q = 65536u;
-        else if (x >= 1.0) q = (uint32_t)x;   // truncation = floor for positive x
+        uint32_t q = 1u;                      // uniform selector: equal weights
+        if (selector == PCM_SELECT_PCM) {
+            const double x = keep_probs[c] * 65536.0 + 0.5;
+            if (x >= 65536.0) q = 65536u;
+            else if (x >= 1.0) q = (uint32_t)x;   // truncation = floor for positive x
+        } else if (selector == PCM_SELECT_TOP_PHASE) {
+            q = c == only ? 1u : 0u;
+        }
         qtab[c] = q;
     }
     __syncthreads();
 
     const int i = blockIdx.x * waves_per_block + wv;
     if (i >= T) return;                       // no barrier below this point
-    const int m = kept_count(n_chunks, active, i, N, B);
+    const int m = kept_count(n_chunks, active, phase, i, N, K, B, only);
     if (m == 0) return;
     int Ni = n_chunks ? n_chunks[i] : N;
     Ni = Ni > N ? N : Ni;
@@ -180,17 +210,20 @@ extern "C" size_t pcm_sample_chunks_workspace_bytes(int T, int N, int K, int B) 
     return 0;   // offsets and counts live in the caller's output arrays
 }
 
-extern "C" int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
-                                 const uint8_t* active, int T, int N, int K, int B, uint64_t seed,
-                                 uint64_t step, int32_t* kept_idx, int32_t* kept_offsets, int32_t* n_kept,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes;
+namespace {
+
+int run_sample(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks, const uint8_t* active, int T,
+               int N, int K, int B, int selector, uint64_t seed, uint64_t step, int32_t* kept_idx,
+               int32_t* kept_offsets, int32_t* n_kept, void* stream) {
     if (!keep_probs || !phase || !kept_idx || !kept_offsets || !n_kept) return PCM_EINVAL;
     if (!shape_ok(T, N, K, B)) return PCM_EINVAL;
+    if (selector != PCM_SELECT_PCM && selector != PCM_SELECT_RANDOM && selector != PCM_SELECT_TOP_PHASE)
+        return PCM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
         StageTimer t(ST_SAMPLE_SCAN, s);
-        sample_scan<<<1, kThreads, 0, s>>>(n_chunks, active, T, N, B, kept_offsets, n_kept);
+        sample_scan<<<1, kThreads, 0, s>>>(keep_probs, phase, n_chunks, active, T, N, K, B, selector, kept_offsets,
+                                           n_kept);
     }
     {
         StageTimer t(ST_SAMPLE_COMPACT, s);
@@ -198,7 +231,80 @@ extern "C" int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase,
         const int waves = N > 2048 ? 2 : kWavesPerBlock;
         const size_t lds_bytes = (PCM_MAX_PHASES + (size_t)waves * N) * sizeof(uint32_t);
         sample_compact<<<ceil_div(T, waves), waves * kWave, lds_bytes, s>>>(
-            keep_probs, phase, n_chunks, active, T, N, K, B, seed, step, kept_offsets, kept_idx);
+            keep_probs, phase, n_chunks, active, T, N, K, B, selector, seed, step, kept_offsets, kept_idx);
     }
+    return launch_status();
+}
+
+// One wavefront per trajectory: per-phase counts of its valid chunks and of its kept chunks in LDS,
+// then weight = N_c / b_c for each kept chunk.
+__global__ __launch_bounds__(kThreads) void importance_weights(const uint8_t* __restrict__ phase,
+                                                               const int32_t* __restrict__ n_chunks,
+                                                               const int32_t* __restrict__ kept_idx,
+                                                               const int32_t* __restrict__ kept_offsets, int T, int N,
+                                                               int K, float* __restrict__ weights) {
+    __shared__ int counts[kWavesPerBlock][2][PCM_MAX_PHASES];
+    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+    const int i = blockIdx.x * kWavesPerBlock + wv;
+    if (i >= T) return;                       // no workgroup barrier below
+    int* all = counts[wv][0];
+    int* kept = counts[wv][1];
+    for (int c = lane; c < K; c += kWave) {
+        all[c] = 0;
+        kept[c] = 0;
+    }
+    __builtin_amdgcn_wave_barrier();
+    int Ni = n_chunks ? n_chunks[i] : N;
+    Ni = Ni < 0 ? 0 : (Ni > N ? N : Ni);
+    const uint8_t* ph = phase + (size_t)i * N;
+    for (int k = lane; k < Ni; k += kWave) {
+        int c = ph[k];
+        c = c < K ? c : K - 1;
+        atomicAdd(&all[c], 1);
+    }
+    const int lo = kept_offsets[i], hi = kept_offsets[i + 1];
+    for (int j = lo + lane; j < hi; j += kWave) {
+        const int k = kept_idx[j] - i * N;
+        int c = (k >= 0 && k < N) ? ph[k] : 0;
+        c = c < K ? c : K - 1;
+        atomicAdd(&kept[c], 1);
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int j = lo + lane; j < hi; j += kWave) {
+        const int k = kept_idx[j] - i * N;
+        int c = (k >= 0 && k < N) ? ph[k] : 0;
+        c = c < K ? c : K - 1;
+        weights[j] = (float)all[c] / (float)kept[c];
+    }
+}
+
+}  // namespace
+
+extern "C" int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
+                                 const uint8_t* active, int T, int N, int K, int B, uint64_t seed,
+                                 uint64_t step, int32_t* kept_idx, int32_t* kept_offsets, int32_t* n_kept,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    return run_sample(keep_probs, phase, n_chunks, active, T, N, K, B, PCM_SELECT_PCM, seed, step, kept_idx,
+                      kept_offsets, n_kept, stream);
+}
+
+extern "C" int pcm_sample_chunks_ex(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
+                                    const uint8_t* active, int T, int N, int K, int B, int selector, uint64_t seed,
+                                    uint64_t step, int32_t* kept_idx, int32_t* kept_offsets, int32_t* n_kept,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    return run_sample(keep_probs, phase, n_chunks, active, T, N, K, B, selector, seed, step, kept_idx, kept_offsets,
+                      n_kept, stream);
+}
+
+extern "C" int pcm_importance_weights(const uint8_t* phase, const int32_t* n_chunks, const int32_t* kept_idx,
+                                      const int32_t* kept_offsets, int T, int N, int K, float* weights, void* stream) {
+    if (!phase || !kept_idx || !kept_offsets || !weights) return PCM_EINVAL;
+    if (!shape_ok(T, N, K, 1)) return PCM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    StageTimer t(ST_SAMPLE_COMPACT, s);
+    importance_weights<<<ceil_div(T, kWavesPerBlock), kThreads, 0, s>>>(phase, n_chunks, kept_idx, kept_offsets, T, N,
+                                                                        K, weights);
     return launch_status();
 }

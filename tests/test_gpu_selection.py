@@ -110,14 +110,21 @@ def test_keep_probs_chain_bit_exact(pcm):
     assert np.array_equal(p.cpu().numpy(), [0.25, 0.25, 0.25])
 
 
-def _sample_both(pcm, p, phase, n_chunks, active, B, seed, step):
-    kept_o, off_o, nk_o = O.sample_chunks(p, phase, n_chunks, active, B, seed, step)
-    kept, off, nk = pcm.pcm_sample_chunks(dev(p), dev(phase), None if n_chunks is None else dev(n_chunks),
-                                          None if active is None else dev(active), B, seed, step)
+def _sample_both(pcm, p, phase, n_chunks, active, B, seed, step, selector="pcm", weights=False):
+    kept_o, off_o, nk_o = O.sample_chunks(p, phase, n_chunks, active, B, seed, step, selector=selector)
+    d_nch = None if n_chunks is None else dev(n_chunks)
+    kept, off, nk = pcm.pcm_sample_chunks(dev(p), dev(phase), d_nch, None if active is None else dev(active), B, seed,
+                                          step, selector=selector)
     torch.cuda.synchronize()
     assert int(nk.item()) == nk_o
     assert np.array_equal(off.cpu().numpy(), off_o)
     assert np.array_equal(kept.cpu().numpy()[:nk_o], kept_o)
+    if weights:
+        w = pcm.pcm_importance_weights(dev(phase), d_nch, kept, off, len(p))
+        torch.cuda.synchronize()
+        ref = O.importance_weights(phase, n_chunks, kept_o, len(p))
+        assert np.array_equal(w.cpu().numpy()[:nk_o].view(np.int32), ref.view(np.int32))   # bit for bit
+    return kept_o, off_o
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
@@ -129,6 +136,57 @@ def test_sample_chunks_bit_exact(pcm, name):
     p[rng.integers(0, cfg.K)] = 1.0
     _, active = O.advantages(ro["reward"], cfg.G)
     _sample_both(pcm, p, ro["phase"], ro["n_chunks"], active, cfg.B, seed=cfg.seed, step=3)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "cfg5"])
+@pytest.mark.parametrize("selector", ["random", "top_phase"])
+def test_ablation_selectors_bit_exact(pcm, name, selector):
+    cfg = CONFIGS[name]
+    ro = make_rollouts(cfg, 0)
+    rng = np.random.default_rng(cfg.seed + 17)
+    p = np.maximum(0.1, rng.random(cfg.K))
+    p[rng.integers(0, cfg.K)] = 1.0
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, off = _sample_both(pcm, p, ro["phase"], ro["n_chunks"], active, cfg.B, seed=cfg.seed, step=5, selector=selector)
+    if selector == "top_phase":
+        assert np.all(ro["phase"].reshape(-1)[kept] == int(np.argmax(p)))
+
+
+def test_ablation_selectors_edge_cases(pcm):
+    cfg = CONFIGS["cfg1"].with_(n_groups=9)
+    ro = make_rollouts(cfg, 1)
+    n = ragged_n_chunks(cfg)
+    active = (np.arange(cfg.T) % 5 != 0).astype(np.uint8)
+    p_tie = np.array([0.4, 1.0, 1.0, 0.1])                     # tie: the lower index wins
+    for selector in ("random", "top_phase"):
+        _sample_both(pcm, p_tie, ro["phase"], n, active, cfg.B, seed=2 ** 40 + 7, step=2 ** 33 + 1, selector=selector)
+        _sample_both(pcm, p_tie, ro["phase"], n, None, cfg.N + 5, seed=1, step=0, selector=selector)
+        _sample_both(pcm, p_tie, ro["phase"], None, np.zeros(cfg.T, np.uint8), cfg.B, seed=1, step=0, selector=selector)
+    # a top phase that no trajectory contains: nothing is kept
+    p_none = np.array([0.1, 0.1, 0.1, 0.1, 1.0])
+    kept, off = _sample_both(pcm, p_none, np.minimum(ro["phase"], 3), None, None, cfg.B, 1, 0, selector="top_phase")
+    assert len(kept) == 0
+    rng = np.random.default_rng(2)
+    for N, B in [(100, 17), (4096, 64), (3000, 5)]:
+        phase = np.sort(rng.integers(0, 9, size=(6, N)), axis=1).astype(np.uint8)
+        pk = np.maximum(0.1, rng.random(9))
+        nn = rng.integers(0, N + 1, size=6).astype(np.int32)
+        for selector in ("random", "top_phase"):
+            _sample_both(pcm, pk, phase, nn, None, B, seed=N, step=B, selector=selector)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "cfg5"])
+def test_importance_weights_bit_exact(pcm, name):
+    cfg = CONFIGS[name]
+    ro = make_rollouts(cfg, 0)
+    rng = np.random.default_rng(cfg.seed + 3)
+    p = np.maximum(0.1, rng.random(cfg.K))
+    _, active = O.advantages(ro["reward"], cfg.G)
+    _sample_both(pcm, p, ro["phase"], ro["n_chunks"], active, cfg.B, seed=cfg.seed, step=1, weights=True)
+    if name == "cfg1":
+        n = ragged_n_chunks(cfg)
+        _sample_both(pcm, p, ro["phase"], n, None, cfg.B, seed=3, step=1, weights=True)
+        _sample_both(pcm, p, ro["phase"], n, None, cfg.B, seed=3, step=1, selector="top_phase", weights=True)
 
 
 def test_sample_chunks_edge_cases(pcm):
