@@ -17,6 +17,7 @@ Parity status of each function (what pins it is in tests/test_oracle_*.py):
   philox4x32_10       pinned: published known-answer vectors of the generator
   sample_chunks       pinned: brute-force Plackett-Luce enumeration on tiny inputs
   compact / sample    pinned: set properties (|K_i| = min(B, N_i), ascending, unique)
+  label_phases        pinned: hand-labelled gripper traces, one per rule and per overlap of windows
   selectors, weights  pinned: uniform inclusion frequencies of "random", phase purity and counts of
                       "top_phase", sum of N_c / b_c over a phase's kept chunks = N_c, hand example
   actor_step          pinned by invariants only (finite differences, all-kept = unmasked,
@@ -225,6 +226,62 @@ def rng64(seed, step, traj, rnd):
     step = int(step) & MASK64
     out = philox4x32_10((traj, rnd, step & MASK32, step >> 32), (seed & MASK32, seed >> 32))
     return out[0] | (out[1] << 32)
+
+
+# ----------------------------------------------------------------------------------------
+# App. D, phase allotment rules -- gripper-based phase labels
+# ----------------------------------------------------------------------------------------
+
+PHASE_APPROACH, PHASE_PRE_GRASP, PHASE_ACTIVE_GRIP, PHASE_RELEASE_RAMP, PHASE_TAIL = 0, 1, 2, 3, 4
+
+
+def label_phases(actions, n_chunks, L, D, gripper_dim=None, close_threshold=0.0):
+    """Deterministic gripper-based phase label of every chunk (App. D, phase allotment rules).
+
+    actions [T, N, L*D]: L timesteps of D values per chunk; the gripper-close command of a
+    timestep is active when its gripper value (dimension `gripper_dim`, the last one by
+    default) exceeds `close_threshold`.  With n_j the number of active timesteps of chunk j
+    (g_f = n_j / L, compared exactly through integers):
+      sustained close   g_f >= 0.75; maximal runs of such chunks are the grasp intervals
+      active-grip       g_f >= 0.5
+      pre-grasp         one of the three chunks right before a grasp interval, 0.1 <= g_f < 0.5
+      release-ramp      one of the three chunks right after a grasp interval, g_f < 0.5
+      approach          g_f < 0.5 and a grasp interval begins later in the trajectory
+      tail              what remains after the last grasp interval
+    with priority active-grip > pre-grasp > release-ramp > approach > tail where windows overlap.
+    Readings where the rules leave a gap: the window tests apply chunk by chunk (a chunk that
+    fails its threshold does not end the window); a trajectory without any grasp interval is
+    all approach (nothing has been grasped yet) apart from its active-grip chunks; chunks after
+    the last interval that are neither in its release window nor open (g_f >= 0.1) are tail.
+    Returns u8 [T, N]; chunk slots at and beyond n_chunks[i] get 0.
+    """
+    actions = np.asarray(actions)
+    T, N, LD = actions.shape
+    assert LD == L * D
+    g = D - 1 if gripper_dim is None else gripper_dim
+    n_chunks = np.full(T, N, dtype=np.int64) if n_chunks is None else np.asarray(n_chunks, dtype=np.int64)
+    out = np.zeros((T, N), dtype=np.uint8)
+    for i in range(T):
+        Ni = int(min(max(n_chunks[i], 0), N))
+        count = [int(sum(1 for t in range(L) if actions[i, j, t * D + g] > close_threshold)) for j in range(Ni)]
+        sustained = [4 * c >= 3 * L for c in count]
+        last = max((j for j in range(Ni) if sustained[j]), default=-1)
+        for j in range(Ni):
+            c = count[j]
+            if 2 * c >= L:
+                out[i, j] = PHASE_ACTIVE_GRIP
+                continue
+            before_grasp = any(sustained[k] for k in range(j + 1, min(j + 4, Ni)))
+            after_grasp = any(sustained[k] for k in range(max(j - 3, 0), j))
+            if before_grasp and 10 * c >= L:
+                out[i, j] = PHASE_PRE_GRASP
+            elif after_grasp:
+                out[i, j] = PHASE_RELEASE_RAMP
+            elif last < 0 or j < last:
+                out[i, j] = PHASE_APPROACH
+            else:
+                out[i, j] = PHASE_TAIL
+    return out
 
 
 # ----------------------------------------------------------------------------------------
