@@ -161,7 +161,8 @@ def cpu_baseline(wl, kept_host, sample_chunks):
 
 
 def selection_only(cfg, dev, steps, warmup):
-    """Times the three selection calls alone (any configuration; no hidden states or weights needed)."""
+    """Times the three selection calls alone (any configuration; no hidden states or weights needed), preceded by the
+    phase labeler on gripper-structured actions of the same shape."""
     import torch
     import paper_2605_16154_amd as pcm
     from workloads import make_rollouts
@@ -170,9 +171,13 @@ def selection_only(cfg, dev, steps, warmup):
     actions, phase, reward, n_chunks = t(ro["actions"]), t(ro["phase"]), t(ro["reward"]), t(ro["n_chunks"])
     state = pcm.pcm_state_init(cfg.K, dev)
     sel = samp = None
+    from workloads import make_gripper_actions
+    grip = t(make_gripper_actions(cfg, 0))
+    labels = torch.empty((cfg.T, cfg.N), dtype=torch.uint8, device=dev)
 
     def one(step):
         nonlocal sel, samp
+        pcm.pcm_label_phases(grip, n_chunks, cfg.L, cfg.D, out=labels)
         sel = pcm.pcm_score_phases(actions, phase, reward, n_chunks, cfg.n_groups, cfg.G, cfg.K, 1e-6, out=sel)
         p = pcm.pcm_update_keep_probs(state, sel[0], sel[1], 0.1, 5)
         samp = pcm.pcm_sample_chunks(p, phase, n_chunks, sel[3], cfg.B, cfg.seed, step, out=samp)
@@ -198,7 +203,8 @@ def selection_only(cfg, dev, steps, warmup):
     pcm.pcm_profile_enable(False)
     n_kept = int(samp[2].item())
     chunks = cfg.T * cfg.N
-    alg_bytes = {"score_accumulate": chunks * (cfg.A * 4 + 1) + cfg.T, "sample_compact": chunks + 4 * n_kept + 4 * cfg.T}
+    alg_bytes = {"score_accumulate": chunks * (cfg.A * 4 + 1) + cfg.T, "sample_compact": chunks + 4 * n_kept + 4 * cfg.T,
+                 "label_phases": chunks * (cfg.A * 4 + 1)}     # the gripper values sit 4 D bytes apart: whole sectors move
     out = {}
     for name, (ms, n) in stages.items():
         if n == 0:

@@ -80,6 +80,31 @@ PCM_API size_t pcm_state_bytes(int K);
 PCM_API int pcm_state_init(void* state, int K, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * pcm_label_phases -- the deterministic gripper-based phase label of every chunk (App. D, phase
+ * allotment rules); produces the `phase` input of pcm_score_phases and pcm_sample_chunks.
+ *
+ * A timestep's gripper-close command is active when actions[.., t*D + gripper_dim] exceeds
+ * close_threshold; g_f of a chunk is the fraction of its L timesteps with an active command.
+ * Chunks with g_f >= 0.75 are "sustained close"; maximal runs of them are the grasp intervals.
+ * Labels, highest priority first:
+ *   2 active-grip    g_f >= 0.5
+ *   1 pre-grasp      one of the three chunks right before a grasp interval and 0.1 <= g_f < 0.5
+ *   3 release-ramp   one of the three chunks right after a grasp interval (g_f < 0.5)
+ *   0 approach       g_f < 0.5 and a grasp interval begins later in the trajectory, or the
+ *                    trajectory has no grasp interval at all
+ *   4 tail           the rest: after the last grasp interval and outside its release window
+ * (so K = 5).  The outcome of the rollout is not an input.
+ *
+ *   actions   device f32 [T, N, L*D]: per chunk, L timesteps of D values
+ *   n_chunks  device i32 [T] or NULL (all N); clamped to [0, N]; slots beyond it get label 0
+ *   phase     device u8 [T, N], written
+ * Errors: PCM_EINVAL for null pointers, N > PCM_MAX_CHUNK_SLOTS, gripper_dim outside [0, D),
+ * NaN threshold, non-positive sizes.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API int pcm_label_phases(const float* actions, const int32_t* n_chunks, int T, int N, int L, int D,
+                     int gripper_dim, float close_threshold, uint8_t* phase, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * pcm_score_phases -- Eq. 1 and Eq. 5 (with the skip rule of App. D.2, last paragraph).
  *
  * For every group with both outcomes and every phase c: pool the group's chunks of phase c

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     library_path,
     pcm_adamw_clip_step,
     pcm_importance_weights,
+    pcm_label_phases,
     pcm_profile_collect,
     pcm_profile_enable,
     pcm_sample_chunks,

@@ -50,6 +50,7 @@ def lib() -> C.CDLL:
     _sig(L.pcm_status_string, C.c_char_p, [i32])
     _sig(L.pcm_state_bytes, sz, [i32])
     _sig(L.pcm_state_init, i32, [vp, i32, vp])
+    _sig(L.pcm_label_phases, i32, [vp, vp, i32, i32, i32, i32, i32, f32, vp, vp])
     _sig(L.pcm_score_phases_workspace_bytes, sz, [i32] * 5)
     _sig(L.pcm_score_phases, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f64, vp, vp, vp, vp, vp, sz, vp])
     _sig(L.pcm_update_keep_probs, i32, [vp, vp, vp, i32, f64, i32, vp, vp])
@@ -127,6 +128,21 @@ def pcm_state_init(K: int, device="cuda") -> torch.Tensor:
     state = torch.empty(nbytes // 8, dtype=torch.int64, device=device)
     _check(lib().pcm_state_init(state.data_ptr(), K, _stream()), "pcm_state_init")
     return state
+
+
+def pcm_label_phases(actions, n_chunks, L: int, D: int, gripper_dim: Optional[int] = None, close_threshold: float = 0.0,
+                     out=None):
+    """actions f32 [T, N, L*D] -> phase u8 [T, N] (0 approach, 1 pre-grasp, 2 active-grip, 3 release-ramp, 4 tail)."""
+    T, N, A = actions.shape
+    if A != L * D:
+        raise PcmError("actions must be [T, N, L*D]")
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.uint8, device=actions.device)
+    g = D - 1 if gripper_dim is None else gripper_dim
+    rc = lib().pcm_label_phases(_ptr(actions, torch.float32, "actions"), _ptr(n_chunks, torch.int32, "n_chunks"), T, N,
+                                L, D, g, close_threshold, _ptr(out, torch.uint8, "phase"), _stream())
+    _check(rc, "pcm_label_phases")
+    return out
 
 
 def pcm_score_phases(actions, phase, reward, n_chunks, n_groups: int, G: int, K: int, adv_eps: float = 1e-6,

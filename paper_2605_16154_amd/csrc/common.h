@@ -61,6 +61,7 @@ enum Stage : int {
     ST_F32_BACKWARD,
     ST_OPT_NORM,
     ST_OPT_ADAMW,
+    ST_LABEL_PHASES,
     ST_COUNT
 };
 

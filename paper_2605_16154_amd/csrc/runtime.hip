@@ -12,7 +12,8 @@ const char* const kStageNames[ST_COUNT] = {
     "sample_compact",  "weight_layout",    "transpose",      "zero_fill",   "gather",         "gemm_gate_up", "gemm_down",
     "gemm_logits_loss", "gemm_dWo",        "gemm_dy",        "gemm_dWd",    "gemm_da",
     "gemm_dWg_dWu",    "gemm_dX",          "reduce",         "f32_forward", "f32_loss",
-    "f32_backward",    "opt_grad_norm",    "opt_adamw"};
+    "f32_backward",    "opt_grad_norm",    "opt_adamw",
+    "label_phases"};
 
 struct Pending {
     int stage;

@@ -9,6 +9,7 @@ from .rollouts import (  # noqa: F401
     CONFIGS,
     RolloutConfig,
     make_head_numpy,
+    make_gripper_actions,
     make_head_torch,
     make_hidden_numpy,
     make_hidden_torch,

@@ -162,6 +162,40 @@ def make_rollouts(cfg: RolloutConfig, step: int = 0) -> Dict[str, np.ndarray]:
             "n_chunks": n_chunks, "divergent": gap}
 
 
+def make_gripper_actions(cfg: RolloutConfig, step: int = 0) -> np.ndarray:
+    """Continuous actions [T, N, L*D] whose last dimension is a gripper command in {-1 (open), +1 (close)}
+    with manipulation-like structure: per trajectory zero, one or two grasp cycles (open approach, a few
+    chunks in which the command starts to flicker closed, a held grasp with occasional drop-outs, a release
+    with flicker, an open tail), plus 3 % random flips of single timesteps.  Other dimensions are noise."""
+    r = _rng(cfg.seed, 0x6A1B, step)
+    T, N, L, D = cfg.T, cfg.N, cfg.L, cfg.D
+    a = r.uniform(-1, 1, size=(T, N, L, D)).astype(np.float32)
+    close_prob = np.zeros((T, N))
+    for i in range(T):
+        cycles = int(r.integers(0, 3))
+        pos = int(r.integers(1, max(2, N // 4)))
+        for _ in range(cycles):
+            ramp = int(r.integers(0, 4))
+            hold = int(r.integers(1, max(2, N // 4)))
+            release = int(r.integers(0, 4))
+            for k in range(ramp):
+                if pos + k < N:
+                    close_prob[i, pos + k] = r.uniform(0.05, 0.6)
+            pos += ramp
+            close_prob[i, pos:pos + hold] = r.uniform(0.7, 1.0, size=len(close_prob[i, pos:pos + hold]))
+            pos += hold
+            for k in range(release):
+                if pos + k < N:
+                    close_prob[i, pos + k] = r.uniform(0.0, 0.6)
+            pos += release + int(r.integers(0, max(1, N // 6)))
+            if pos >= N:
+                break
+    cmd = r.random((T, N, L)) < close_prob[:, :, None]
+    cmd ^= r.random((T, N, L)) < 0.03
+    a[..., D - 1] = np.where(cmd, 1.0, -1.0)
+    return a.reshape(T, N, L * D)
+
+
 def ragged_n_chunks(cfg: RolloutConfig, salt: int = 0) -> np.ndarray:
     """Per-trajectory valid chunk counts in [0, N], including 0, values below B and N."""
     r = _rng(cfg.seed, 0xC0DE, salt)
