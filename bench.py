@@ -113,11 +113,15 @@ def timed_steps(wl, steps, warmup, B=None, profile=False, **loss_variants):
     torch.cuda.synchronize()
     if profile:
         wl.pcm.pcm_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
+    marks[0].record()
     for t in range(warmup, warmup + steps):
         nk = wl.step(t, B, **loss_variants)
+        marks[t - warmup + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    wl.step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))   # per-step device time
     stages = None
     if profile:
         stages = wl.pcm.pcm_profile_collect()
@@ -296,6 +300,7 @@ def main():
     dt, n_kept, stages = timed_steps(wl, args.steps, args.warmup, profile=True)
     rows = n_kept * cfg.A
     ms_step = dt / args.steps * 1e3
+    step_ms = list(wl.step_ms)
     value = rows * args.steps / dt
 
     flops = gemm_flops_per_launch(rows, cfg.d, cfg.ff, cfg.V)
@@ -321,6 +326,7 @@ def main():
 
     result = {"metric": "kept_action_tokens_per_sec_masked_grpo_actor_step", "value": value, "unit": "tokens/s",
               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+              "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
               "data": "synthetic",
               "config": {"workload": f"{cfg.name}: {cfg.n_groups} groups x {cfg.G} rollouts, {cfg.N} chunks x {cfg.A} tokens, "

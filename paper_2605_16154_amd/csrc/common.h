@@ -43,8 +43,6 @@ enum Stage : int {
     ST_SAMPLE_SCAN,
     ST_SAMPLE_COMPACT,
     ST_WEIGHT_LAYOUT,
-    ST_TRANSPOSE,
-    ST_ZERO_FILL,
     ST_GATHER,
     ST_GEMM_GATE_UP,
     ST_GEMM_DOWN,

@@ -76,7 +76,7 @@ extern "C" int pcm_label_phases(const float* actions, const int32_t* n_chunks, i
         return PCM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     StageTimer t(ST_LABEL_PHASES, s);
-    const int waves = N > 8192 ? 1 : kWavesPerBlock;    // N <= 4096: four count arrays of 2 N bytes fit easily
+    const int waves = kWavesPerBlock;                   // N <= 4096: four count arrays of 2 N bytes are 32 KB at most
     label_phases<<<ceil_div(T, waves), waves * kWave, (size_t)waves * N * sizeof(uint16_t), s>>>(
         actions, n_chunks, T, N, L, D, gripper_dim, close_threshold, phase);
     return launch_status();

@@ -9,7 +9,7 @@ namespace {
 
 const char* const kStageNames[ST_COUNT] = {
     "score_prepare",   "score_accumulate", "score_finalise", "keep_probs",  "sample_scan",
-    "sample_compact",  "weight_layout",    "transpose",      "zero_fill",   "gather",         "gemm_gate_up", "gemm_down",
+    "sample_compact",  "weight_layout",    "gather",         "gemm_gate_up", "gemm_down",
     "gemm_logits_loss", "gemm_dWo",        "gemm_dy",        "gemm_dWd",    "gemm_da",
     "gemm_dWg_dWu",    "gemm_dX",          "reduce",         "f32_forward", "f32_loss",
     "f32_backward",    "opt_grad_norm",    "opt_adamw",
