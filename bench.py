@@ -262,6 +262,9 @@ def main():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unmasked", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the legs after the timed steps (loss variants, optimizer step): with --no-unmasked and "
+                         "--no-cpu-baseline the timed steps are then the last launches of the process")
     ap.add_argument("--cpu-sample-chunks", type=int, default=192)
     ap.add_argument("--selection-only", action="store_true",
                     help="time only the three selection calls of --config and print their bytes and GB/s")
@@ -342,7 +345,7 @@ def main():
         result["unmasked"] = {"ms_per_step": ms_un, "kept_rows": n_un * cfg.A, "tokens_per_s": n_un * cfg.A * k_un / dt_un,
                               "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
                               "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
-    if cfg.dtype == "bf16":
+    if cfg.dtype == "bf16" and not args.no_extras:
         # the same step with the loss of App. D (entropy bonus 1e-3, token-mean normalisation) and with one
         # ratio per chunk: extended entry point, same kernels plus two small ones in the per-chunk case
         wl.state = pcm.pcm_state_init(cfg.K, dev)
