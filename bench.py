@@ -306,6 +306,11 @@ def main():
     step_ms = list(wl.step_ms)
     value = rows * args.steps / dt
 
+    # what the matrix cores sustain with no memory traffic at all (power-limited; depends on the operand data)
+    tf_rand, clk_rand = pcm.pcm_measure_mfma_rate(True, 100)
+    tf_zero, clk_zero = pcm.pcm_measure_mfma_rate(False, 100)
+    mfma_only = {"random_operands": {"tflops": tf_rand, "clock_ghz": clk_rand},
+                 "zero_operands": {"tflops": tf_zero, "clock_ghz": clk_zero}}
     flops = gemm_flops_per_launch(rows, cfg.d, cfg.ff, cfg.V)
     per_stage = {}
     for name, (ms, launches) in stages.items():
@@ -323,6 +328,8 @@ def main():
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                 "traffic": stored_traffic("gemm_gate_up_cfg2_traffic.txt") if cfg.name == "cfg2" else None,
                 "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
+                "mfma_only_sustained": mfma_only,
+                "frac_of_mfma_only_random": achieved / tf_rand,
                 "all_head_gemms": {"tflops": total_flops_step / (gemm_ms_step * 1e-3) / 1e12,
                                    "frac": total_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                                    "ms_per_step": gemm_ms_step}}

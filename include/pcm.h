@@ -17,8 +17,8 @@
  *   - Return value: PCM_OK or a negative pcm_status.  Nothing throws, aborts or prints.
  *   - "device" pointers are HIP device memory owned by the caller; they must stay valid until
  *     `stream` has executed the call.  "host" values are plain arguments.  The library never
- *     allocates or frees device memory and never synchronises the stream or the device: all
- *     work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     allocates or frees device memory and never synchronises the stream or the device (the
+ *     measurement aid pcm_measure_mfma_rate excepted): all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - Scratch memory comes from the caller: `workspace` (device, 256-byte aligned) of at least
  *     the size returned by the matching *_workspace_bytes query (host-only, no GPU work).  Its
  *     contents on entry are irrelevant; two calls that share a workspace must be ordered on
@@ -322,6 +322,17 @@ PCM_API int pcm_profile_stage_count(void);
 PCM_API const char* pcm_profile_stage_name(int stage);  /* NULL if out of range */
 /* host arrays of pcm_profile_stage_count() entries: total milliseconds and launch counts */
 PCM_API int pcm_profile_collect(double* total_ms, int64_t* launches);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement aid (host side; the one entry point that allocates: two small device buffers for its
+ * own use, freed before it returns; it synchronises the device).  Runs bf16 matrix instructions
+ * (v_mfma_f32_32x32x16_bf16, fp32 accumulation) from registers on every CU of device 0 for about
+ * `milliseconds`, with all-zero operands (random_operands = 0) or roughly normal random operands,
+ * and reports the sustained rate in TFLOP/s and the mean shader clock in GHz (clock_ghz may be
+ * NULL).  The chip is power-limited under matrix load and the rate depends on the data, so this
+ * is the ceiling a bf16 GEMM on such data can approach; the nominal peak assumes the top clock.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API int pcm_measure_mfma_rate(int random_operands, int milliseconds, double* tflops, double* clock_ghz);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     pcm_adamw_clip_step,
     pcm_importance_weights,
     pcm_label_phases,
+    pcm_measure_mfma_rate,
     pcm_profile_collect,
     pcm_profile_enable,
     pcm_sample_chunks,

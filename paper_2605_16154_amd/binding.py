@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
     _sig(L.pcm_adamw_clip_step, i32,
          [i32, C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i64,
           f64, f64, f64, f64, f64, f64, vp, vp, sz, vp])
+    _sig(L.pcm_measure_mfma_rate, i32, [i32, i32, C.POINTER(f64), C.POINTER(f64)])
     _sig(L.pcm_profile_enable, i32, [i32])
     _sig(L.pcm_profile_stage_count, i32, [])
     _sig(L.pcm_profile_stage_name, C.c_char_p, [i32])
@@ -333,6 +334,14 @@ def pcm_adamw_clip_step(grads, weights, m, v, step: int, lr: float = 1e-5, beta1
                                    ws, ws_bytes, _stream())
     _check(rc, "pcm_adamw_clip_step")
     return grad_norm_out
+
+
+def pcm_measure_mfma_rate(random_operands: bool = True, milliseconds: int = 100) -> Tuple[float, float]:
+    """-> (TFLOP/s, shader clock in GHz) that the bf16 matrix cores sustain on their own, on zeros or random data."""
+    tf, clk = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().pcm_measure_mfma_rate(int(random_operands), milliseconds, C.byref(tf), C.byref(clk)),
+           "pcm_measure_mfma_rate")
+    return tf.value, clk.value
 
 
 def pcm_profile_enable(on: bool) -> None:

@@ -13,7 +13,7 @@ LIB = os.path.join(PKG, "libpcm.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
 SOURCES = ["runtime.hip", "score.hip", "keep_probs.hip", "sample.hip", "gather.hip",
-           "actor_f32.hip", "actor_bf16.hip", "actor_api.hip", "optimizer.hip", "labeler.hip"]
+           "actor_f32.hip", "actor_bf16.hip", "actor_api.hip", "optimizer.hip", "labeler.hip", "ceiling.hip"]
 # the fp64 tails of the selection stage are specified without fused multiply-add
 NO_CONTRACT = {"score.hip", "keep_probs.hip"}
 
