@@ -236,13 +236,13 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         const bool seg1 = step < steps1;
         return seg_origin[operand][seg1 ? 0 : 1] + (int64_t)(seg1 ? step : step - steps1) * k_step_bytes[operand];
     };
-    auto load_ctx_at = [&](int operand, uint32_t slot, const char* origin) {
+    auto load_ctx_at = [&](int operand, uint32_t slot /* byte offset of the ring slot */, const char* origin) {
         LoadCtx c;
         c.base = origin;
         c.off[0] = lane_off[operand][0];
         c.off[1] = lane_off[operand][1];
         c.stride = load_stride[operand];
-        c.dst = lds_base + slot * kTileBytes + (uint32_t)wave * 8192u;
+        c.dst = lds_base + slot + (uint32_t)wave * 8192u;
         return c;
     };
     auto load_ctx = [&](int operand, uint32_t slot, int step) { return load_ctx_at(operand, slot, tile_origin(operand, step)); };
@@ -276,12 +276,12 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         return (uint32_t)(k * 512 + (swizzle_unit(col0 >> 4, j >> 2) << 5) + ((j & 3) << 3));
     };
     auto read_frag_a = [&](int set, uint32_t slot_a, int ks, int i) {
-        const char* sa = reinterpret_cast<const char*>(smem) + slot_a * kTileBytes + frag_offset(kLayA, wm * 128, ks, i);
+        const char* sa = reinterpret_cast<const char*>(smem) + slot_a + frag_offset(kLayA, wm * 128, ks, i);
         if (kLayA == kRowsByK) fa[set][i] = *reinterpret_cast<const bf16x8*>(sa);
         else fa[set][i] = read_transposed_fragment(sa);
     };
     auto read_frag_b = [&](int set, uint32_t slot_b, int ks, int j) {
-        const char* sb = reinterpret_cast<const char*>(smem) + slot_b * kTileBytes + frag_offset(kLayB, wn * 128, ks, j);
+        const char* sb = reinterpret_cast<const char*>(smem) + slot_b + frag_offset(kLayB, wn * 128, ks, j);
         if (kLayB == kRowsByK) fb[set][j] = *reinterpret_cast<const bf16x8*>(sb);
         else fb[set][j] = read_transposed_fragment(sb);
     };
@@ -293,21 +293,22 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
 #pragma unroll
         for (int i = 0; i < 4; ++i) read_frag_pair(set, slot_a, slot_b, ks, i);
     };
-    auto next_slot = [](uint32_t s) { return s + 1u >= (uint32_t)kRingSlots ? s + 1u - kRingSlots : s + 1u; };
+    // ring slots are named by their byte offset in LDS
+    auto next_slot = [](uint32_t s) { return s + kTileBytes >= (uint32_t)kSmemBytes ? s + kTileBytes - kSmemBytes : s + kTileBytes; };
 
     if (step_begin < step_end) {
         // Operand tiles are numbered 2 s + o (o = 0 for A, 1 for B of step s) and tile t lives in ring
         // slot t mod 5.  Prologue: tiles 0..4 (steps 0, 1 and the A tile of step 2) are requested;
         // steps past the end re-request the last step's tiles, which nobody reads.
         const int last = step_end - 1;
-        issue_loads(load_ctx(0, 0, step_begin), 0, 8);
-        issue_loads(load_ctx(1, 1, step_begin), 0, 8);
-        issue_loads(load_ctx(0, 2, min(step_begin + 1, last)), 0, 8);
-        issue_loads(load_ctx(1, 3, min(step_begin + 1, last)), 0, 8);
-        issue_loads(load_ctx(0, 4, min(step_begin + 2, last)), 0, 8);
+        issue_loads(load_ctx(0, 0 * kTileBytes, step_begin), 0, 8);
+        issue_loads(load_ctx(1, 1 * kTileBytes, step_begin), 0, 8);
+        issue_loads(load_ctx(0, 2 * kTileBytes, min(step_begin + 1, last)), 0, 8);
+        issue_loads(load_ctx(1, 3 * kTileBytes, min(step_begin + 1, last)), 0, 8);
+        issue_loads(load_ctx(0, 4 * kTileBytes, min(step_begin + 2, last)), 0, 8);
         wait_direct_loads<3 * kLoadsPerTile>();
         __syncthreads();
-        read_frags(0, 0, 1, 0);
+        read_frags(0, 0 * kTileBytes, 1 * kTileBytes, 0);
         // One 64-wide step per trip.  `sa`, `sb` are the slots of this step's tiles; the next step's
         // are the two after them in the ring.  Fragment set 0 holds slice 0 of this step on entry and
         // slice 0 of the next step on exit.  The single barrier sits before the last slice: by then
@@ -358,7 +359,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
             }
         };
         uint32_t sa = 0;
-        LoadCtx pend_b = load_ctx(0, 4, min(step_begin + 2, last));   // nothing pending yet: harmless re-request
+        LoadCtx pend_b = load_ctx(0, 4 * kTileBytes, min(step_begin + 2, last));   // nothing pending yet: harmless re-request
         LoadCtx pend_a = pend_b;
         // tile streams: origin of the newest tile requested so far of each operand, and its step
         int at_a = min(step_begin + 2, last), at_b = min(step_begin + 1, last);
@@ -378,11 +379,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
                 origin_b = at_b == steps1 ? seg_origin[1][1] : origin_b;
             }
         };
+        // slots of this step's tiles and of the next step's; those of the step after are worked out in
+        // otherwise empty gaps of the second slice
+        uint32_t sb = next_slot(sa), na = next_slot(sb), nb = next_slot(na), after_a = 0, after_b = 0;
+        auto rotate = [&](int half) {
+            if (half == 0) after_a = next_slot(nb);
+            else after_b = next_slot(after_a);
+        };
         for (int step = step_begin; step < step_end; ++step) {
-            const uint32_t sb = next_slot(sa);
-            const uint32_t na = next_slot(sb), nb = next_slot(na);
             slice(0, pend_b, 1, sa, sb, 1, no_hook);
-            slice(1, pend_a, 0, sa, sb, 2, no_hook);
+            slice(1, pend_a, 0, sa, sb, 2, rotate);
             slice(0, pend_a, 1, sa, sb, 3, advance);
             wait_direct_loads<kLoadsPerTile>();
             __syncthreads();
@@ -390,6 +396,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
             pend_a = load_ctx_at(0, sb, origin_a);   // tile 2 s + 6 -> slot of tile 2 s + 1
             slice(1, pend_b, 0, na, nb, 0, no_hook);
             sa = na;
+            sb = nb;
+            na = after_a;
+            nb = after_b;
         }
         wait_direct_loads<0>();
         __syncthreads();
