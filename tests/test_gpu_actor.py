@@ -306,11 +306,12 @@ def test_bf16_full_size_head_sampled_rows_and_one_group(pcm):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name", ["cfg4", "cfg5"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
 def test_bf16_large_configs_chained_selection_and_sampled_rows(pcm, name):
-    """Larger-batch and skewed long-horizon instances at full size: the four calls chained on the GPU,
-    selection compared bit for bit, per-row outputs (logp, dX) of sampled kept chunks against the checker.
-    In the skewed instance a quarter of the groups have uniform rewards and are dropped at compaction."""
+    """Unmasked (B = N), larger-batch and skewed long-horizon instances at full size: the four calls chained
+    on the GPU, selection compared bit for bit, per-row outputs (logp, dX) of sampled kept chunks against the
+    checker.  With B = N the kept list is every chunk in order (the all-kept mask is unmasked GRPO, Eq. 2); in
+    the skewed instance a quarter of the groups have uniform rewards and are dropped at compaction."""
     cfg = CONFIGS[name]
     dv = torch.device("cuda")
     ro = make_rollouts(cfg, 0)
@@ -320,6 +321,8 @@ def test_bf16_large_configs_chained_selection_and_sampled_rows(pcm, name):
     kept_o, off_o, nk_o = O.sample_chunks(p_o, ro["phase"], None, act_o, cfg.B, cfg.seed, 0)
     if name == "cfg5":
         assert nk_o == (cfg.n_groups - cfg.n_groups // 4) * cfg.G * cfg.B     # collapsed groups keep nothing
+    if name == "cfg3":
+        assert np.array_equal(kept_o, np.arange(cfg.T * cfg.N))               # nothing is masked
 
     phase = dev(ro["phase"])
     C, valid, adv, act = pcm.pcm_score_phases(dev(ro["actions"]), phase, dev(ro["reward"]), None, cfg.n_groups,
