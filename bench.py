@@ -4,7 +4,9 @@
 One step = one pass of the whole path over one synthetic rollout batch that is already resident
 in HBM: pcm_score_phases -> pcm_update_keep_probs -> pcm_sample_chunks -> grpo_masked_actor_step
 (gather, head forward, fused clipped-GRPO loss, full backward), all through the C-ABI library.
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric, value, ms_per_step (mean, median, min), roofline of the dominant GEMM, per-stage
+times, the unmasked step for the masking speed-up, timings of the loss variants and the optimizer step, and the
+CPU checker timed on the host cores.
 """
 from __future__ import annotations
 
@@ -273,7 +275,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures the single-GPU hot path only; run it with --gpus 1 "
-              "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(sharding over GPUs is a design note, not built)", file=sys.stderr)
         sys.exit(2)
 
     import torch
