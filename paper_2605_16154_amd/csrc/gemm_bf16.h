@@ -101,12 +101,21 @@ __device__ inline int unswizzle_unit(int phys, int k_low2) {
     return ((t & 1) << 2) | (t & 2) | ((t >> 2) & 1) | (t & 8);
 }
 
-// Workgroup id -> (tile_m, tile_n).  Consecutive hardware workgroup ids go to different XCDs, each
-// with its own L2, so ids are first regrouped so that one XCD works on a contiguous range of
-// tiles, then tiles are walked in column-major bands of 8 row-tiles to reuse operand panels.
-__device__ inline void tile_of_workgroup(int wg, int n_wg, int tiles_m, int tiles_n, int& tm, int& tn) {
+// Workgroup id -> (tile_m, tile_n), or false if the workgroup has no tile.  Consecutive hardware
+// workgroup ids go to different XCDs, each with its own L2, so ids are first regrouped so that one
+// XCD works on a contiguous range of tiles, then tiles are walked in column-major bands of 8
+// row-tiles to reuse operand panels.  Of the n_wg workgroups launched only tiles_m * tiles_n have a
+// tile (the row dimension may be cut short by a device-side count): the live tiles are dealt out
+// evenly over the XCDs, so that a short batch does not leave some XCDs without work.
+__device__ inline bool tile_of_workgroup(int wg, int n_wg, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int n_live = tiles_m * tiles_n;
+    const int per_xcd = (n_live + kNumXcd - 1) / kNumXcd;
     int logical = wg;
-    if (n_wg % kNumXcd == 0) logical = (wg % kNumXcd) * (n_wg / kNumXcd) + wg / kNumXcd;
+    if (kNumXcd * per_xcd <= n_wg) {
+        if (wg / kNumXcd >= per_xcd) return false;
+        logical = (wg % kNumXcd) * per_xcd + wg / kNumXcd;
+    }
+    if (logical >= n_live) return false;
     constexpr int kBand = 8;
     const int band_size = kBand * tiles_n;
     const int band = logical / band_size;
@@ -115,6 +124,7 @@ __device__ inline void tile_of_workgroup(int wg, int n_wg, int tiles_m, int tile
     const int in_band = logical % band_size;
     tm = first + in_band % rows;
     tn = in_band / rows;
+    return true;
 }
 
 #define PCM_AS_LDS(p) ((__attribute__((address_space(3))) void*)(p))
@@ -162,18 +172,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
     const int tiles_m = p.M / kTileM, tiles_n = p.N / kTileN;
     const int n_tiles = tiles_m * tiles_n;
     const int split = blockIdx.x / n_tiles;
-    int tm, tn;
-    tile_of_workgroup(blockIdx.x % n_tiles, n_tiles, tiles_m, tiles_n, tm, tn);
-    const int m0 = tm * kTileM, n0 = tn * kTileN;
-
-    int k1 = p.K1;
+    int k1 = p.K1, live_m = tiles_m;
     if (p.kept != nullptr) {
         int nk = *p.kept;
         nk = nk < 0 ? 0 : (nk > p.kept_max ? p.kept_max : nk);
         const int rows = nk * p.rows_per_kept;
-        if (p.rows_role == kRowsAreM && m0 >= rows) return;      // the whole workgroup leaves, before any barrier
+        if (p.rows_role == kRowsAreM) live_m = min(tiles_m, (rows + kTileM - 1) / kTileM);
         if (p.rows_role == kRowsAreK) k1 = min(k1, (rows + kTileK - 1) / kTileK * kTileK);
     }
+    int tm, tn;
+    if (!tile_of_workgroup(blockIdx.x % n_tiles, n_tiles, live_m, tiles_n, tm, tn)) return;   // before any barrier
+    const int m0 = tm * kTileM, n0 = tn * kTileN;
     // reduction range of this workgroup, in 64-wide steps over the concatenation of both segments
     const int steps1 = k1 / kTileK, steps_all = steps1 + p.K2 / kTileK;
     const int per_split = (steps_all + p.splits - 1) / p.splits;
