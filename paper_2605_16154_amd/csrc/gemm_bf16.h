@@ -17,10 +17,9 @@
 //
 // The MFMA is issued with the B fragment as the first operand, so the accumulator tile is the
 // transpose of the usual one: a lane holds, for one output row m, runs of 4 consecutive n.
-// Epilogues therefore see 4-wide row-contiguous vectors (8-byte bf16 stores).
+// Epilogues therefore see 4-wide row-contiguous vectors (8-byte writes into the staging area,
+// from which whole rows leave as 16-byte-per-lane stores).
 #pragma once
-
-#include <type_traits>
 
 #include "actor.h"
 
