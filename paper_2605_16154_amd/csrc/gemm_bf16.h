@@ -244,7 +244,8 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         const bool seg1 = step < steps1;
         return seg_origin[operand][seg1 ? 0 : 1] + (int64_t)(seg1 ? step : step - steps1) * k_step_bytes[operand];
     };
-    auto load_ctx_at = [&](int operand, uint32_t slot /* byte offset of the ring slot */, const char* origin) {
+    // `slot` is the byte offset of a ring slot
+    auto load_ctx_at = [&](int operand, uint32_t slot, const char* origin) {
         LoadCtx c;
         c.base = origin;
         c.off[0] = lane_off[operand][0];

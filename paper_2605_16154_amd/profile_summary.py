@@ -72,12 +72,16 @@ KERNEL_SOURCES = ("gemm_bf16.h", "actor_bf16.hip")
 
 
 def kernel_source_hash() -> str:
-    """Hash of the sources of the bf16 GEMM; byte counters are only valid for the code they were taken on."""
+    """Hash of the code of the bf16 GEMM (comments and white space left out); byte counters are only valid for
+    the code they were taken on."""
     import hashlib
+    import re
     h = hashlib.sha256()
     here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc")
     for name in KERNEL_SOURCES:
-        h.update(open(os.path.join(here, name), "rb").read())
+        text = open(os.path.join(here, name), encoding="utf-8").read()
+        text = re.sub(r"//[^\n]*", "", text)            # line comments (the sources use no block comments or // in strings)
+        h.update("".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 
