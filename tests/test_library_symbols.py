@@ -77,6 +77,24 @@ def test_optimizer_entry_validates_on_the_host(cdll):
                 d(2.0), None, None, ctypes.c_size_t(0), None) == -1
 
 
+def test_header_is_valid_c_and_a_plain_c_client_links(cdll, tmp_path):
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = tmp_path / "abi_check"
+    lib_dir = os.path.dirname(LIB)
+    cmd = [cc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c", "abi_check.c"), "-o", str(exe), "-L", lib_dir, "-l:libpcm.so",
+           "-Wl,-rpath," + lib_dir]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert "pcm" in r.stdout
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     import paper_2605_16154_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)
