@@ -39,36 +39,54 @@ __global__ void state_init(void* state, int K) {
     }
 }
 
-__global__ void update_keep_probs(void* state, const double* __restrict__ C,
-                                  const uint8_t* __restrict__ valid, int K, double p_min, int T_rc,
-                                  double* keep_probs_out) {
-    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+// One wavefront, lane c owns phase c (K <= 64).  Everything is per phase except the maximum of the
+// sums, and a maximum does not depend on the order it is taken in, so the results are those of the
+// one-lane walk in index order.
+__global__ __launch_bounds__(kWave) void update_keep_probs(void* state, const double* __restrict__ C,
+                                                            const uint8_t* __restrict__ valid, int K, double p_min,
+                                                            int T_rc, double* keep_probs_out) {
+    if (blockIdx.x != 0) return;
     StateView v(state, K);
-    for (int c = 0; c < K; ++c) {
+    const int c = threadIdx.x;
+    const bool mine = c < K;
+    double S = 0.0, p = 0.0;
+    long long count = 0;
+    if (mine) {
+        S = v.S[c];
+        count = v.count[c];
+        p = v.p[c];
         if (valid[c]) {
-            v.S[c] = v.S[c] + C[c];            // Eq. 7: append (as a running sum)
-            v.count[c] += 1;
+            S = S + C[c];                      // Eq. 7: append (as a running sum)
+            count += 1;
         }
     }
     long long since = *v.since + 1;
     const long long step = *v.step;
     if (step == 0 || since == (long long)T_rc) {
-        double s_max = 0.0;
-        for (int c = 0; c < K; ++c)
-            if (v.S[c] > s_max) s_max = v.S[c];
-        for (int c = 0; c < K; ++c) {
-            // Eq. 8: rho_c / max rho = S_c / max S (the share denominator cancels)
-            const double rho_tilde = s_max > 0.0 ? v.S[c] / s_max : 0.0;
-            v.p[c] = rho_tilde > p_min ? rho_tilde : p_min;   // Eq. 9
-            v.S[c] = 0.0;
-            v.count[c] = 0;
+        double s_max = (mine && S > 0.0) ? S : 0.0;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+            const double other = __shfl_xor(s_max, off, kWave);
+            s_max = other > s_max ? other : s_max;
         }
+        // Eq. 8: rho_c / max rho = S_c / max S (the share denominator cancels)
+        const double rho_tilde = s_max > 0.0 ? S / s_max : 0.0;
+        p = rho_tilde > p_min ? rho_tilde : p_min;   // Eq. 9
+        S = 0.0;
+        count = 0;
         since = 0;
     }
-    *v.since = since;
-    *v.step = step + 1;
-    if (keep_probs_out)
-        for (int c = 0; c < K; ++c) keep_probs_out[c] = v.p[c];
+    __builtin_amdgcn_wave_barrier();           // every lane has read step and since before lane 0 rewrites them
+    if (mine) {
+        v.S[c] = S;
+        v.count[c] = count;
+        v.p[c] = p;
+        if (keep_probs_out) keep_probs_out[c] = p;
+    }
+    if (c == 0) {
+        *v.since = since;
+        *v.step = step + 1;
+    }
 }
 
 }  // namespace

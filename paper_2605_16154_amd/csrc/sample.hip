@@ -158,8 +158,15 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
 
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t s0 = (uint32_t)step, s1 = (uint32_t)(step >> 32);
+    uint32_t x_lo = 0, x_hi = 0;              // lane l holds the random bits of round (r & ~63) + l
     for (int r = 0; r < m; ++r) {
-        const uint64_t x = philox_bits((uint32_t)i, (uint32_t)r, s0, s1, k0, k1);
+        if ((r & (kWave - 1)) == 0) {         // the draws of the next 64 rounds, one per lane, in parallel
+            const uint64_t mine = philox_bits((uint32_t)i, (uint32_t)(r + lane), s0, s1, k0, k1);
+            x_lo = (uint32_t)mine;
+            x_hi = (uint32_t)(mine >> 32);
+        }
+        const uint64_t x = (uint64_t)(uint32_t)__shfl((int)x_lo, r & (kWave - 1), kWave) |
+                           ((uint64_t)(uint32_t)__shfl((int)x_hi, r & (kWave - 1), kWave) << 32);
         const uint32_t t = (uint32_t)__umul64hi(x, (uint64_t)W_rem);   // in [0, W_rem)
         const uint64_t over = __ballot(incl > t);
         if (over == 0) break;                 // cannot happen while W_rem > 0; keeps the loop total

@@ -209,20 +209,38 @@ __global__ __launch_bounds__(kThreads) void score_pairs(const ull* __restrict__ 
     }
 }
 
-__global__ void score_mean(const double* __restrict__ pair, const uint8_t* __restrict__ pair_valid,
-                           int n_groups, int K, double* C_out, uint8_t* valid_out) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= K) return;
+// Batch score of phase c = mean over the groups that contributed, added for g ascending (the order is
+// part of the definition: the result must not depend on the launch).  One workgroup: the per-group values
+// are brought into LDS 32 groups at a time with coalesced loads, then lane c adds its column in order.
+constexpr int kMeanGroups = 32;
+__global__ __launch_bounds__(256) void score_mean(const double* __restrict__ pair, const uint8_t* __restrict__ pair_valid,
+                                                  int n_groups, int K, double* C_out, uint8_t* valid_out) {
+    __shared__ double val[kMeanGroups * PCM_MAX_PHASES];
+    __shared__ uint8_t ok[kMeanGroups * PCM_MAX_PHASES];
+    const int c = threadIdx.x;
     double tot = 0.0;
     int n = 0;
-    for (int g = 0; g < n_groups; ++g) {
-        if (pair_valid[(size_t)g * K + c]) {
-            tot = tot + pair[(size_t)g * K + c];
-            ++n;
+    for (int g0 = 0; g0 < n_groups; g0 += kMeanGroups) {
+        const int groups = min(kMeanGroups, n_groups - g0);
+        for (int i = threadIdx.x; i < groups * K; i += blockDim.x) {
+            val[i] = pair[(size_t)g0 * K + i];
+            ok[i] = pair_valid[(size_t)g0 * K + i];
         }
+        __syncthreads();
+        if (c < K) {
+            for (int g = 0; g < groups; ++g) {
+                if (ok[g * K + c]) {
+                    tot = tot + val[g * K + c];
+                    ++n;
+                }
+            }
+        }
+        __syncthreads();
     }
-    C_out[c] = n > 0 ? tot / (double)n : 0.0;
-    valid_out[c] = n > 0 ? 1 : 0;
+    if (c < K) {
+        C_out[c] = n > 0 ? tot / (double)n : 0.0;
+        valid_out[c] = n > 0 ? 1 : 0;
+    }
 }
 
 bool shape_ok(int n_groups, int G, int N, int A, int K) {
@@ -284,7 +302,7 @@ extern "C" int pcm_score_phases(const float* actions, const uint8_t* phase, cons
         const int waves = n_groups * K;
         score_pairs<<<ceil_div(waves, kThreads / kWave), kThreads, 0, s>>>(w.sums, w.counts, n_groups, A,
                                                                          K, w.pair, w.pair_valid);
-        score_mean<<<1, kWave, 0, s>>>(w.pair, w.pair_valid, n_groups, K, C_out, valid_out);
+        score_mean<<<1, 256, 0, s>>>(w.pair, w.pair_valid, n_groups, K, C_out, valid_out);
     }
     return launch_status();
 }
