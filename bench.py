@@ -227,6 +227,37 @@ def selection_only(cfg, dev, steps, warmup):
                                       "GB_per_s": 2 * actions.numel() * 4 / copy_us / 1e3}}
 
 
+def graph_replay_timing(wl, steps):
+    """The same steps replayed from HIP graphs (one graph per resident batch, captured once): what is left when the
+    launch gaps between the ~30 kernels of a step are gone.  Reported beside `value`, which stays the eager figure."""
+    torch, pcm, cfg = wl.torch, wl.pcm, wl.cfg
+    n = len(wl.batches)
+    wl.state = pcm.pcm_state_init(cfg.K, wl.dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graphs = []
+    with torch.cuda.stream(side):
+        for t in range(n):
+            wl.step(t)                              # sizes buffers and workspace on the capture stream
+        torch.cuda.synchronize()
+        for t in range(n):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                wl.step(t)
+            graphs.append(g)
+    torch.cuda.current_stream().wait_stream(side)
+    for t in range(3):
+        graphs[t % n].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        graphs[t % n].replay()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return {"ms_per_step": dt / steps * 1e3, "graphs": n,
+            "note": "each graph replays its batch with the step index it was captured with"}
+
+
 def optimizer_step_timing(wl, iters=10):
     """The optimizer step that would follow the actor gradients (App. D: clipping at 2.0 + AdamW), timed on
     the head's real tensors: not part of `value`, reported beside it.  HBM-bound: per parameter the norm pass
@@ -363,6 +394,7 @@ def main():
         dt_c, _, _ = timed_steps(wl, k_v, 1, entropy_coef=1e-3, token_mean=True, chunk_ratio=True)
         result["loss_variants"] = {"entropy_bonus_token_mean_ms_per_step": dt_v / k_v * 1e3,
                                    "with_per_chunk_ratio_ms_per_step": dt_c / k_v * 1e3}
+        result["hip_graph_replay"] = graph_replay_timing(wl, args.steps)
         wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
         result["optimizer_step"] = optimizer_step_timing(wl)
     if not args.no_cpu_baseline:
