@@ -82,3 +82,14 @@ def test_captured_step_replays_bit_for_bit(pcm):
         state.copy_(state0)
         step(3)
         same(ref, snapshot())
+
+
+def test_mfma_rate_measurement_aid(pcm):
+    """The matrix cores' own sustained rate: positive, below the nominal peak, and lower on random operands than on
+    zeros (the chip is power-limited under matrix load)."""
+    tf_zero, clk_zero = pcm.pcm_measure_mfma_rate(False, 30)
+    tf_rand, clk_rand = pcm.pcm_measure_mfma_rate(True, 30)
+    assert 500.0 < tf_rand <= tf_zero * 1.02 and tf_zero < 2600.0
+    assert 0.5 < clk_rand <= clk_zero * 1.02 and clk_zero < 2.6
+    with pytest.raises(pcm.PcmError):
+        pcm.pcm_measure_mfma_rate(True, 0)
