@@ -183,6 +183,24 @@ def test_bf16_small_head_matches_checker(pcm):
     check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2)
 
 
+@pytest.mark.parametrize("d,ff,n_kept,A_dims", [
+    (256, 256, 3, (8, 7)),        # a single row tile, mostly padding; one tile in every weight dimension
+    (768, 1280, 23, (8, 7)),      # 3 x 5 weight tiles, 1288 rows = 5 row tiles + ragged tail
+    (512, 256, 64, (2, 2)),       # short chunks: 256 rows, exactly one full row tile
+    (256, 1024, 40, (4, 4)),      # 640 rows: the row count is a multiple of 64 but not of 256
+])
+def test_bf16_shape_sweep(pcm, d, ff, n_kept, A_dims):
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=4, N=16, K=4, B=8, d=d, ff=ff, L=A_dims[0], D=A_dims[1], seed=40 + n_kept)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, cfg.seed, 0)
+    assert len(kept) >= n_kept
+    # weight scale chosen so that logits stay O(1): the bf16 error of a log-probability grows with the logit scale
+    pr = make_problem(cfg, wstd=0.04, margin=0.08, kept=kept[:n_kept], old_rel=0.2, eps=(0.2, 0.4))
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), torch_dtype=torch.bfloat16, max_kept=n_kept + 2)
+    check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2)
+
+
 def test_bf16_all_kept_and_forward_only(pcm):
     cfg = CONFIGS["cfg2"].with_(n_groups=1, G=4, N=6, K=3, B=6, d=256, ff=256, seed=13)
     pr = make_problem(cfg, wstd=0.08, margin=0.08, kept=np.arange(cfg.T * cfg.N), old_rel=0.1)
