@@ -332,6 +332,37 @@ def sample_trajectory(weights, m, seed, step, traj):
     return picks
 
 
+def stratified_allocation(q, n_c, m):
+    """Per-phase budgets b_c of the stratified estimator (App. C, Theorem 1: b_c* = B N_c sqrt(V_c) / sum N_c' sqrt(V_c'),
+    with the keep probability, as integer weight q_c, standing for sqrt(V_c)).
+
+    m chunks are shared out over the phases in proportion to N_c q_c by the largest-remainder rule, never more than
+    N_c to a phase: b_c = floor(m N_c q_c / D), D = sum N_c' q_c'; the chunks left over go one at a time to the
+    phase with the largest remainder (m N_c q_c) mod D that still has room (lowest index on ties), and, if the caps
+    leave some undistributed after every remainder has been served once, on in the same order.  All integers.
+    The rounding rule is not in the paper (the theorem treats b_c as real numbers).
+    """
+    K = len(q)
+    weight = [int(n_c[c]) * int(q[c]) for c in range(K)]
+    D = sum(weight)
+    assert 0 <= m <= sum(int(x) for x in n_c)
+    if D == 0:
+        return [0] * K
+    b = [min(int(n_c[c]), (m * weight[c]) // D) for c in range(K)]
+    rem = [(m * weight[c]) % D for c in range(K)]
+    order = sorted(range(K), key=lambda c: (-rem[c], c))
+    left = m - sum(b)
+    while left > 0:
+        progressed = False
+        for c in order:
+            if left > 0 and b[c] < int(n_c[c]):
+                b[c] += 1
+                left -= 1
+                progressed = True
+        assert progressed
+    return b
+
+
 def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step, selector="pcm"):
     """Kept set per trajectory and its compaction (Eq. 10; Algorithm 1 inner loop; Sec. 4.5).
 
@@ -341,6 +372,10 @@ def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step, selector="
       "top_phase"  only chunks of the single phase with the largest keep probability (lowest
                    index on ties) are eligible, with equal weights; a trajectory keeps
                    min(B, number of its chunks in that phase) of them (none if it has none).
+      "stratified" the sampling scheme that the variance analysis of App. C assumes: a fixed budget b_c per
+                   phase (stratified_allocation, from the keep probabilities and the trajectory's phase sizes),
+                   then b_c chunks of phase c uniformly without replacement, phases in index order, the draw
+                   counter running on across phases.
 
     Every chunk inherits its phase's keep probability as weight (Sec. 4.4); each
     active trajectory keeps min(B, N_i) chunks; trajectories of collapsed groups
@@ -353,7 +388,7 @@ def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step, selector="
     phase = np.asarray(phase)
     T, N = phase.shape
     K = len(keep_probs)
-    if selector == "pcm":
+    if selector in ("pcm", "stratified"):
         q = quantise_keep_probs(keep_probs)
     elif selector == "random":
         q = np.ones(K, dtype=np.int64)
@@ -374,9 +409,23 @@ def sample_chunks(keep_probs, phase, n_chunks, active, B, seed, step, selector="
         if (active is not None and not active[i]) or Ni == 0:
             offsets[i + 1] = offsets[i]
             continue
-        w = [int(q[min(int(phase[i, k]), K - 1)]) for k in range(Ni)]
+        ph = [min(int(phase[i, k]), K - 1) for k in range(Ni)]
+        w = [int(q[c]) for c in ph]
         m = min(B, sum(1 for x in w if x > 0))
-        picks = sorted(sample_trajectory(w, m, seed, step, i))
+        if selector == "stratified":
+            n_c = [sum(1 for c in ph if c == cc) for cc in range(K)]
+            budget = stratified_allocation(q, n_c, m)
+            picks, r = [], 0
+            for cc in range(K):
+                members = [k for k in range(Ni) if ph[k] == cc]
+                for _ in range(budget[cc]):
+                    x = rng64(seed, step, i, r)
+                    t = (x * len(members)) >> 64          # uniform over the phase's remaining chunks, ascending
+                    picks.append(members.pop(t))
+                    r += 1
+            picks.sort()
+        else:
+            picks = sorted(sample_trajectory(w, m, seed, step, i))
         kept.extend(i * N + k for k in picks)
         offsets[i + 1] = offsets[i] + m
     return np.asarray(kept, dtype=np.int32), offsets, int(offsets[T])

@@ -393,3 +393,60 @@ def test_importance_weights_hand_example_and_phase_totals():
             if sel.any():
                 n_c = int((ro["phase"][i, :nch[i]] == c).sum())
                 assert abs(wi[sel].sum() - n_c) < 1e-4 * n_c
+
+
+# --------------------------------------------------------------------------- stratified sampling (App. C, Theorem 1)
+
+def test_stratified_allocation_hand_examples_and_invariants():
+    # m = 12 over weights N_c q_c = (10*4, 20*1, 30*1) = (40, 20, 30): shares 5.33, 2.67, 4.0 -> floors 5, 2, 4, one
+    # chunk left for the largest remainder (phase 1: 60 mod 90... remainders 30, 60, 0)
+    assert O.stratified_allocation([4, 1, 1], [10, 20, 30], 12) == [5, 3, 4]
+    # caps: phase 0 would get 9 of 12 but has only 3 chunks; the rest flows on by remainder order, then around again
+    assert O.stratified_allocation([9, 1, 1], [3, 5, 5], 12) == [3, 5, 4]
+    assert O.stratified_allocation([1, 1, 1], [4, 4, 4], 12) == [4, 4, 4]
+    assert O.stratified_allocation([5, 5], [0, 7], 3) == [0, 3]
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        K = int(rng.integers(1, 8))
+        q = rng.integers(1, 65537, size=K)
+        n = rng.integers(0, 40, size=K)
+        m = int(rng.integers(0, n.sum() + 1))
+        b = O.stratified_allocation(q, n, m)
+        assert sum(b) == m and all(0 <= b[c] <= n[c] for c in range(K))
+        # within one chunk of the real-valued optimum of Theorem 1 wherever the cap does not bind
+        D = float((n * q).sum())
+        if D > 0 and all(m * n[c] * q[c] / D <= n[c] for c in range(K)):
+            assert all(abs(b[c] - m * n[c] * q[c] / D) < 1.0 for c in range(K))
+
+
+def test_stratified_selector_budgets_uniformity_and_unbiased_weights():
+    T, N, K, B = 2, 12, 3, 6
+    phase = np.array([[0] * 2 + [1] * 6 + [2] * 4, [2] * 5 + [0] * 7], dtype=np.uint8)
+    p = np.array([1.0, 0.25, 0.5])
+    q = O.quantise_keep_probs(p)
+    budgets = [O.stratified_allocation(q, [int((phase[i] == c).sum()) for c in range(K)], B) for i in range(T)]
+    f = np.random.default_rng(4).standard_normal((T, N))          # any per-chunk quantity
+    counts = np.zeros((T, N))
+    est = np.zeros(T)
+    steps = 3000
+    for s in range(steps):
+        kept, off, nk = O.sample_chunks(p, phase, None, None, B, 21, s, selector="stratified")
+        w = O.importance_weights(phase, None, kept, K).astype(np.float64)
+        for i in range(T):
+            mine = kept[off[i]:off[i + 1]] % N
+            assert [int((phase[i, mine] == c).sum()) for c in range(K)] == budgets[i]   # the budget is deterministic
+            counts[i, mine] += 1
+            est[i] += (w[off[i]:off[i + 1]] * f[i, mine]).sum()
+    for i in range(T):
+        for c in range(K):
+            members = np.where(phase[i] == c)[0]
+            if len(members) == 0:
+                continue
+            want = budgets[i][c] / len(members)                    # uniform within the phase
+            sigma = math.sqrt(max(want * (1 - want), 1e-9) / steps)
+            assert np.all(np.abs(counts[i, members] / steps - want) <= 5 * sigma + 1e-12)
+        # with N_c / b_c weights the sampled sum is an unbiased estimate of the full sum (phases with b_c = 0 excluded)
+        covered = [c for c in range(K) if budgets[i][c] > 0]
+        full = sum(f[i, phase[i] == c].sum() for c in covered)
+        spread = np.abs(f[i]).sum() * N / B
+        assert abs(est[i] / steps - full) < 5 * spread / math.sqrt(steps)
