@@ -182,6 +182,14 @@ PCM_API int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, co
  *   PCM_SELECT_TOP_PHASE  only chunks of the one phase with the largest keep probability (lowest
  *                         index on ties) are eligible, with equal weights; a trajectory keeps
  *                         min(B, its chunks in that phase), possibly none
+ *   PCM_SELECT_STRATIFIED the scheme the variance analysis of App. C assumes (Theorem 1): a fixed
+ *                         budget b_c per phase, then b_c chunks of phase c uniformly without
+ *                         replacement.  With q_c = clamp(floor(p_c 2^16 + 0.5), 1, 2^16), N_c the
+ *                         trajectory's valid chunks in phase c, m = min(B, N_i), D = sum N_c q_c:
+ *                         b_c = min(N_c, floor(m N_c q_c / D)); the chunks left over go one at a
+ *                         time to the phase with the largest (m N_c q_c) mod D that still has
+ *                         room (lowest index on ties), round after round.  Draws run through the
+ *                         phases in index order with one draw counter.
  *
  * pcm_importance_weights -- the weights N_c / b_c of the ratio estimator (App. C, the unbiased
  * alternative to Eq. 11), one per kept chunk, for grpo_masked_actor_step_ex's chunk_weight:
@@ -189,7 +197,12 @@ PCM_API int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, co
  *   kept_idx, kept_offsets  device, as written by pcm_sample_chunks
  *   weights   device f32 [kept_offsets[T]]: entry j belongs to kept_idx[j]
  * ------------------------------------------------------------------------------------------ */
-typedef enum { PCM_SELECT_PCM = 0, PCM_SELECT_RANDOM = 1, PCM_SELECT_TOP_PHASE = 2 } pcm_selector;
+typedef enum {
+    PCM_SELECT_PCM = 0,
+    PCM_SELECT_RANDOM = 1,
+    PCM_SELECT_TOP_PHASE = 2,
+    PCM_SELECT_STRATIFIED = 3
+} pcm_selector;
 PCM_API int pcm_sample_chunks_ex(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
                          const uint8_t* active, int T, int N, int K, int B, int selector,
                          uint64_t seed, uint64_t step, int32_t* kept_idx, int32_t* kept_offsets,

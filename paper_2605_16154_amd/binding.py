@@ -177,7 +177,7 @@ def pcm_update_keep_probs(state, Cc, valid, p_min: float = 0.1, T_rc: int = 5, k
     return keep_probs_out
 
 
-SELECTORS = {"pcm": 0, "random": 1, "top_phase": 2}
+SELECTORS = {"pcm": 0, "random": 1, "top_phase": 2, "stratified": 3}
 
 
 def pcm_sample_chunks(keep_probs, phase, n_chunks, active, B: int, seed: int, step: int, out=None,

@@ -113,13 +113,15 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
     extern __shared__ uint32_t lds[];
     uint32_t* qtab = lds;
     const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
-    uint32_t* w = lds + PCM_MAX_PHASES + (size_t)wv * N;
+    uint32_t* w = lds + PCM_MAX_PHASES + (size_t)wv * (N + 2 * PCM_MAX_PHASES);
+    int* n_in_phase = reinterpret_cast<int*>(w + N);      // stratified selector: chunks per phase, then budgets
+    int* budget = n_in_phase + PCM_MAX_PHASES;
 
     const int waves_per_block = blockDim.x / kWave;
     const int only = selector == PCM_SELECT_TOP_PHASE ? top_phase(keep_probs, K) : -1;
     for (int c = tid; c < K; c += blockDim.x) {
         uint32_t q = 1u;                      // uniform selector: equal weights
-        if (selector == PCM_SELECT_PCM) {
+        if (selector == PCM_SELECT_PCM || selector == PCM_SELECT_STRATIFIED) {
             const double x = keep_probs[c] * 65536.0 + 0.5;
             if (x >= 65536.0) q = 65536u;
             else if (x >= 1.0) q = (uint32_t)x;   // truncation = floor for positive x
@@ -140,57 +142,120 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
     const int per_lane = (N + kWave - 1) / kWave;   // <= 64 because N <= 4096
     const int k_lo = lane * per_lane;
     const uint8_t* ph = phase + (size_t)i * N;
-    uint32_t lane_sum = 0;
-    for (int j = 0; j < per_lane; ++j) {
-        const int k = k_lo + j;
-        uint32_t wk = 0;
-        if (k < Ni) {
-            int c = ph[k];
-            c = c < K ? c : K - 1;
-            wk = qtab[c];
-        }
-        if (k < N) w[k] = wk;
-        lane_sum += wk;
-    }
-    uint32_t incl = (uint32_t)wave_inclusive_scan((int)lane_sum, lane);
-    uint32_t W_rem = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
-    uint64_t mask = 0;
+    auto phase_of = [&](int k) {
+        const int c = ph[k];
+        return c < K ? c : K - 1;
+    };
 
+    // Stratified selector: a fixed budget per phase, m shared out in proportion to N_c q_c by the largest-
+    // remainder rule with caps N_c (lane c owns phase c), then uniform draws inside each phase.
+    int passes = 1;
+    if (selector == PCM_SELECT_STRATIFIED) {
+        passes = K;
+        for (int c = lane; c < K; c += kWave) n_in_phase[c] = 0;
+        __builtin_amdgcn_wave_barrier();
+        for (int k = lane; k < Ni; k += kWave) atomicAdd(&n_in_phase[phase_of(k)], 1);
+        __builtin_amdgcn_wave_barrier();
+        const int c = lane;                       // K <= 64
+        const long long n_c = c < K ? n_in_phase[c] : 0;
+        const long long weight = c < K ? n_c * (long long)qtab[c] : 0;
+        long long D = weight;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) D += __shfl_xor(D, off, kWave);
+        long long b = 0, rem = -1;
+        if (c < K && D > 0) {
+            b = ((long long)m * weight) / D;
+            rem = ((long long)m * weight) % D;
+            b = b < n_c ? b : n_c;
+        }
+        // rank of this phase in the order (larger remainder first, lower index first)
+        int rank = 0;
+        for (int o = 0; o < K; ++o) {
+            const long long ro = __shfl(rem, o, kWave);
+            rank += (c < K && (ro > rem || (ro == rem && o < c))) ? 1 : 0;
+        }
+        long long given = b;
+#pragma unroll
+        for (int off = kWave / 2; off > 0; off >>= 1) given += __shfl_xor(given, off, kWave);
+        int left = m - (int)given;
+        while (left > 0) {                        // each trip serves every phase with room once, in rank order
+            const bool room = c < K && b < n_c;
+            // position of this phase among those with room, in rank order
+            int* has_room = budget;               // indexed by rank
+            for (int o = lane; o < K; o += kWave) has_room[o] = 0;
+            __builtin_amdgcn_wave_barrier();
+            if (room) has_room[rank] = 1;
+            __builtin_amdgcn_wave_barrier();
+            int before = 0, total = 0;
+            for (int o = 0; o < K; ++o) {
+                const int h = has_room[o];
+                before += (o < rank) ? h : 0;
+                total += h;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (total == 0) break;                // cannot happen: m <= N_i = sum of the caps
+            if (room && before < left) b += 1;
+            left -= left < total ? left : total;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (c < K) budget[c] = (int)b;
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    uint64_t mask = 0;
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t s0 = (uint32_t)step, s1 = (uint32_t)(step >> 32);
     uint32_t x_lo = 0, x_hi = 0;              // lane l holds the random bits of round (r & ~63) + l
-    for (int r = 0; r < m; ++r) {
-        if ((r & (kWave - 1)) == 0) {         // the draws of the next 64 rounds, one per lane, in parallel
-            const uint64_t mine = philox_bits((uint32_t)i, (uint32_t)(r + lane), s0, s1, k0, k1);
-            x_lo = (uint32_t)mine;
-            x_hi = (uint32_t)(mine >> 32);
-        }
-        const uint64_t x = (uint64_t)(uint32_t)__shfl((int)x_lo, r & (kWave - 1), kWave) |
-                           ((uint64_t)(uint32_t)__shfl((int)x_hi, r & (kWave - 1), kWave) << 32);
-        const uint32_t t = (uint32_t)__umul64hi(x, (uint64_t)W_rem);   // in [0, W_rem)
-        const uint64_t over = __ballot(incl > t);
-        if (over == 0) break;                 // cannot happen while W_rem > 0; keeps the loop total
-        const int L = __ffsll((long long)over) - 1;
-        uint32_t picked_w = 0;
-        if (lane == L) {
-            uint32_t run = incl - lane_sum;
-            for (int j = 0; j < per_lane; ++j) {
-                const int k = k_lo + j;
-                if (k >= N) break;
-                const uint32_t wk = w[k];
-                run += wk;
-                if (wk > 0 && run > t) {
-                    picked_w = wk;
-                    w[k] = 0;
-                    mask |= (uint64_t)1 << j;
-                    break;
-                }
+    int r = 0;                                // draw counter, running on across passes
+    for (int pass = 0; pass < passes; ++pass) {
+        const int draws = selector == PCM_SELECT_STRATIFIED ? budget[pass] : m;
+        if (draws == 0) continue;
+        uint32_t lane_sum = 0;
+        for (int j = 0; j < per_lane; ++j) {
+            const int k = k_lo + j;
+            uint32_t wk = 0;
+            if (k < Ni) {
+                const int c = phase_of(k);
+                wk = selector == PCM_SELECT_STRATIFIED ? (c == pass ? 1u : 0u) : qtab[c];
             }
-            lane_sum -= picked_w;
+            if (k < N) w[k] = wk;
+            lane_sum += wk;
         }
-        picked_w = (uint32_t)__shfl((int)picked_w, L, kWave);
-        if (lane >= L) incl -= picked_w;
-        W_rem -= picked_w;
+        uint32_t incl = (uint32_t)wave_inclusive_scan((int)lane_sum, lane);
+        uint32_t W_rem = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+        for (int d = 0; d < draws; ++d, ++r) {
+            if ((r & (kWave - 1)) == 0) {     // the draws of the next 64 rounds, one per lane, in parallel
+                const uint64_t mine = philox_bits((uint32_t)i, (uint32_t)((r & ~(kWave - 1)) + lane), s0, s1, k0, k1);
+                x_lo = (uint32_t)mine;
+                x_hi = (uint32_t)(mine >> 32);
+            }
+            const uint64_t x = (uint64_t)(uint32_t)__shfl((int)x_lo, r & (kWave - 1), kWave) |
+                               ((uint64_t)(uint32_t)__shfl((int)x_hi, r & (kWave - 1), kWave) << 32);
+            const uint32_t t = (uint32_t)__umul64hi(x, (uint64_t)W_rem);   // in [0, W_rem)
+            const uint64_t over = __ballot(incl > t);
+            if (over == 0) break;             // cannot happen while W_rem > 0; keeps the loop total
+            const int L = __ffsll((long long)over) - 1;
+            uint32_t picked_w = 0;
+            if (lane == L) {
+                uint32_t run = incl - lane_sum;
+                for (int j = 0; j < per_lane; ++j) {
+                    const int k = k_lo + j;
+                    if (k >= N) break;
+                    const uint32_t wk = w[k];
+                    run += wk;
+                    if (wk > 0 && run > t) {
+                        picked_w = wk;
+                        w[k] = 0;
+                        mask |= (uint64_t)1 << j;
+                        break;
+                    }
+                }
+                lane_sum -= picked_w;
+            }
+            picked_w = (uint32_t)__shfl((int)picked_w, L, kWave);
+            if (lane >= L) incl -= picked_w;
+            W_rem -= picked_w;
+        }
     }
 
     const int mine = __popcll(mask);
@@ -224,7 +289,8 @@ int run_sample(const double* keep_probs, const uint8_t* phase, const int32_t* n_
                int32_t* kept_offsets, int32_t* n_kept, void* stream) {
     if (!keep_probs || !phase || !kept_idx || !kept_offsets || !n_kept) return PCM_EINVAL;
     if (!shape_ok(T, N, K, B)) return PCM_EINVAL;
-    if (selector != PCM_SELECT_PCM && selector != PCM_SELECT_RANDOM && selector != PCM_SELECT_TOP_PHASE)
+    if (selector != PCM_SELECT_PCM && selector != PCM_SELECT_RANDOM && selector != PCM_SELECT_TOP_PHASE &&
+        selector != PCM_SELECT_STRATIFIED)
         return PCM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     {
@@ -236,7 +302,7 @@ int run_sample(const double* keep_probs, const uint8_t* phase, const int32_t* n_
         StageTimer t(ST_SAMPLE_COMPACT, s);
         // one weight array per wavefront must fit the 64 KB a workgroup may take by default
         const int waves = N > 2048 ? 2 : kWavesPerBlock;
-        const size_t lds_bytes = (PCM_MAX_PHASES + (size_t)waves * N) * sizeof(uint32_t);
+        const size_t lds_bytes = (PCM_MAX_PHASES + (size_t)waves * (N + 2 * PCM_MAX_PHASES)) * sizeof(uint32_t);
         sample_compact<<<ceil_div(T, waves), waves * kWave, lds_bytes, s>>>(
             keep_probs, phase, n_chunks, active, T, N, K, B, selector, seed, step, kept_offsets, kept_idx);
     }

@@ -139,7 +139,7 @@ def test_sample_chunks_bit_exact(pcm, name):
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "cfg5"])
-@pytest.mark.parametrize("selector", ["random", "top_phase"])
+@pytest.mark.parametrize("selector", ["random", "top_phase", "stratified"])
 def test_ablation_selectors_bit_exact(pcm, name, selector):
     cfg = CONFIGS[name]
     ro = make_rollouts(cfg, 0)
@@ -158,7 +158,7 @@ def test_ablation_selectors_edge_cases(pcm):
     n = ragged_n_chunks(cfg)
     active = (np.arange(cfg.T) % 5 != 0).astype(np.uint8)
     p_tie = np.array([0.4, 1.0, 1.0, 0.1])                     # tie: the lower index wins
-    for selector in ("random", "top_phase"):
+    for selector in ("random", "top_phase", "stratified"):
         _sample_both(pcm, p_tie, ro["phase"], n, active, cfg.B, seed=2 ** 40 + 7, step=2 ** 33 + 1, selector=selector)
         _sample_both(pcm, p_tie, ro["phase"], n, None, cfg.N + 5, seed=1, step=0, selector=selector)
         _sample_both(pcm, p_tie, ro["phase"], None, np.zeros(cfg.T, np.uint8), cfg.B, seed=1, step=0, selector=selector)
@@ -171,8 +171,16 @@ def test_ablation_selectors_edge_cases(pcm):
         phase = np.sort(rng.integers(0, 9, size=(6, N)), axis=1).astype(np.uint8)
         pk = np.maximum(0.1, rng.random(9))
         nn = rng.integers(0, N + 1, size=6).astype(np.int32)
-        for selector in ("random", "top_phase"):
+        for selector in ("random", "top_phase", "stratified"):
             _sample_both(pcm, pk, phase, nn, None, B, seed=N, step=B, selector=selector)
+    # stratified budgets with caps that bind (a heavy phase with few chunks), many phases, more than 64 draws
+    phase = np.sort(rng.integers(0, 40, size=(5, 700)), axis=1).astype(np.uint8)
+    phase[:, :3] = 0
+    phase[:, 3:] = np.maximum(phase[:, 3:], 1)
+    pk = np.full(40, 0.1)
+    pk[0] = 1.0
+    _sample_both(pcm, pk, phase, None, None, 150, seed=9, step=4, selector="stratified", weights=True)
+    _sample_both(pcm, pk, phase[:, :7].copy(), None, None, 5, seed=9, step=4, selector="stratified", weights=True)   # N < K
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg4", "cfg5"])
