@@ -93,17 +93,22 @@ struct ActionVec<1> {
     __device__ void load(const float* p) { v[0] = *p; }
 };
 
-// grid = T * slices workgroups.  LDS: K*A 64-bit sums followed by K chunk counts.
+// grid = T * slices * phase_blocks workgroups; a workgroup pools the phases [c0, c0 + Kb) of its
+// chunks (phase_blocks is 1 unless K*A sums do not fit in LDS; then the chunks are read once per
+// block of phases).  LDS: Kb*A 64-bit sums followed by Kb chunk counts, indexed by phase - c0.
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void score_accumulate(
     const float* __restrict__ actions, const uint8_t* __restrict__ phase,
     const uint8_t* __restrict__ reward, const int32_t* __restrict__ n_chunks, int G, int N, int A,
-    int K, int slices, ull* sums, int* counts) {
+    int K, int Kb, int slices, ull* sums, int* counts) {
     extern __shared__ ull lds_sum[];
-    int* lds_cnt = reinterpret_cast<int*>(lds_sum + (size_t)K * A);
+    int* lds_cnt = reinterpret_cast<int*>(lds_sum + (size_t)Kb * A);
 
-    const int i = blockIdx.x / slices;
-    const int slice = blockIdx.x % slices;
+    const int phase_blocks = (K + Kb - 1) / Kb;
+    const int c0 = (blockIdx.x % phase_blocks) * Kb;
+    const int kb = min(Kb, K - c0);                     // phases of this workgroup
+    const int slice = (blockIdx.x / phase_blocks) % slices;
+    const int i = blockIdx.x / phase_blocks / slices;
     const int g = i / G;
     int s = 0;
     for (int r = 0; r < G; ++r) s += reward[(size_t)g * G + r] != 0;
@@ -117,8 +122,8 @@ __global__ __launch_bounds__(kThreads) void score_accumulate(
     if (k0 >= k1) return;
 
     const int tid = threadIdx.x;
-    for (int e = tid; e < K * A; e += kThreads) lds_sum[e] = 0;
-    for (int c = tid; c < K; c += kThreads) lds_cnt[c] = 0;
+    for (int e = tid; e < kb * A; e += kThreads) lds_sum[e] = 0;
+    for (int c = tid; c < kb; c += kThreads) lds_cnt[c] = 0;
     __syncthreads();
 
     const int AV = A / VEC;            // vectors per chunk
@@ -130,7 +135,7 @@ __global__ __launch_bounds__(kThreads) void score_accumulate(
         for (int v = 0; v < VEC; ++v) acc[v] = 0;
         int cur = -1, run = 0;
         auto flush = [&]() {
-            if (cur >= 0 && cur < K && run > 0) {
+            if (cur >= 0 && cur < kb && run > 0) {
 #pragma unroll
                 for (int v = 0; v < VEC; ++v)
                     atomicAdd(&lds_sum[(size_t)cur * A + jv * VEC + v], (ull)acc[v]);
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void score_accumulate(
         const float* row = actions + (size_t)i * N * A + (size_t)jv * VEC;
         const uint8_t* ph = phase + (size_t)i * N;
         for (int k = k0 + cs; k < k1; k += CPI) {
-            const int c = ph[k];
+            const int c = (int)ph[k] - c0;              // outside [0, kb): not this workgroup's (or no phase at all)
             ActionVec<VEC> x;
             x.load(row + (size_t)k * A);
             if (c != cur) {
@@ -158,12 +163,12 @@ __global__ __launch_bounds__(kThreads) void score_accumulate(
     }
     __syncthreads();
 
-    const size_t base = ((size_t)g * 2 + outcome) * K;
-    for (int e = tid; e < K * A; e += kThreads) {
+    const size_t base = ((size_t)g * 2 + outcome) * K + c0;
+    for (int e = tid; e < kb * A; e += kThreads) {
         const int c = e / A;
         if (lds_cnt[c] > 0) atomicAdd(&sums[base * A + e], lds_sum[e]);
     }
-    for (int c = tid; c < K; c += kThreads)
+    for (int c = tid; c < kb; c += kThreads)
         if (lds_cnt[c] > 0) atomicAdd(&counts[base + c], lds_cnt[c]);
 }
 
@@ -265,8 +270,11 @@ extern "C" int pcm_score_phases(const float* actions, const uint8_t* phase, cons
                                 void* stream) {
     if (!actions || !phase || !reward || !C_out || !valid_out) return PCM_EINVAL;
     if (!shape_ok(n_groups, G, N, A, K) || !(adv_eps >= 0.0)) return PCM_EINVAL;
-    const size_t lds_bytes = (size_t)K * A * sizeof(ull) + (size_t)K * sizeof(int);
-    if (lds_bytes > 64 * 1024) return PCM_EUNSUPPORTED;
+    // phases per workgroup: all K if their sums fit in 64 KB of LDS (A <= 256: at least 31 do)
+    int Kb = (int)((size_t)64 * 1024 / ((size_t)A * sizeof(ull) + sizeof(int)));
+    if (Kb > K) Kb = K;
+    const int phase_blocks = ceil_div(K, Kb);
+    const size_t lds_bytes = (size_t)Kb * A * sizeof(ull) + (size_t)Kb * sizeof(int);
     ScoreWorkspace w = carve(workspace, n_groups, A, K);
     if (!workspace_ok(workspace, workspace_bytes, w.bytes)) return PCM_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -289,13 +297,13 @@ extern "C" int pcm_score_phases(const float* actions, const uint8_t* phase, cons
         const int max_slices = ceil_div(N, 2 * chunks_per_pass);
         if (slices > max_slices) slices = max_slices;
         if (slices < 1) slices = 1;
-        const unsigned grid = (unsigned)T * (unsigned)slices;
+        const unsigned grid = (unsigned)T * (unsigned)slices * (unsigned)phase_blocks;
         if (vec4)
             score_accumulate<4><<<grid, kThreads, lds_bytes, s>>>(actions, phase, reward, n_chunks, G,
-                                                                N, A, K, slices, w.sums, w.counts);
+                                                                N, A, K, Kb, slices, w.sums, w.counts);
         else
             score_accumulate<1><<<grid, kThreads, lds_bytes, s>>>(actions, phase, reward, n_chunks, G,
-                                                                N, A, K, slices, w.sums, w.counts);
+                                                                N, A, K, Kb, slices, w.sums, w.counts);
     }
     {
         StageTimer t(ST_SCORE_FINALISE, s);

@@ -74,13 +74,18 @@ def test_score_phases_ragged_collapsed_and_null_n_chunks(pcm):
 def test_score_phases_degenerate_shapes(pcm):
     # every group collapsed: nothing valid; A not a multiple of 4 (scalar load path); K = 1; N = 1
     rng = np.random.default_rng(0)
-    for (n_groups, G, N, A, K) in [(3, 4, 5, 7, 1), (2, 2, 1, 56, 3), (5, 3, 17, 13, 6), (1, 8, 700, 56, 4)]:
+    # ... the largest K with the widest chunk (the phases are pooled in several blocks); a large group;
+    # many groups (one slice each); ragged trajectories over several slices
+    for (n_groups, G, N, A, K) in [(3, 4, 5, 7, 1), (2, 2, 1, 56, 3), (5, 3, 17, 13, 6), (1, 8, 700, 56, 4),
+                                   (2, 3, 40, 256, 64), (3, 40, 9, 56, 5), (2500, 2, 3, 8, 2), (4, 8, 130, 56, 9)]:
         T = n_groups * G
         actions = rng.uniform(-1, 1, size=(T, N, A)).astype(np.float32)
         phase = rng.integers(0, K, size=(T, N)).astype(np.uint8)
         reward = rng.integers(0, 2, size=T).astype(np.uint8)
-        C_o, valid_o = O.phase_scores(actions, phase, reward, None, n_groups, G, K)
-        C, valid, adv, act = pcm.pcm_score_phases(dev(actions), dev(phase), dev(reward), None, n_groups, G, K, 1e-6)
+        n_chunks = rng.integers(0, N + 1, size=T).astype(np.int32) if K == 9 else None
+        C_o, valid_o = O.phase_scores(actions, phase, reward, n_chunks, n_groups, G, K)
+        C, valid, adv, act = pcm.pcm_score_phases(dev(actions), dev(phase), dev(reward),
+                                                  None if n_chunks is None else dev(n_chunks), n_groups, G, K, 1e-6)
         assert np.array_equal(bits(C.cpu().numpy()), bits(C_o)), (n_groups, G, N, A, K)
         assert np.array_equal(valid.cpu().numpy(), valid_o)
     T = 8
