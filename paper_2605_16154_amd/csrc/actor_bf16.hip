@@ -75,7 +75,7 @@ __global__ void sum_parts_f32(const float* parts, int n_parts, size_t n, float* 
 
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
-    bf16 *X, *u, *v, *a, *y, *dz, *dz_extra;
+    bf16 *X, *fu, *fv, *a, *y, *dz, *dz_extra;   // fu, fv: SwiGLU derivative factors, then du, dv
     bf16* dy;
     float* parts;   // partial products of split reductions
     RowMeta meta;
@@ -94,9 +94,9 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     w.WdT = c.take<bf16>(d * ff);
     w.WoT = c.take<bf16>(V * d);
     w.X = c.take<bf16>(Mp * d);
-    w.u = c.take<bf16>(Mp * ff);
-    w.v = c.take<bf16>(Mp * ff);
     w.a = c.take<bf16>(Mp * ff);
+    if (bwd) w.fu = c.take<bf16>(Mp * ff);
+    if (bwd) w.fv = c.take<bf16>(Mp * ff);
     w.y = c.take<bf16>(Mp * d);
     w.dz = c.take<bf16>(Mp * V);
     w.meta.token = c.take<uint8_t>(Mp);
@@ -185,7 +185,9 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     if (rc != PCM_OK) return rc;
     {
         StageTimer t(ST_GEMM_GATE_UP, s);
-        launch_gemm(problem(w.X, d, w.WguT, d, Mp, 2 * ff, d, kr, kRowsAreM), EpiSwigluForward{w.u, w.v, w.a, ff}, s);
+        const GemmProblem p = problem(w.X, d, w.WguT, d, Mp, 2 * ff, d, kr, kRowsAreM);
+        if (bwd) launch_gemm(p, EpiSwigluForward<true>{w.fu, w.fv, w.a, ff}, s);
+        else launch_gemm(p, EpiSwigluForward<false>{nullptr, nullptr, w.a, ff}, s);
     }
     {
         StageTimer t(ST_GEMM_DOWN, s);
@@ -219,16 +221,16 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     }
     {
         StageTimer t(ST_GEMM_DA, s);
-        launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.u, w.v, ff}, s);      // u <- du, v <- dv
+        launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);    // fu <- du, fv <- dv
     }
     if (grads) {
-        launch_weight_grad(problem(w.X, d, w.u, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, ST_GEMM_DWG_DWU, s);   // dWg = X^T du
-        launch_weight_grad(problem(w.X, d, w.v, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, ST_GEMM_DWG_DWU, s);   // dWu = X^T dv
+        launch_weight_grad(problem(w.X, d, w.fu, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, ST_GEMM_DWG_DWU, s);   // dWg = X^T du
+        launch_weight_grad(problem(w.X, d, w.fv, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, ST_GEMM_DWG_DWU, s);   // dWu = X^T dv
     }
     if (io.dX) {
         StageTimer t(ST_GEMM_DX, s);
-        GemmProblem p = problem(w.u, ff, Wg, ff, Mp, d, ff, kr, kRowsAreM);                                      // dX = du Wg^T + dv Wu^T
-        p.A2 = w.v; p.B2 = Wu; p.K2 = ff;
+        GemmProblem p = problem(w.fu, ff, Wg, ff, Mp, d, ff, kr, kRowsAreM);                                     // dX = du Wg^T + dv Wu^T
+        p.A2 = w.fv; p.B2 = Wu; p.K2 = ff;
         launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX), d, (int)sh.rows_max()}, s);
     }
     return launch_status();

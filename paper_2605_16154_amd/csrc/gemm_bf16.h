@@ -545,12 +545,15 @@ struct EpiStoreF32 {
 
 // Gate/up projection with the activation fused: the B operand holds, per 128 packed rows, 64 gate
 // columns followed by the 64 up columns of the same index range, so a wavefront's tiles j = 0, 1
-// are u and j = 2, 3 the matching v.  Writes u, v and a = silu(u) * v (bf16, [M, ff]).
+// are u (gate) and j = 2, 3 the matching v (up).  Writes a = silu(u) * v (bf16, [M, ff]) and, for
+// a backward pass to come, the two factors it will need, computed here where the sigmoid is at
+// hand: fu = v * silu'(u) (so du = da * fu) and fv = silu(u) (so dv = da * fv).
+template <bool kKeepFactors>
 struct EpiSwigluForward {
-    bf16 *u, *v, *a;
+    bf16 *fu, *fv, *a;
     int64_t ld;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
-        constexpr int kStride = 392;                       // [u 64 | v 64 | a 64] bf16 + 8 bytes
+        constexpr int kStride = kKeepFactors ? 392 : 136;  // [a 64 | fu 64 | fv 64] bf16 + 8 bytes
         char* st = wave_stage(tc, lds);
         const int col_base = ((tc.n0 + tc.wn * 128) / 128) * 64;
 #pragma unroll
@@ -558,52 +561,65 @@ struct EpiSwigluForward {
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii) {
                 const int i = half * 2 + ii;
-                const int lr = ii * 32 + (tc.lane & 31);
-                // u and v are rounded first: the backward pass sees the stored values
-                auto uval = [&](int j, int e) { return (float)(__bf16)acc[i][j][e]; };
-                auto vval = [&](int j, int e) { return (float)(__bf16)acc[i][j + 2][e]; };
-                auto aval = [&](int j, int e) {
-                    const float x = uval(j, e);
-                    return x * fast_sigmoid(x) * vval(j, e);
-                };
-                stage_tile_row(st, kStride, tc.lane, lr, 0, 2, uval);
-                stage_tile_row(st, kStride, tc.lane, lr, 64, 2, vval);
-                stage_tile_row(st, kStride, tc.lane, lr, 128, 2, aval);
+                char* row = st + (ii * 32 + (tc.lane & 31)) * kStride;
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float av[4], fuv[4], fvv[4];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float x = acc[i][j][4 * q + t], y = acc[i][j + 2][4 * q + t];
+                            const float sg = fast_sigmoid(x);
+                            fvv[t] = x * sg;
+                            av[t] = fvv[t] * y;
+                            fuv[t] = (y * sg) * (1.f + x * (1.f - sg));
+                        }
+                        char* at = row + (j * 32 + 8 * q + 4 * (tc.lane >> 5)) * 2;
+                        *reinterpret_cast<bf16x4*>(at) = to_bf16x4(av[0], av[1], av[2], av[3]);
+                        if (kKeepFactors) {
+                            *reinterpret_cast<bf16x4*>(at + 128) = to_bf16x4(fuv[0], fuv[1], fuv[2], fuv[3]);
+                            *reinterpret_cast<bf16x4*>(at + 256) = to_bf16x4(fvv[0], fvv[1], fvv[2], fvv[3]);
+                        }
+                    }
             }
             __builtin_amdgcn_wave_barrier();
             const int row_base = tc.m0 + tc.wm * 128 + half * 64;
             const int64_t at = (int64_t)row_base * ld + col_base;     // 64 rows x 128 bytes of each output
-            copy_rows_out<64, 128>(st, kStride, reinterpret_cast<char*>(u + at), ld * 2, 64, tc.lane);
-            copy_rows_out<64, 128>(st + 128, kStride, reinterpret_cast<char*>(v + at), ld * 2, 64, tc.lane);
-            copy_rows_out<64, 128>(st + 256, kStride, reinterpret_cast<char*>(a + at), ld * 2, 64, tc.lane);
+            copy_rows_out<64, 128>(st, kStride, reinterpret_cast<char*>(a + at), ld * 2, 64, tc.lane);
+            if (kKeepFactors) {
+                copy_rows_out<64, 128>(st + 128, kStride, reinterpret_cast<char*>(fu + at), ld * 2, 64, tc.lane);
+                copy_rows_out<64, 128>(st + 256, kStride, reinterpret_cast<char*>(fv + at), ld * 2, 64, tc.lane);
+            }
             __builtin_amdgcn_wave_barrier();
         }
     }
 };
 
-// acc = da.  In place: u <- du = da * v * silu'(u), v <- dv = da * silu(u)  (bf16, [M, ff]).
-// Works through the wavefront's 128 x 128 block in four passes of 32 rows; the u, v rows of the
-// next pass are fetched into registers while the current pass is computed.
+// acc = da.  In place: fu <- du = da * fu, fv <- dv = da * fv  (bf16, [M, ff]; the factors are
+// those written by the forward epilogue).  Works through the wavefront's 128 x 128 block in four
+// passes of 32 rows; the rows of the next pass are fetched into registers while the current pass
+// is computed.
 struct EpiSwigluBackward {
-    bf16 *u, *v;
+    bf16 *fu, *fv;
     int64_t ld;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
         constexpr int kStride = 520;                       // [du 128 | dv 128] bf16 + 8 bytes
         char* st = wave_stage(tc, lds);
         const int col_base = tc.n0 + tc.wn * 128;
         const int64_t ld_bytes = ld * 2;
-        char* const u0 = reinterpret_cast<char*>(u + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
-        char* const v0 = reinterpret_cast<char*>(v + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
-        RowFetch<32, 256> fu, fv;
-        fu.fetch_rows(u0, ld_bytes, tc.lane);
-        fv.fetch_rows(v0, ld_bytes, tc.lane);
+        char* const u0 = reinterpret_cast<char*>(fu + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
+        char* const v0 = reinterpret_cast<char*>(fv + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
+        RowFetch<32, 256> ru, rv;
+        ru.fetch_rows(u0, ld_bytes, tc.lane);
+        rv.fetch_rows(v0, ld_bytes, tc.lane);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {                      // 32 rows per pass
-            fu.stash_rows(st, kStride, tc.lane);
-            fv.stash_rows(st + 256, kStride, tc.lane);
+            ru.stash_rows(st, kStride, tc.lane);
+            rv.stash_rows(st + 256, kStride, tc.lane);
             if (i < 3) {
-                fu.fetch_rows(u0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
-                fv.fetch_rows(v0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
+                ru.fetch_rows(u0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
+                rv.fetch_rows(v0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
             }
             __builtin_amdgcn_wave_barrier();
             const int lr = tc.lane & 31;
@@ -619,10 +635,9 @@ struct EpiSwigluBackward {
                     float du[4], dv[4];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        const float x = (float)u4[t], g = acc[i][j][4 * q + t];
-                        const float sg = fast_sigmoid(x);
-                        du[t] = g * (float)v4[t] * (sg * (1.f + x * (1.f - sg)));
-                        dv[t] = g * (x * sg);
+                        const float g = acc[i][j][4 * q + t];
+                        du[t] = g * (float)u4[t];
+                        dv[t] = g * (float)v4[t];
                     }
                     *reinterpret_cast<bf16x4*>(pu) = to_bf16x4(du[0], du[1], du[2], du[3]);
                     *reinterpret_cast<bf16x4*>(pv) = to_bf16x4(dv[0], dv[1], dv[2], dv[3]);
