@@ -573,7 +573,8 @@ struct EpiSwigluForward {
                             const float sg = fast_sigmoid(x);
                             fvv[t] = x * sg;
                             av[t] = fvv[t] * y;
-                            fuv[t] = (y * sg) * (1.f + x * (1.f - sg));
+                            const float ys = y * sg;
+                            fuv[t] = __builtin_fmaf(ys, x - fvv[t], ys);     // y sg (1 + x (1 - sg))
                         }
                         char* at = row + (j * 32 + 8 * q + 4 * (tc.lane >> 5)) * 2;
                         *reinterpret_cast<bf16x4*>(at) = to_bf16x4(av[0], av[1], av[2], av[3]);
