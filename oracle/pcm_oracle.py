@@ -20,9 +20,12 @@ Parity status of each function (what pins it is in tests/test_oracle_*.py):
   label_phases        pinned: hand-labelled gripper traces, one per rule and per overlap of windows
   selectors, weights  pinned: uniform inclusion frequencies of "random", phase purity and counts of
                       "top_phase", sum of N_c / b_c over a phase's kept chunks = N_c, hand example
-  actor_step          pinned by invariants only (finite differences, all-kept = unmasked,
-                      zero gradient for uniform rewards, rho = 1 reduces to A * grad log pi);
-                      no value printed in the paper fixes the head numerics.
+  actor_step          pinned: head forward against explicit loops over the definition, log-softmax
+                      and entropy against scipy, loss and every weight gradient against a library's
+                      reverse-mode autodiff of the clipped surrogate (torch, fp64, CPU; its
+                      cross_entropy routine in the rho = 1 case), finite differences, all-kept =
+                      unmasked, zero gradient for uniform rewards, additivity over groups.  (The
+                      paper prints no value for the head, so there is no golden number.)
   clip_grad_norm,     pinned: closed forms (first step moves every weight by lr * g / (|g| + eps),
   adamw_step          norm after clipping, decoupled decay with zero gradient) and agreement with
                       torch.optim.AdamW + torch.nn.utils.clip_grad_norm_ run in fp64 on the CPU

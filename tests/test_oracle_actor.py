@@ -1,10 +1,11 @@
 """Pins for the CPU checker's actor step (Eq. 2 and Eq. 11 of the paper, with PPO clipping).
 
-No number printed in the paper fixes the head's arithmetic, so the pins are the
-invariants the objective must satisfy: finite differences of the scalar loss,
-the all-kept mask reproducing the unmasked objective, zero gradient for uniform
-rewards, the rho = 1 case reducing to A * grad log pi, and textbook definitions
-of softmax and matrix products evaluated independently.
+No number printed in the paper fixes the head's arithmetic, so the pins are what
+the mathematics fixes: textbook definitions of softmax and matrix products
+evaluated independently, finite differences of the scalar loss, a library's
+reverse-mode autodiff of the clipped surrogate (and its cross-entropy routine in
+the rho = 1 case), the all-kept mask reproducing the unmasked objective, zero
+gradient for uniform rewards, additivity over groups.
 """
 import numpy as np
 import pytest
@@ -91,6 +92,52 @@ def test_gradients_match_finite_differences(perturb):
             W[idx] = keep
             fd = (lp - lm) / (2 * h)
             assert abs(fd - analytic) <= 1e-6 * max(1.0, abs(analytic)) + 1e-8, (name, idx, fd, analytic)
+
+
+def _torch_head(p, Wt, rows):
+    import torch
+    import torch.nn.functional as F
+    X = torch.tensor(p["hidden"][rows], dtype=torch.float64)
+    z = ((F.silu(X @ Wt["Wg"]) * (X @ Wt["Wu"])) @ Wt["Wd"]) @ Wt["Wo"]
+    return X, z
+
+
+@pytest.mark.parametrize("perturb", [0.0, 0.2])
+def test_gradients_match_library_autograd(perturb):
+    """The clipped surrogate written with a library's primitives (silu, matmul, log_softmax, clamp,
+    minimum) and differentiated by its reverse-mode autodiff, fp64 on the CPU: every weight gradient
+    and the loss.  At perturb = 0 the ratio is 1 and the objective is advantage-weighted cross-entropy,
+    which is evaluated with the library's own cross_entropy routine."""
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    p = _problem(seed=6)
+    r = np.random.default_rng(8)
+    old = {k: p[k] + perturb * r.standard_normal(p[k].shape) for k in ("Wg", "Wu", "Wd", "Wo")}
+    logp_old = _logp_all(p, old)
+    kept = np.array([1, 2, 5, 8, 9, 13, 17])
+    eps_low, eps_high, scale = 0.2, 0.4, 0.125
+    ref = _call(p, kept, logp_old, eps_low=eps_low, eps_high=eps_high, loss_scale=scale)
+    rows = (kept[:, None] * p["A"] + np.arange(p["A"])[None, :]).reshape(-1)
+    assert np.array_equal(rows, ref["rows"])
+    Wt = {k: torch.tensor(p[k], dtype=torch.float64, requires_grad=True) for k in ("Wg", "Wu", "Wd", "Wo")}
+    _, z = _torch_head(p, Wt, rows)
+    tok = torch.tensor(p["tokens"][rows], dtype=torch.long)
+    adv_row = torch.tensor(p["adv"][kept // p["N"]].repeat(p["A"]), dtype=torch.float64)
+    if perturb == 0.0:
+        loss = scale * (adv_row * F.cross_entropy(z, tok, reduction="none")).sum()
+        # value of the surrogate at rho = 1 is -scale * sum A; only its gradient is that of the cross-entropy
+        value = -scale * float(adv_row.sum())
+    else:
+        logp = F.log_softmax(z, dim=1).gather(1, tok[:, None])[:, 0]
+        rho = torch.exp(logp - torch.tensor(logp_old[rows]))
+        loss = -scale * torch.minimum(rho * adv_row, torch.clamp(rho, 1 - eps_low, 1 + eps_high) * adv_row).sum()
+        value = float(loss.detach())
+        assert 0.05 < ref["stats"][0] < 0.95                # some rows clipped, some not
+    loss.backward()
+    assert np.isclose(ref["loss"], value, rtol=1e-12, atol=1e-12)
+    for k in ("Wg", "Wu", "Wd", "Wo"):
+        g = Wt[k].grad.numpy()
+        assert np.allclose(ref["d" + k], g, rtol=1e-10, atol=1e-12 * max(1.0, np.abs(g).max())), k
 
 
 def test_all_kept_equals_unmasked_objective():
