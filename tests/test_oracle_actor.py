@@ -140,6 +140,48 @@ def test_gradients_match_library_autograd(perturb):
         assert np.allclose(ref["d" + k], g, rtol=1e-10, atol=1e-12 * max(1.0, np.abs(g).max())), k
 
 
+@pytest.mark.parametrize("kw", [dict(entropy_coef=0.05), dict(token_mean=True), dict(chunk_ratio=True),
+                                dict(chunk_weight=True), dict(token_mean=True, entropy_coef=0.02, chunk_ratio=True,
+                                                              chunk_weight=True)])
+def test_variant_gradients_match_library_autograd(kw):
+    """The loss variants written with library primitives (entropy through torch.special.entr, one
+    ratio per chunk through a sum of log-probabilities) and differentiated by reverse-mode autodiff."""
+    torch = pytest.importorskip("torch")
+    import torch.nn.functional as F
+    p = _problem(seed=9)
+    r = np.random.default_rng(10)
+    old = {k: p[k] + 0.1 * r.standard_normal(p[k].shape) for k in ("Wg", "Wu", "Wd", "Wo")}
+    logp_old = _logp_all(p, old)
+    kept = np.array([0, 2, 6, 7, 10, 14, 15, 19])
+    A = p["A"]
+    eps_low, eps_high, scale0 = 0.2, 0.4, 0.5
+    kw = dict(kw)
+    cw = r.uniform(0.5, 3.0, size=len(kept)) if kw.pop("chunk_weight", False) else None
+    ref = _call(p, kept, logp_old, eps_low=eps_low, eps_high=eps_high, loss_scale=scale0, chunk_weight=cw, **kw)
+    rows = ref["rows"]
+    Wt = {k: torch.tensor(p[k], dtype=torch.float64, requires_grad=True) for k in ("Wg", "Wu", "Wd", "Wo")}
+    _, z = _torch_head(p, Wt, rows)
+    tok = torch.tensor(p["tokens"][rows], dtype=torch.long)
+    adv_chunk = torch.tensor(p["adv"][kept // p["N"]], dtype=torch.float64)
+    w_chunk = torch.ones(len(kept), dtype=torch.float64) if cw is None else torch.tensor(cw)
+    delta = F.log_softmax(z, dim=1).gather(1, tok[:, None])[:, 0] - torch.tensor(logp_old[rows])
+    scale = scale0 / len(rows) if kw.get("token_mean") else scale0
+    if kw.get("chunk_ratio"):
+        rho = torch.exp(delta.reshape(-1, A).sum(1))                       # one ratio, one term per chunk
+        terms = w_chunk * torch.minimum(rho * adv_chunk, torch.clamp(rho, 1 - eps_low, 1 + eps_high) * adv_chunk)
+    else:
+        rho = torch.exp(delta)
+        a_row, w_row = adv_chunk.repeat_interleave(A), w_chunk.repeat_interleave(A)
+        terms = w_row * torch.minimum(rho * a_row, torch.clamp(rho, 1 - eps_low, 1 + eps_high) * a_row)
+    entropy = torch.special.entr(F.softmax(z, dim=1)).sum()
+    loss = -scale * terms.sum() - kw.get("entropy_coef", 0.0) * scale * entropy
+    loss.backward()
+    assert np.isclose(ref["loss"], float(loss.detach()), rtol=1e-12, atol=1e-12)
+    for k in ("Wg", "Wu", "Wd", "Wo"):
+        g = Wt[k].grad.numpy()
+        assert np.allclose(ref["d" + k], g, rtol=1e-10, atol=1e-12 * max(1.0, np.abs(g).max())), (k, kw)
+
+
 def test_all_kept_equals_unmasked_objective():
     # Eq. 11 with K_i = all chunks is Eq. 2: loss = -(1/T) sum_i A_i sum_k log pi(chunk), at rho = 1
     p = _problem(seed=3)
