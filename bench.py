@@ -394,6 +394,23 @@ def main():
         dt_c, _, _ = timed_steps(wl, k_v, 1, entropy_coef=1e-3, token_mean=True, chunk_ratio=True)
         result["loss_variants"] = {"entropy_bonus_token_mean_ms_per_step": dt_v / k_v * 1e3,
                                    "with_per_chunk_ratio_ms_per_step": dt_c / k_v * 1e3}
+        # the same step with the down and the logit projection applied as one matrix (PCM_HEAD_COMPOSED): the same
+        # loss and gradients, three of the large products replaced by products through the V-wide bottleneck
+        wl.state = pcm.pcm_state_init(cfg.K, dev)
+        k_h = max(2, min(10, args.steps))
+        dt_h, n_h, st_h = timed_steps(wl, k_h, 2, profile=True, composed_head=True)
+        rows_h = n_h * cfg.A
+        # per row: gate/up, dWg + dWu, dX (4 d ff each) and z, G, da (2 ff V each); per step: W_do, dWd, dWo (2 ff d V each)
+        executed = rows_h * (12.0 * cfg.d * cfg.ff + 6.0 * cfg.ff * cfg.V) + 6.0 * cfg.ff * cfg.d * cfg.V
+        gemm_ms_h = sum(st_h[s_][0] for s_ in GEMM_STAGES) / k_h
+        result["composed_head"] = {
+            "ms_per_step": dt_h / k_h * 1e3, "tokens_per_s": rows_h * k_h / dt_h,
+            "speedup_vs_as_written": (dt / args.steps) / (dt_h / k_h),
+            "executed_flops_per_step": executed, "as_written_flops_per_step": total_flops_step,
+            "gemm_ms_per_step": gemm_ms_h, "executed_tflops": executed / (gemm_ms_h * 1e-3) / 1e12,
+            "stages_ms_per_step": {n_: st_h[n_][0] / k_h for n_ in st_h if st_h[n_][1]},
+            "note": "z = a (Wd Wo); G = a^T dz, dWd = G Wo^T, dWo = Wd^T G, da = dz (Wd Wo)^T; `value` above is the "
+                    "evaluation as written"}
         result["hip_graph_replay"] = graph_replay_timing(wl, args.steps)
         wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
         result["optimizer_step"] = optimizer_step_timing(wl)

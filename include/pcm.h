@@ -265,16 +265,29 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
  *   loss = -scale * T - entropy_coef * scale * sum over rows of H_r
  * Gradients are those of that loss.
  *
+ * head_evaluation chooses how the two linear maps after the gated activation a are applied:
+ *   PCM_HEAD_AS_WRITTEN  y = a Wd, z = y Wo, and in the backward pass dWo = y^T dz, dy = dz Wo^T,
+ *                        dWd = a^T dy, da = dy Wd^T;
+ *   PCM_HEAD_COMPOSED    as one matrix W_do = Wd Wo [ff, V], formed inside the call from the
+ *                        current weights: z = a W_do; G = a^T dz, dWd = G Wo^T, dWo = Wd^T G,
+ *                        da = dz W_do^T.  The same function and the same gradients in exact
+ *                        arithmetic (only a linear map sits between the two projections); with
+ *                        V much smaller than d the three large products through d (down, dWd, da)
+ *                        become products through the V-wide bottleneck, about 30 % fewer
+ *                        multiply-adds for the whole step.  Rounding differs: y and dy are
+ *                        never formed (nor rounded to bf16), W_do and G are rounded instead.
+ *
  *   options    host pointer, read during the call only
  *   options->chunk_weight  device f32 [max_kept_chunks] or NULL (e.g. N_c / b_c: chunks of the
  *              chunk's phase in its trajectory over those kept)
  *   stats_out  device f32 [5] or NULL: as grpo_masked_actor_step (with a per-chunk ratio, entries 0
  *              and 1 use the chunk's ratio for each of its rows), then the mean row entropy
- * Errors: PCM_EINVAL also for options == NULL, an unknown normalisation or ratio_level, NaN
- * coefficients.
+ * Errors: PCM_EINVAL also for options == NULL, an unknown normalisation, ratio_level or
+ * head_evaluation, NaN coefficients.
  * ------------------------------------------------------------------------------------------ */
 typedef enum { PCM_NORM_SCALE = 0, PCM_NORM_TOKEN_MEAN = 1 } pcm_normalisation;
 typedef enum { PCM_RATIO_TOKEN = 0, PCM_RATIO_CHUNK = 1 } pcm_ratio_level;
+typedef enum { PCM_HEAD_AS_WRITTEN = 0, PCM_HEAD_COMPOSED = 1 } pcm_head_evaluation;
 typedef struct {
     float eps_low, eps_high;    /* clip thresholds (App. D: 0.2, 0.4) */
     float loss_scale;
@@ -282,6 +295,7 @@ typedef struct {
     int normalisation;          /* pcm_normalisation */
     int ratio_level;            /* pcm_ratio_level */
     const float* chunk_weight;  /* device, or NULL */
+    int head_evaluation;        /* pcm_head_evaluation */
 } pcm_loss_options;
 
 PCM_API int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* tokens, const float* logp_old,

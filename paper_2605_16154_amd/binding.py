@@ -28,7 +28,7 @@ class LossOptions(C.Structure):
     """pcm_loss_options of include/pcm.h."""
     _fields_ = [("eps_low", C.c_float), ("eps_high", C.c_float), ("loss_scale", C.c_float),
                 ("entropy_coef", C.c_float), ("normalisation", C.c_int), ("ratio_level", C.c_int),
-                ("chunk_weight", C.c_void_p)]
+                ("chunk_weight", C.c_void_p), ("head_evaluation", C.c_int)]
 
 
 def _sig(fn, res, args):
@@ -230,12 +230,14 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                            want_grads: bool = True, want_dX: bool = True, max_kept_chunks: Optional[int] = None,
                            out: Optional[Dict[str, torch.Tensor]] = None, token_mean: bool = False,
                            entropy_coef: float = 0.0, chunk_ratio: bool = False,
-                           chunk_weight: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+                           chunk_weight: Optional[torch.Tensor] = None,
+                           composed_head: bool = False) -> Dict[str, torch.Tensor]:
     """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[5], and if requested dWg, dWu, dWd, dWo, dX).
 
     `out` may carry preallocated tensors under those names (they are reused, not reallocated).  With none of
-    token_mean, entropy_coef, chunk_ratio, chunk_weight set this is grpo_masked_actor_step (stats[4] stays 0);
-    otherwise grpo_masked_actor_step_ex.
+    token_mean, entropy_coef, chunk_ratio, chunk_weight, composed_head set this is grpo_masked_actor_step
+    (stats[4] stays 0); otherwise grpo_masked_actor_step_ex.  composed_head = PCM_HEAD_COMPOSED (down and logit
+    projection applied as one matrix).
     """
     dev = hidden.device
     d, ff = Wg.shape
@@ -287,11 +289,11 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
     tail = (_ptr(loss, torch.float32, "loss"), _ptr(logp, torch.float32, "logp"),
             *[_ptr(g, torch.float32, "dW") for g in grads], _ptr(dX, None, "dX"), _ptr(stats, torch.float32, "stats"),
             ws, ws_bytes, _stream())
-    if token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None:
+    if token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None or composed_head:
         if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
             raise PcmError("chunk_weight is shorter than max_kept_chunks")
         opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
-                          _ptr(chunk_weight, torch.float32, "chunk_weight"))
+                          _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head))
         rc = lib().grpo_masked_actor_step_ex(*head, C.byref(opt), *tail)
         _check(rc, "grpo_masked_actor_step_ex")
     else:

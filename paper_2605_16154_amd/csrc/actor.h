@@ -43,6 +43,7 @@ struct ActorIO {
     void* dX;
     float* stats_out;
     int n_stats;      // 4, or 5 when the mean row entropy is reported too
+    bool composed;    // down and logit projection applied as one matrix Wd Wo (PCM_HEAD_COMPOSED)
     bool want_grads() const { return dWg != nullptr; }
 };
 

@@ -31,6 +31,7 @@ namespace {
 int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_old, const float* adv,
                    const int32_t* kept_idx, const int32_t* n_kept, int max_kept_chunks, int T, int N, int A, int d, int ff,
                    int V, int dtype, const void* Wg, const void* Wu, const void* Wd, const void* Wo, const LossOptions& opt,
+                   bool composed,
                    float* loss_out, float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
                    float* stats_out, int n_stats, void* workspace, size_t workspace_bytes, void* stream) {
     if (!hidden || !tokens || !logp_old || !adv || !kept_idx || !n_kept || !Wg || !Wu || !Wd || !Wo || !loss_out)
@@ -49,7 +50,7 @@ int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_
     if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
 
     ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, opt,
-               loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, n_stats};
+               loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, n_stats, composed};
     hipStream_t s = static_cast<hipStream_t>(stream);
     return dtype == PCM_F32 ? actor_f32_run(sh, io, workspace, s) : actor_bf16_run(sh, io, workspace, s);
 }
@@ -65,7 +66,7 @@ extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens,
                                       float* stats_out, void* workspace, size_t workspace_bytes, void* stream) {
     const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr};
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
-                          Wu, Wd, Wo, opt, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 4, workspace,
+                          Wu, Wd, Wo, opt, false, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 4, workspace,
                           workspace_bytes, stream);
 }
 
@@ -78,12 +79,13 @@ extern "C" int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* toke
                                          void* workspace, size_t workspace_bytes, void* stream) {
     if (!options) return PCM_EINVAL;
     if ((options->normalisation != PCM_NORM_SCALE && options->normalisation != PCM_NORM_TOKEN_MEAN) ||
-        (options->ratio_level != PCM_RATIO_TOKEN && options->ratio_level != PCM_RATIO_CHUNK))
+        (options->ratio_level != PCM_RATIO_TOKEN && options->ratio_level != PCM_RATIO_CHUNK) ||
+        (options->head_evaluation != PCM_HEAD_AS_WRITTEN && options->head_evaluation != PCM_HEAD_COMPOSED))
         return PCM_EINVAL;
     const LossOptions opt{options->eps_low, options->eps_high, options->loss_scale, options->entropy_coef,
                           options->normalisation == PCM_NORM_TOKEN_MEAN, options->ratio_level == PCM_RATIO_CHUNK,
                           options->chunk_weight};
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
-                          Wu, Wd, Wo, opt, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 5, workspace,
-                          workspace_bytes, stream);
+                          Wu, Wd, Wo, opt, options->head_evaluation == PCM_HEAD_COMPOSED, loss_out, logp_out, dWg, dWu,
+                          dWd, dWo, dX, stats_out, 5, workspace, workspace_bytes, stream);
 }

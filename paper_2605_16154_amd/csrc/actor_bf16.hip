@@ -73,10 +73,27 @@ __global__ void sum_parts_f32(const float* parts, int n_parts, size_t n, float* 
     }
 }
 
+// The same sum, rounded once to bf16 (a product that the next GEMM takes as an operand).
+__global__ void sum_parts_bf16(const float* parts, int n_parts, size_t n, bf16* out) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+        float4 acc = *reinterpret_cast<const float4*>(parts + i);
+        for (int s = 1; s < n_parts; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(parts + (size_t)s * n + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        out[i] = __float2bfloat16(acc.x);
+        out[i + 1] = __float2bfloat16(acc.y);
+        out[i + 2] = __float2bfloat16(acc.z);
+        out[i + 3] = __float2bfloat16(acc.w);
+    }
+}
+
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
     bf16 *X, *fu, *fv, *a, *y, *dz, *dz_extra;   // fu, fv: SwiGLU derivative factors, then du, dv
     bf16* dy;
+    bf16 *Wdo, *G;  // composed evaluation: Wd Wo and a^T dz, both [ff, V]
     float* parts;   // partial products of split reductions
     RowMeta meta;
     RowOut out;
@@ -110,7 +127,9 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     w.out.coef = c.take<float>(Mp);
     if (bwd) w.dz_extra = c.take<bf16>(Mp * V);
     if (bwd) w.dy = c.take<bf16>(Mp * d);
-    if (grads) w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
+    w.Wdo = c.take<bf16>(ff * V);
+    if (grads) w.G = c.take<bf16>(ff * V);
+    w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
     w.bytes = c.used();
     return w;
 }
@@ -133,20 +152,28 @@ struct KeptRows {
     int kept_max, rows_per_kept;
 };
 
-// Weight gradient C[M, N] (fp32) = A^T B over the kept rows, both operands stored [rows][features].  A small
-// output is computed as several partial products over slices of the rows, summed by a second kernel.
-void launch_weight_grad(GemmProblem p, float* C, float* parts, int stage, hipStream_t s) {
+// C[M, N] = product of p with a long reduction and possibly a small output: fp32 (C32) or rounded to bf16
+// (C16), exactly one of the two given.  A small output is computed as several partial products over slices of
+// the reduction, summed by a second kernel (no atomics).  The weight gradients are the case
+// kLayA = kLayB = kKByRows: A^T B over the kept rows with both operands stored [rows][features].
+template <int kLayA, int kLayB>
+void launch_reduction_gemm(GemmProblem p, float* C32, bf16* C16, float* parts, int stage, hipStream_t s) {
     p.splits = pick_splits((p.M / kTileM) * (p.N / kTileN), p.K1 / kTileK);
     StageTimer t(stage, s);
     if (p.splits == 1) {
-        launch_gemm<kKByRows, kKByRows>(p, EpiStoreF32{C, p.N, 0}, s);
+        if (C32) launch_gemm<kLayA, kLayB>(p, EpiStoreF32{C32, p.N, 0}, s);
+        else launch_gemm<kLayA, kLayB>(p, EpiStoreBf16{C16, p.N, p.M}, s);
         return;
     }
     const size_t n = (size_t)p.M * p.N;
-    launch_gemm<kKByRows, kKByRows>(p, EpiStoreF32{parts, p.N, (int64_t)n}, s);
+    launch_gemm<kLayA, kLayB>(p, EpiStoreF32{parts, p.N, (int64_t)n}, s);
     size_t blocks = (n / 4 + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    sum_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C);
+    if (C32) sum_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32);
+    else sum_parts_bf16<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C16);
+}
+void launch_weight_grad(const GemmProblem& p, float* C, float* parts, int stage, hipStream_t s) {
+    launch_reduction_gemm<kKByRows, kKByRows>(p, C, nullptr, parts, stage, s);
 }
 
 GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
@@ -179,8 +206,15 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
 
     transpose(s, Wg, d, ff, w.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);   // [d, ff] -> packed rows of [2 ff, d]
     transpose(s, Wu, d, ff, w.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
-    transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
-    transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
+    const KeptRows all_rows{nullptr, 0, 0};
+    if (io.composed) {
+        // W_do = Wd Wo [ff, V], from the weights as given (Wd [rows][K], Wo [K][rows])
+        launch_reduction_gemm<kRowsByK, kKByRows>(problem(Wd, d, Wo, V, ff, V, d, all_rows, kRowsUnused), nullptr, w.Wdo,
+                                                  w.parts, ST_WEIGHT_LAYOUT, s);
+    } else {
+        transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
+        transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
+    }
     int rc = launch_gather(sh, io, 2, w.X, Mp, w.meta, s);
     if (rc != PCM_OK) return rc;
     {
@@ -189,7 +223,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         if (bwd) launch_gemm(p, EpiSwigluForward<true>{w.fu, w.fv, w.a, ff}, s);
         else launch_gemm(p, EpiSwigluForward<false>{nullptr, nullptr, w.a, ff}, s);
     }
-    {
+    if (!io.composed) {
         StageTimer t(ST_GEMM_DOWN, s);
         launch_gemm(problem(w.a, ff, w.WdT, ff, Mp, d, ff, kr, kRowsAreM), EpiStoreBf16{w.y, d, Mp}, s);
     }
@@ -197,7 +231,10 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         StageTimer t(ST_GEMM_LOGITS_LOSS, s);
         EpiLogitsLoss epi{w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A,
                           io.opt, bwd ? w.dz : nullptr, w.dz_extra, io.logp_out, w.out};
-        launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM), epi, s);
+        if (io.composed)   // z = a W_do, W_do read as [K][rows]
+            launch_gemm<kRowsByK, kKByRows>(problem(w.a, ff, w.Wdo, V, Mp, V, ff, kr, kRowsAreM), epi, s);
+        else
+            launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM), epi, s);
     }
     if (io.opt.chunk_ratio) {
         rc = launch_chunk_ratio(sh, io, w.meta, w.out, Mp, s);
@@ -211,15 +248,30 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     if (rc != PCM_OK) return rc;
     if (!bwd) return launch_status();
 
-    {
-        StageTimer t(ST_GEMM_DY, s);
-        launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
-    }
-    if (grads) {
-        launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, ST_GEMM_DWO, s);   // dWo = y^T dz
-        launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, ST_GEMM_DWD, s); // dWd = a^T dy
-    }
-    {
+    if (io.composed) {
+        if (grads) {
+            // G = a^T dz [ff, V] over the kept rows, rounded to bf16 as the operand of the two products below
+            launch_reduction_gemm<kKByRows, kKByRows>(problem(w.a, ff, w.dz, V, ff, V, Mp, kr, kRowsAreK), nullptr, w.G,
+                                                      w.parts, ST_GEMM_DWD, s);
+            {
+                StageTimer t(ST_GEMM_DWD, s);                                                                     // dWd = G Wo^T
+                launch_gemm<kRowsByK, kRowsByK>(problem(w.G, V, Wo, V, ff, d, V, all_rows, kRowsUnused),
+                                                EpiStoreF32{io.dWd, d, 0}, s);
+            }
+            launch_weight_grad(problem(Wd, d, w.G, V, d, V, ff, all_rows, kRowsUnused), io.dWo, w.parts, ST_GEMM_DWO,
+                               s);                                                                                // dWo = Wd^T G
+        }
+        StageTimer t(ST_GEMM_DA, s);                                                                              // da = dz W_do^T
+        launch_gemm(problem(w.dz, V, w.Wdo, V, Mp, ff, V, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);
+    } else {
+        {
+            StageTimer t(ST_GEMM_DY, s);
+            launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
+        }
+        if (grads) {
+            launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, ST_GEMM_DWO, s);   // dWo = y^T dz
+            launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, ST_GEMM_DWD, s); // dWd = a^T dy
+        }
         StageTimer t(ST_GEMM_DA, s);
         launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);    // fu <- du, fv <- dv
     }

@@ -176,6 +176,7 @@ __global__ __launch_bounds__(kThreads) void loss_rows(float* __restrict__ z, flo
 
 struct F32Workspace {
     float *X, *u, *v, *a, *y, *z, *z_extra, *dy, *da;
+    float *Wdo, *G;   // composed evaluation: Wd Wo and a^T dz, both [ff, V]
     RowMeta meta;
     RowOut out;
     size_t bytes;
@@ -200,6 +201,8 @@ F32Workspace carve(void* ws, const ActorShape& sh, bool grads) {
     w.out.clipped = c.take<uint8_t>(M);
     w.out.entropy = c.take<float>(M);
     w.out.coef = c.take<float>(M);
+    w.Wdo = c.take<float>((size_t)sh.ff * sh.V);
+    w.G = c.take<float>((size_t)sh.ff * sh.V);
     if (grads) {
         w.z_extra = c.take<float>(M * sh.V);
         w.dy = c.take<float>(M * sh.d);
@@ -262,8 +265,13 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
         gemm(s, w.X, false, Wg, false, w.u, M, ff, d, 1, false);
         gemm(s, w.X, false, Wu, false, w.v, M, ff, d, 1, false);
         swiglu_forward<<<ew_blocks, 256, 0, s>>>(w.u, w.v, w.a, n_ff);
-        gemm(s, w.a, false, Wd, false, w.y, M, d, ff, 1, false);
-        gemm(s, w.y, false, Wo, false, w.z, M, V, d, 1, false);
+        if (io.composed) {
+            gemm(s, Wd, false, Wo, false, w.Wdo, ff, V, d, 1, false);                           // W_do = Wd Wo
+            gemm(s, w.a, false, w.Wdo, false, w.z, M, V, ff, 1, false);                         // z = a W_do
+        } else {
+            gemm(s, w.a, false, Wd, false, w.y, M, d, ff, 1, false);
+            gemm(s, w.y, false, Wo, false, w.z, M, V, d, 1, false);
+        }
     }
     {
         StageTimer t(ST_F32_LOSS, s);
@@ -290,12 +298,23 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
             zero(s, io.dWd, (size_t)ff * d);
             zero(s, io.dWg, (size_t)d * ff);
             zero(s, io.dWu, (size_t)d * ff);
-            gemm(s, w.y, true, dz, false, io.dWo, d, V, M, pick_splits(d, V, M), false);      // dWo = y^T dz
+            if (io.composed) {
+                zero(s, w.G, (size_t)ff * V);
+                gemm(s, w.a, true, dz, false, w.G, ff, V, M, pick_splits(ff, V, M), false);   // G = a^T dz
+                gemm(s, w.G, false, Wo, true, io.dWd, ff, d, V, 1, false);                    // dWd = G Wo^T
+                gemm(s, Wd, true, w.G, false, io.dWo, d, V, ff, pick_splits(d, V, ff), false); // dWo = Wd^T G
+            } else {
+                gemm(s, w.y, true, dz, false, io.dWo, d, V, M, pick_splits(d, V, M), false);  // dWo = y^T dz
+            }
         }
-        gemm(s, dz, false, Wo, true, w.dy, M, d, V, 1, false);                                  // dy = dz Wo^T
-        if (io.want_grads())
-            gemm(s, w.a, true, w.dy, false, io.dWd, ff, d, M, pick_splits(ff, d, M), false);  // dWd = a^T dy
-        gemm(s, w.dy, false, Wd, true, w.da, M, ff, d, 1, false);                               // da = dy Wd^T
+        if (io.composed) {
+            gemm(s, dz, false, w.Wdo, true, w.da, M, ff, V, 1, false);                          // da = dz W_do^T
+        } else {
+            gemm(s, dz, false, Wo, true, w.dy, M, d, V, 1, false);                              // dy = dz Wo^T
+            if (io.want_grads())
+                gemm(s, w.a, true, w.dy, false, io.dWd, ff, d, M, pick_splits(ff, d, M), false);  // dWd = a^T dy
+            gemm(s, w.dy, false, Wd, true, w.da, M, ff, d, 1, false);                           // da = dy Wd^T
+        }
         swiglu_backward<<<ew_blocks, 256, 0, s>>>(w.u, w.v, w.da, n_ff);                        // u <- du, v <- dv
         if (io.want_grads()) {
             gemm(s, w.X, true, w.u, false, io.dWg, d, ff, M, pick_splits(d, ff, M), false);   // dWg = X^T du

@@ -16,7 +16,7 @@ import torch
 from oracle import pcm_oracle as O
 from workloads import CONFIGS, make_rollouts
 
-from test_gpu_actor import BF16_TOL, check, make_problem, run_both  # noqa: E402
+from test_gpu_actor import BF16_TOL, check, composed, make_problem, run_both  # noqa: E402,F401
 
 pytestmark = pytest.mark.gpu
 
@@ -66,7 +66,7 @@ def test_fp32_cfg1_variants(pcm, name, variants):
     check(ref, got, 1e-5, len(ref["rows"]), n_stats=5)
 
 
-def test_fp32_chunk_ratio_alone_and_with_everything(pcm):
+def test_fp32_chunk_ratio_alone_and_with_everything(pcm, composed):
     cfg = CONFIGS["cfg1"]
     pr = make_problem(cfg, wstd=0.05, old_rel=0.1, eps=(0.2, 0.4))
     pr = condition_chunks(pr, (0.2, 0.4), 1e-3)
@@ -74,7 +74,8 @@ def test_fp32_chunk_ratio_alone_and_with_everything(pcm):
     assert 0.05 < ref["stats"][0] < 0.95                      # chunk ratios fall on both sides of the clip
     check(ref, got, 5e-5, len(ref["rows"]), stats_tol=5e-5, n_stats=5)
     everything = dict(chunk_ratio=True, token_mean=True, entropy_coef=1e-3, chunk_weight=weights_for(pr, 4))
-    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), scale=2.0, variants=everything, max_kept=len(pr["kept"]) + 3)
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), scale=2.0, variants=everything, max_kept=len(pr["kept"]) + 3,
+                        composed_head=composed)
     check(ref, got, 5e-5, len(ref["rows"]), stats_tol=5e-5, n_stats=5)
 
 
@@ -106,11 +107,12 @@ def _bf16_problem(A_dims=None, seed=21, n_kept=37):
     return cfg, kept[:n_kept]
 
 
-def test_bf16_token_level_variants(pcm):
+def test_bf16_token_level_variants(pcm, composed):
     cfg, kept = _bf16_problem()
     pr = make_problem(cfg, wstd=0.05, margin=0.08, kept=kept, old_rel=0.1, eps=(0.2, 0.4))
     variants = dict(entropy_coef=0.05, token_mean=True, chunk_weight=weights_for(pr, 6))
-    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), scale=50.0, torch_dtype=torch.bfloat16, max_kept=40, variants=variants)
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), scale=50.0, torch_dtype=torch.bfloat16, max_kept=40, variants=variants,
+                        composed_head=composed)
     assert 0.05 < ref["stats"][0] < 0.95
     check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2, n_stats=5)
     # the entropy term alone (zero advantages): gradients come from the entropy bonus only
@@ -121,13 +123,14 @@ def test_bf16_token_level_variants(pcm):
     check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2, n_stats=5)
 
 
-def test_bf16_chunk_ratio_short_chunks(pcm):
+def test_bf16_chunk_ratio_short_chunks(pcm, composed):
     cfg, kept = _bf16_problem(A_dims=(2, 2), seed=22, n_kept=40)          # A = 4 tokens per chunk
     assert cfg.A == 4
     pr = make_problem(cfg, wstd=0.05, kept=kept, old_rel=0.1, eps=(0.2, 0.4))
     pr = condition_chunks(pr, (0.2, 0.4), 0.12)
     variants = dict(chunk_ratio=True, entropy_coef=0.02, token_mean=True, chunk_weight=weights_for(pr, 7))
-    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), scale=20.0, torch_dtype=torch.bfloat16, max_kept=48, variants=variants)
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), scale=20.0, torch_dtype=torch.bfloat16, max_kept=48, variants=variants,
+                        composed_head=composed)
     assert 0.05 < ref["stats"][0] < 0.95
     check(ref, got, 2 * BF16_TOL, len(ref["rows"]), stats_tol=8e-2, n_stats=5)
 
