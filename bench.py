@@ -298,7 +298,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the legs after the timed steps (loss variants, optimizer step): with --no-unmasked and "
                          "--no-cpu-baseline the timed steps are then the last launches of the process")
-    ap.add_argument("--cpu-sample-chunks", type=int, default=192)
+    ap.add_argument("--cpu-sample-chunks", type=int, default=384)
     ap.add_argument("--selection-only", action="store_true",
                     help="time only the three selection calls of --config and print their bytes and GB/s")
     ap.add_argument("--copy-calibration", action="store_true",
