@@ -3,9 +3,14 @@
 // Forward:  X -> [gate|up] GEMM with silu(u)*v fused -> down GEMM -> logit GEMM with the
 //           log-softmax / ratio / clipped surrogate / dz fused.
 // Backward: dy = dz Wo^T; da = dy Wd^T with the gated-activation derivative fused (du, dv
-//           overwrite u, v); weight gradients reduce over the row dimension (a small output, dWo,
-//           as partial products over slices of the rows, summed afterwards: no atomics);
-//           dX = du Wg^T + dv Wu^T as one GEMM over two reduction segments.
+//           overwrite the two factors the forward epilogue stored); weight gradients reduce over
+//           the row dimension (a small output, dWo, as partial products over slices of the rows,
+//           summed afterwards: no atomics); dX = du Wg^T + dv Wu^T as one GEMM over two
+//           reduction segments.
+// Composed evaluation (an option): the down and the logit projection as the one matrix
+//           W_do = Wd Wo [ff, V] formed at the start of the call: z = a W_do; G = a^T dz,
+//           dWd = G Wo^T, dWo = Wd^T G, da = dz W_do^T.  y and dy are never formed; the three
+//           products through d shrink to products through V.
 //
 // The forward and input-gradient products take both operands reduction-contiguous; for the forward
 // pass the [in, out] weights are first copied transposed (gate and up interleaved in blocks of 64
