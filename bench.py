@@ -301,6 +301,9 @@ def main():
     ap.add_argument("--cpu-sample-chunks", type=int, default=384)
     ap.add_argument("--selection-only", action="store_true",
                     help="time only the three selection calls of --config and print their bytes and GB/s")
+    ap.add_argument("--scale-groups", type=int, default=1,
+                    help="with --selection-only: multiply the number of groups of --config (same per-trajectory shape), "
+                         "to see the bandwidth of the selection kernels on inputs large enough to reach it")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a known-size reference for HBM byte counters)")
     args = ap.parse_args()
@@ -318,6 +321,8 @@ def main():
     cfg = CONFIGS[args.config]
 
     if args.selection_only:
+        if args.scale_groups > 1:
+            cfg = cfg.with_(n_groups=cfg.n_groups * args.scale_groups)
         print(json.dumps(selection_only(cfg, dev, max(args.steps, 50), args.warmup)))
         return
     wl = Workload(cfg, dev, cfg.n_steps)

@@ -216,28 +216,45 @@ __global__ __launch_bounds__(kThreads) void score_pairs(const ull* __restrict__ 
 
 // Batch score of phase c = mean over the groups that contributed, added for g ascending (the order is
 // part of the definition: the result must not depend on the launch).  One workgroup: the per-group values
-// are brought into LDS 32 groups at a time with coalesced loads, then lane c adds its column in order.
-constexpr int kMeanGroups = 32;
+// are brought into LDS a block of groups at a time (kMeanEntries values, so 4096 / K groups) with coalesced
+// loads, then lane c adds its column in order.
+constexpr int kMeanEntries = 4096;
 __global__ __launch_bounds__(256) void score_mean(const double* __restrict__ pair, const uint8_t* __restrict__ pair_valid,
                                                   int n_groups, int K, double* C_out, uint8_t* valid_out) {
-    __shared__ double val[kMeanGroups * PCM_MAX_PHASES];
-    __shared__ uint8_t ok[kMeanGroups * PCM_MAX_PHASES];
+    __shared__ double val[kMeanEntries];
+    __shared__ uint8_t ok[kMeanEntries];
     const int c = threadIdx.x;
+    const int block_groups = kMeanEntries / K;          // K <= 64: at least 64 groups
     double tot = 0.0;
     int n = 0;
-    for (int g0 = 0; g0 < n_groups; g0 += kMeanGroups) {
-        const int groups = min(kMeanGroups, n_groups - g0);
-        for (int i = threadIdx.x; i < groups * K; i += blockDim.x) {
-            val[i] = pair[(size_t)g0 * K + i];
-            ok[i] = pair_valid[(size_t)g0 * K + i];
+    for (int g0 = 0; g0 < n_groups; g0 += block_groups) {
+        const int groups = min(block_groups, n_groups - g0);
+        // eight loads per thread in flight before the first is stored (a thread has at most 16 entries per block)
+        for (int i0 = threadIdx.x; i0 < groups * K; i0 += 8 * 256) {
+            double v[8];
+            uint8_t o[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * 256;
+                v[u] = i < groups * K ? pair[(size_t)g0 * K + i] : 0.0;
+                o[u] = i < groups * K ? pair_valid[(size_t)g0 * K + i] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * 256;
+                if (i < groups * K) {
+                    val[i] = o[u] ? v[u] : 0.0;   // a skipped pair adds +0.0, which leaves the non-negative sum as it is
+                    ok[i] = o[u];
+                }
+            }
         }
         __syncthreads();
         if (c < K) {
+            // branch-free, so that the LDS reads run ahead of the additions, which stay in group order
+#pragma unroll 8
             for (int g = 0; g < groups; ++g) {
-                if (ok[g * K + c]) {
-                    tot = tot + val[g * K + c];
-                    ++n;
-                }
+                tot = tot + val[g * K + c];
+                n += ok[g * K + c];
             }
         }
         __syncthreads();

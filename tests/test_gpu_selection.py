@@ -219,6 +219,13 @@ def test_sample_chunks_edge_cases(pcm):
         pk = np.maximum(0.1, rng.random(9))
         nn = rng.integers(0, N + 1, size=6).astype(np.int32)
         _sample_both(pcm, pk, phase, nn, None, B, seed=N, step=B)
+    # many short trajectories: the offsets scan runs over several trajectories per thread, with a ragged last run
+    T, N = 3001, 5
+    phase = rng.integers(0, 3, size=(T, N)).astype(np.uint8)
+    nn = rng.integers(0, N + 1, size=T).astype(np.int32)
+    act = (rng.random(T) < 0.7).astype(np.uint8)
+    for selector in ("pcm", "top_phase"):
+        _sample_both(pcm, np.array([0.2, 1.0, 0.5]), phase, nn, act, 2, seed=5, step=6, selector=selector)
 
 
 def test_ten_chained_steps_bit_exact(pcm):
