@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 import numpy as np
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+ALU_FP32_PEAK_TFLOPS = 157.3
 HBM_PEAK_GBPS = 8000.0              # MI355X HBM3E peak
 GEMM_STAGES = ("gemm_gate_up", "gemm_down", "gemm_logits_loss", "gemm_dWo", "gemm_dy", "gemm_dWd", "gemm_da",
                "gemm_dWg_dWu", "gemm_dX")
@@ -357,20 +358,29 @@ def main():
         per_stage[name] = {"ms_per_launch": ms / launches, "launches_per_step": launches / args.steps}
         if name in flops:
             per_stage[name]["tflops"] = flops[name] / (ms / launches * 1e-3) / 1e12
-    gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / args.steps
     total_flops_step = 3.0 * (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * rows
-    dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
-    dom_ms = stages[dominant][0] / stages[dominant][1]
-    achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"gemm_bf16 ({dominant})", "achieved": achieved,
-                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": stored_traffic("gemm_gate_up_cfg2_traffic.txt") if cfg.name == "cfg2" else None,
-                "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
-                "mfma_only_sustained": mfma_only,
-                "frac_of_mfma_only_random": achieved / tf_rand,
-                "all_head_gemms": {"tflops": total_flops_step / (gemm_ms_step * 1e-3) / 1e12,
-                                   "frac": total_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                                   "ms_per_step": gemm_ms_step}}
+    if cfg.dtype == "bf16":
+        gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / args.steps
+        dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
+        dom_ms = stages[dominant][0] / stages[dominant][1]
+        achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": f"gemm_bf16 ({dominant})", "achieved": achieved,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": stored_traffic("gemm_gate_up_cfg2_traffic.txt") if cfg.name == "cfg2" else None,
+                    "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
+                    "mfma_only_sustained": mfma_only,
+                    "frac_of_mfma_only_random": achieved / tf_rand,
+                    "all_head_gemms": {"tflops": total_flops_step / (gemm_ms_step * 1e-3) / 1e12,
+                                       "frac": total_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                       "ms_per_step": gemm_ms_step}}
+    else:
+        # fp32 correctness configuration: plain vector-ALU products (forward and backward stages of the fp32 path),
+        # against the fp32 vector peak 256 CU x 4 SIMD x 64 lanes x 2 flop x 2.4 GHz
+        alu_ms_step = (stages["f32_forward"][0] + stages["f32_backward"][0]) / args.steps
+        achieved = total_flops_step / (alu_ms_step * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": "sgemm (fp32 path, forward + backward)", "achieved": achieved,
+                    "peak": ALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / ALU_FP32_PEAK_TFLOPS,
+                    "traffic": None, "flops_per_step": total_flops_step, "ms_per_step": alu_ms_step}
 
     result = {"metric": "kept_action_tokens_per_sec_masked_grpo_actor_step", "value": value, "unit": "tokens/s",
               "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
