@@ -228,6 +228,42 @@ def selection_only(cfg, dev, steps, warmup):
                                       "GB_per_s": 2 * actions.numel() * 4 / copy_us / 1e3}}
 
 
+def board_power_and_clock(work, seconds=2.0):
+    """Board power (hwmon, watts) and shader clock (rocm-smi, MHz) sampled while `work(deadline)` keeps the GPU busy
+    for about `seconds`: shows whether a load runs into the board's power cap, and at what clock."""
+    import glob
+    import re
+    import subprocess
+    import threading
+    hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+    cap_f = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+    watts, mhz, stop = [], [], threading.Event()
+
+    def sample():
+        time.sleep(0.5)                          # let the load settle
+        while not stop.is_set():
+            try:
+                if hw:
+                    watts.append(int(open(hw[0]).read()) / 1e6)
+                out = subprocess.run(["rocm-smi", "--showclocks"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL,
+                                     text=True, timeout=10).stdout
+                m = re.search(r"sclk clock level: \d+: \((\d+)Mhz\)", out)
+                if m:
+                    mhz.append(int(m.group(1)))
+            except Exception:
+                pass
+            time.sleep(0.05)
+
+    th = threading.Thread(target=sample, daemon=True)
+    th.start()
+    work(time.perf_counter() + seconds)
+    stop.set()
+    th.join(timeout=15)
+    mean = lambda v: sum(v) / len(v) if v else None
+    return {"board_power_w": mean(watts), "shader_clock_mhz": mean(mhz), "samples": len(mhz),
+            "power_cap_w": int(open(cap_f[0]).read()) / 1e6 if cap_f else None}
+
+
 def graph_replay_timing(wl, steps):
     """The same steps replayed from HIP graphs (one graph per resident batch, captured once): what is left when the
     launch gaps between the ~30 kernels of a step are gone.  Reported beside `value`, which stays the eager figure."""
@@ -426,6 +462,18 @@ def main():
             "stages_ms_per_step": {n_: st_h[n_][0] / k_h for n_ in st_h if st_h[n_][1]},
             "note": "z = a (Wd Wo); G = a^T dz, dWd = G Wo^T, dWo = Wd^T G, da = dz (Wd Wo)^T; `value` above is the "
                     "evaluation as written"}
+        # is the board at its power cap, and at what clock: during the step, and during the matrix-core-only loops
+        def steps_until(deadline):
+            t = 0
+            while time.perf_counter() < deadline:
+                for _ in range(5):
+                    wl.step(t)
+                    t += 1
+                torch.cuda.synchronize()
+        result["power_and_clock"] = {
+            "training_steps": board_power_and_clock(steps_until),
+            "mfma_only_random_operands": board_power_and_clock(lambda d: pcm.pcm_measure_mfma_rate(True, 2000)),
+            "mfma_only_zero_operands": board_power_and_clock(lambda d: pcm.pcm_measure_mfma_rate(False, 2000))}
         result["hip_graph_replay"] = graph_replay_timing(wl, args.steps)
         wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
         result["optimizer_step"] = optimizer_step_timing(wl)
