@@ -134,6 +134,26 @@ PCM_API int pcm_score_phases(const float* actions, const uint8_t* phase, const u
                      uint8_t* active_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * pcm_score_phases_static -- pcm_score_phases for callers that cannot provide or allocate a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments (without the workspace pair), same kernels, same results; the
+ * accumulators live in a fixed array of PCM_SCORE_STATIC_MAX_BYTES bytes inside the library, of
+ * which every GPU the library runs on holds one copy until the process ends.  The call allocates
+ * and frees nothing (its first call on a device looks up that device's copy of the array).
+ *
+ * Errors: as pcm_score_phases; PCM_EWORKSPACE when pcm_score_phases_workspace_bytes(...) of the
+ * shape exceeds PCM_SCORE_STATIC_MAX_BYTES (about n_groups * K * A * 16 bytes: the paper-sized
+ * batch needs 0.07 MB, 64 groups of 12 phases 0.7 MB).
+ * All calls on one GPU share that GPU's array: two calls that may overlap (different streams
+ * without an ordering between them, or different host threads) race; order them.
+ * ------------------------------------------------------------------------------------------ */
+#define PCM_SCORE_STATIC_MAX_BYTES (4u << 20)
+PCM_API int pcm_score_phases_static(const float* actions, const uint8_t* phase, const uint8_t* reward,
+                     const int32_t* n_chunks, int n_groups, int G, int N, int A, int K,
+                     double adv_eps, double* C_out, uint8_t* valid_out, float* adv_out,
+                     uint8_t* active_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * pcm_update_keep_probs -- Eq. 7 (append), Eq. 8 (collapse), Eq. 9 (floor); Sec. 4.3-4.4.
  *
  * Appends the valid scores to the per-phase buffers (kept as running sums).  On the first call

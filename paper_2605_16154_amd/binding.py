@@ -53,6 +53,7 @@ def lib() -> C.CDLL:
     _sig(L.pcm_label_phases, i32, [vp, vp, i32, i32, i32, i32, i32, f32, vp, vp])
     _sig(L.pcm_score_phases_workspace_bytes, sz, [i32] * 5)
     _sig(L.pcm_score_phases, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f64, vp, vp, vp, vp, vp, sz, vp])
+    _sig(L.pcm_score_phases_static, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f64, vp, vp, vp, vp, vp])
     _sig(L.pcm_update_keep_probs, i32, [vp, vp, vp, i32, f64, i32, vp, vp])
     _sig(L.pcm_sample_chunks_workspace_bytes, sz, [i32] * 4)
     _sig(L.pcm_sample_chunks, i32, [vp, vp, vp, vp, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, sz, vp])
@@ -147,22 +148,28 @@ def pcm_label_phases(actions, n_chunks, L: int, D: int, gripper_dim: Optional[in
 
 
 def pcm_score_phases(actions, phase, reward, n_chunks, n_groups: int, G: int, K: int, adv_eps: float = 1e-6,
-                     out=None):
-    """-> (C f64[K], valid u8[K], adv f32[T], active u8[T])."""
+                     out=None, static_scratch: bool = False):
+    """-> (C f64[K], valid u8[K], adv f32[T], active u8[T]).
+
+    static_scratch=True calls pcm_score_phases_static (no workspace; `out` must then be given if the call
+    itself is to allocate nothing)."""
     T, N, A = actions.shape
     dev = actions.device
     if out is None:
         out = (torch.empty(K, dtype=torch.float64, device=dev), torch.empty(K, dtype=torch.uint8, device=dev),
                torch.empty(T, dtype=torch.float32, device=dev), torch.empty(T, dtype=torch.uint8, device=dev))
     Cc, valid, adv, active = out
+    args = (_ptr(actions, torch.float32, "actions"), _ptr(phase, torch.uint8, "phase"),
+            _ptr(reward, torch.uint8, "reward"), _ptr(n_chunks, torch.int32, "n_chunks"),
+            n_groups, G, N, A, K, adv_eps, _ptr(Cc, torch.float64, "C_out"),
+            _ptr(valid, torch.uint8, "valid_out"), _ptr(adv, torch.float32, "adv_out"),
+            _ptr(active, torch.uint8, "active_out"))
+    if static_scratch:
+        _check(lib().pcm_score_phases_static(*args, _stream()), "pcm_score_phases_static")
+        return out
     need = lib().pcm_score_phases_workspace_bytes(n_groups, G, N, A, K)
     ws, ws_bytes = _workspace(need, dev)
-    rc = lib().pcm_score_phases(_ptr(actions, torch.float32, "actions"), _ptr(phase, torch.uint8, "phase"),
-                                _ptr(reward, torch.uint8, "reward"), _ptr(n_chunks, torch.int32, "n_chunks"),
-                                n_groups, G, N, A, K, adv_eps, _ptr(Cc, torch.float64, "C_out"),
-                                _ptr(valid, torch.uint8, "valid_out"), _ptr(adv, torch.float32, "adv_out"),
-                                _ptr(active, torch.uint8, "active_out"), ws, ws_bytes, _stream())
-    _check(rc, "pcm_score_phases")
+    _check(lib().pcm_score_phases(*args, ws, ws_bytes, _stream()), "pcm_score_phases")
     return out
 
 

@@ -15,6 +15,8 @@
 //
 // This file must be compiled without floating-point contraction: the fp64 tail is specified as
 // separate multiplies and adds.
+#include <mutex>
+
 #include "common.h"
 
 #pragma clang fp contract(off)
@@ -280,23 +282,26 @@ extern "C" size_t pcm_score_phases_workspace_bytes(int n_groups, int G, int N, i
     return carve(nullptr, n_groups, A, K).bytes;
 }
 
-extern "C" int pcm_score_phases(const float* actions, const uint8_t* phase, const uint8_t* reward,
-                                const int32_t* n_chunks, int n_groups, int G, int N, int A, int K,
-                                double adv_eps, double* C_out, uint8_t* valid_out, float* adv_out,
-                                uint8_t* active_out, void* workspace, size_t workspace_bytes,
-                                void* stream) {
-    if (!actions || !phase || !reward || !C_out || !valid_out) return PCM_EINVAL;
-    if (!shape_ok(n_groups, G, N, A, K) || !(adv_eps >= 0.0)) return PCM_EINVAL;
+// ---- scratch memory owned by the library, for the entry point that takes no workspace -------------
+// Every GPU holds its own copy of this array at its own address.  In host code the array's name is
+// only a handle for hipGetSymbolAddress: the address that kernels and fills receive is the one that
+// call returns on the device that is current, looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = PCM_SCORE_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+// Argument checks and the four launches shared by both entry points; `workspace` has been checked
+// to hold carve(...).bytes.
+int run_score(const float* actions, const uint8_t* phase, const uint8_t* reward, const int32_t* n_chunks,
+              int n_groups, int G, int N, int A, int K, double adv_eps, double* C_out, uint8_t* valid_out,
+              float* adv_out, uint8_t* active_out, const ScoreWorkspace& w, hipStream_t s) {
     // phases per workgroup: all K if their sums fit in 64 KB of LDS (A <= 256: at least 31 do)
     int Kb = (int)((size_t)64 * 1024 / ((size_t)A * sizeof(ull) + sizeof(int)));
     if (Kb > K) Kb = K;
     const int phase_blocks = ceil_div(K, Kb);
     const size_t lds_bytes = (size_t)Kb * A * sizeof(ull) + (size_t)Kb * sizeof(int);
-    ScoreWorkspace w = carve(workspace, n_groups, A, K);
-    if (!workspace_ok(workspace, workspace_bytes, w.bytes)) return PCM_EWORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const int T = n_groups * G;
-
     {
         StageTimer t(ST_SCORE_PREPARE, s);
         const size_t work = w.zero_words > (size_t)T ? w.zero_words : (size_t)T;
@@ -330,4 +335,58 @@ extern "C" int pcm_score_phases(const float* actions, const uint8_t* phase, cons
         score_mean<<<1, 256, 0, s>>>(w.pair, w.pair_valid, n_groups, K, C_out, valid_out);
     }
     return launch_status();
+}
+
+bool args_ok(const float* actions, const uint8_t* phase, const uint8_t* reward, int n_groups, int G, int N, int A,
+             int K, double adv_eps, const double* C_out, const uint8_t* valid_out) {
+    return actions && phase && reward && C_out && valid_out && shape_ok(n_groups, G, N, A, K) && adv_eps >= 0.0;
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void* scratch_of_device[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return PCM_EHIP;
+    if (device < 0 || device >= kMaxDevices) return PCM_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (scratch_of_device[device] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return PCM_EHIP;
+        }
+        scratch_of_device[device] = p;
+    }
+    *out = scratch_of_device[device];
+    return PCM_OK;
+}
+
+}  // namespace
+
+extern "C" int pcm_score_phases(const float* actions, const uint8_t* phase, const uint8_t* reward,
+                                const int32_t* n_chunks, int n_groups, int G, int N, int A, int K,
+                                double adv_eps, double* C_out, uint8_t* valid_out, float* adv_out,
+                                uint8_t* active_out, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+    if (!args_ok(actions, phase, reward, n_groups, G, N, A, K, adv_eps, C_out, valid_out)) return PCM_EINVAL;
+    ScoreWorkspace w = carve(workspace, n_groups, A, K);
+    if (!workspace_ok(workspace, workspace_bytes, w.bytes)) return PCM_EWORKSPACE;
+    return run_score(actions, phase, reward, n_chunks, n_groups, G, N, A, K, adv_eps, C_out, valid_out, adv_out,
+                     active_out, w, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int pcm_score_phases_static(const float* actions, const uint8_t* phase, const uint8_t* reward,
+                                       const int32_t* n_chunks, int n_groups, int G, int N, int A, int K,
+                                       double adv_eps, double* C_out, uint8_t* valid_out, float* adv_out,
+                                       uint8_t* active_out, void* stream) {
+    if (!args_ok(actions, phase, reward, n_groups, G, N, A, K, adv_eps, C_out, valid_out)) return PCM_EINVAL;
+    if (carve(nullptr, n_groups, A, K).bytes > kStaticScratchBytes) return PCM_EWORKSPACE;
+    void* base = nullptr;
+    const int rc = static_scratch(&base);
+    if (rc != PCM_OK) return rc;
+    const ScoreWorkspace w = carve(base, n_groups, A, K);
+    return run_score(actions, phase, reward, n_chunks, n_groups, G, N, A, K, adv_eps, C_out, valid_out, adv_out,
+                     active_out, w, static_cast<hipStream_t>(stream));
 }
