@@ -229,39 +229,42 @@ def selection_only(cfg, dev, steps, warmup):
 
 
 def board_power_and_clock(work, seconds=2.0):
-    """Board power (hwmon, watts) and shader clock (rocm-smi, MHz) sampled while `work(deadline)` keeps the GPU busy
-    for about `seconds`: shows whether a load runs into the board's power cap, and at what clock."""
+    """Board power (watts) and shader clock (MHz) read from the driver's hwmon files while `work(deadline)` keeps
+    the GPU busy for about `seconds`: shows whether a load runs into the board's power cap, and at what clock.
+    Plain file reads from a thread of this process; no child processes."""
     import glob
-    import re
-    import subprocess
     import threading
-    hw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
-    cap_f = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap"))
+    base = "/sys/class/drm/card*/device/hwmon/hwmon*/"
+    first = lambda pat: (sorted(glob.glob(base + pat)) or [None])[0]
+    f_power = first("power1_input") or first("power1_average")
+    f_clock, f_cap = first("freq1_input"), first("power1_cap")
     watts, mhz, stop = [], [], threading.Event()
+
+    def read(path, scale):
+        try:
+            return int(open(path).read()) / scale
+        except (OSError, ValueError):
+            return None
 
     def sample():
         time.sleep(0.5)                          # let the load settle
         while not stop.is_set():
-            try:
-                if hw:
-                    watts.append(int(open(hw[0]).read()) / 1e6)
-                out = subprocess.run(["rocm-smi", "--showclocks"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL,
-                                     text=True, timeout=10).stdout
-                m = re.search(r"sclk clock level: \d+: \((\d+)Mhz\)", out)
-                if m:
-                    mhz.append(int(m.group(1)))
-            except Exception:
-                pass
-            time.sleep(0.05)
+            w = read(f_power, 1e6) if f_power else None
+            c = read(f_clock, 1e6) if f_clock else None
+            if w is not None:
+                watts.append(w)
+            if c is not None:
+                mhz.append(c)
+            time.sleep(0.02)
 
     th = threading.Thread(target=sample, daemon=True)
     th.start()
     work(time.perf_counter() + seconds)
     stop.set()
-    th.join(timeout=15)
+    th.join(timeout=5)
     mean = lambda v: sum(v) / len(v) if v else None
-    return {"board_power_w": mean(watts), "shader_clock_mhz": mean(mhz), "samples": len(mhz),
-            "power_cap_w": int(open(cap_f[0]).read()) / 1e6 if cap_f else None}
+    return {"board_power_w": mean(watts), "shader_clock_mhz": mean(mhz), "samples": len(watts),
+            "power_cap_w": read(f_cap, 1e6) if f_cap else None}
 
 
 def graph_replay_timing(wl, steps):
@@ -333,8 +336,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unmasked", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the legs after the timed steps (loss variants, optimizer step): with --no-unmasked and "
+                    help="skip the legs after the timed steps (stage pass, optimizer step): with --no-unmasked and "
                          "--no-cpu-baseline the timed steps are then the last launches of the process")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the loss variants, the composed head evaluation, HIP-graph replay and sample board "
+                         "power and clock (none of them enters `value`)")
     ap.add_argument("--cpu-sample-chunks", type=int, default=384)
     ap.add_argument("--selection-only", action="store_true",
                     help="time only the three selection calls of --config and print their bytes and GB/s")
@@ -375,11 +381,20 @@ def main():
     torch.cuda.synchronize()
     kept_host = wl.samp_out[0].cpu().numpy()[:int(nk0.item())]
     wl.state = pcm.pcm_state_init(cfg.K, dev)
-    dt, n_kept, stages = timed_steps(wl, args.steps, args.warmup, profile=True)
+    # `value`: the timed steps run with the library's stage timer off (no events, no locks on the call path)
+    dt, n_kept, _ = timed_steps(wl, args.steps, args.warmup, profile=False)
     rows = n_kept * cfg.A
     ms_step = dt / args.steps * 1e3
     step_ms = list(wl.step_ms)
     value = rows * args.steps / dt
+    # what regime was timed: statistics of the last timed step (fraction of rows whose gradient the clip removes,
+    # mean ratio, mean old-minus-new log-probability, rows) and its loss
+    st = wl.act_out["stats"].cpu().tolist()
+    step_stats = {"clip_fraction": st[0], "mean_ratio": st[1], "mean_logp_old_minus_logp": st[2], "rows": st[3],
+                  "loss": float(wl.act_out["loss"].item())}
+    # second pass over the same steps with the stage timer on: per-kernel durations (HIP events on the call's stream)
+    stage_steps = args.steps if args.no_extras else max(args.steps, 10)
+    dt_staged, _, stages = timed_steps(wl, stage_steps, 1, profile=True)
 
     # what the matrix cores sustain with no memory traffic at all (power-limited; depends on the operand data)
     tf_rand, clk_rand = pcm.pcm_measure_mfma_rate(True, 100)
@@ -391,12 +406,12 @@ def main():
     for name, (ms, launches) in stages.items():
         if launches == 0:
             continue
-        per_stage[name] = {"ms_per_launch": ms / launches, "launches_per_step": launches / args.steps}
+        per_stage[name] = {"ms_per_launch": ms / launches, "launches_per_step": launches / stage_steps}
         if name in flops:
             per_stage[name]["tflops"] = flops[name] / (ms / launches * 1e-3) / 1e12
     total_flops_step = 3.0 * (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * rows
     if cfg.dtype == "bf16":
-        gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / args.steps
+        gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / stage_steps
         dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
         dom_ms = stages[dominant][0] / stages[dominant][1]
         achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
@@ -412,7 +427,7 @@ def main():
     else:
         # fp32 correctness configuration: plain vector-ALU products (forward and backward stages of the fp32 path),
         # against the fp32 vector peak 256 CU x 4 SIMD x 64 lanes x 2 flop x 2.4 GHz
-        alu_ms_step = (stages["f32_forward"][0] + stages["f32_backward"][0]) / args.steps
+        alu_ms_step = (stages["f32_forward"][0] + stages["f32_backward"][0]) / stage_steps
         achieved = total_flops_step / (alu_ms_step * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": "sgemm (fp32 path, forward + backward)", "achieved": achieved,
                     "peak": ALU_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / ALU_FP32_PEAK_TFLOPS,
@@ -426,7 +441,10 @@ def main():
               "config": {"workload": f"{cfg.name}: {cfg.n_groups} groups x {cfg.G} rollouts, {cfg.N} chunks x {cfg.A} tokens, "
                                      f"K={cfg.K}, B={cfg.B}, head {cfg.d}->{cfg.ff}->{cfg.d}->{cfg.V}",
                          "kept_chunks": n_kept, "kept_rows": rows, "global_batch": cfg.T, "selection_included": True},
-              "roofline": roofline, "stages": per_stage}
+              "roofline": roofline, "timed_step_stats": step_stats,
+              "stages": per_stage, "stage_pass": {"steps": stage_steps, "ms_per_step": dt_staged / stage_steps * 1e3,
+                                                  "note": "stage durations come from a second pass with the stage timer "
+                                                          "on; `value` is timed with it off"}}
 
     if not args.no_unmasked and cfg.B < cfg.N:
         wl.state = pcm.pcm_state_init(cfg.K, dev)
@@ -436,7 +454,7 @@ def main():
         result["unmasked"] = {"ms_per_step": ms_un, "kept_rows": n_un * cfg.A, "tokens_per_s": n_un * cfg.A * k_un / dt_un,
                               "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
                               "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
-    if cfg.dtype == "bf16" and not args.no_extras:
+    if cfg.dtype == "bf16" and args.extras:
         # the same step with the loss of App. D (entropy bonus 1e-3, token-mean normalisation) and with one
         # ratio per chunk: extended entry point, same kernels plus two small ones in the per-chunk case
         wl.state = pcm.pcm_state_init(cfg.K, dev)
@@ -475,6 +493,7 @@ def main():
             "mfma_only_random_operands": board_power_and_clock(lambda d: pcm.pcm_measure_mfma_rate(True, 2000)),
             "mfma_only_zero_operands": board_power_and_clock(lambda d: pcm.pcm_measure_mfma_rate(False, 2000))}
         result["hip_graph_replay"] = graph_replay_timing(wl, args.steps)
+    if cfg.dtype == "bf16" and not args.no_extras:
         wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
         result["optimizer_step"] = optimizer_step_timing(wl)
     if not args.no_cpu_baseline:

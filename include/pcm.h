@@ -17,16 +17,16 @@
  *   - Return value: PCM_OK or a negative pcm_status.  Nothing throws, aborts or prints.
  *   - "device" pointers are HIP device memory owned by the caller; they must stay valid until
  *     `stream` has executed the call.  "host" values are plain arguments.  The library never
- *     allocates or frees device memory and never synchronises the stream or the device (the
- *     measurement aid pcm_measure_mfma_rate excepted): all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     allocates or frees device memory and never synchronises the stream or the device: all
+ *     work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - Scratch memory comes from the caller: `workspace` (device, 256-byte aligned) of at least
  *     the size returned by the matching *_workspace_bytes query (host-only, no GPU work).  Its
  *     contents on entry are irrelevant; two calls that share a workspace must be ordered on
  *     one stream.
  *   - Argument checks are made on host scalars and on pointer nullness only; device data is
- *     never read by the host.  Out-of-range device data (phase >= K, token >= V, n_chunks > N,
- *     chunk id out of range) is clamped or ignored by the kernels as stated per call, never
- *     dereferenced out of bounds.
+ *     never read by the host.  Out-of-range device data is never dereferenced out of bounds: a
+ *     phase id >= K counts as phase K-1 in every call, a token >= V as V-1, n_chunks is clamped
+ *     to [0, N], a chunk id outside [0, T*N) is treated as stated per call.
  *   - Layouts are dense row-major; T = n_groups * G trajectories, the G rollouts of group g
  *     being rows g*G .. g*G+G-1; N chunk slots per trajectory; A = L*D action values (and
  *     action tokens) per chunk (8 * 7 = 56 in the paper's setup, Sec. 5.1).
@@ -119,7 +119,7 @@ PCM_API int pcm_label_phases(const float* actions, const int32_t* n_chunks, int 
  * done in a fixed order without fused multiply-add.  Required: |a| <= 2^20, finite.
  *
  *   actions   device f32 [T, N, A]
- *   phase     device u8  [T, N]; entries >= K are ignored
+ *   phase     device u8  [T, N]; entries >= K count as phase K-1 (the same rule as in pcm_sample_chunks)
  *   reward    device u8  [T]; non-zero = success
  *   n_chunks  device i32 [T] valid chunk slots per trajectory (clamped to [0, N]); NULL = all N
  *   adv_eps   host, epsilon of Eq. 1 (>= 0)
@@ -357,29 +357,6 @@ PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float
                                 double beta2, double eps, double weight_decay, double max_grad_norm,
                                 float* grad_norm_out, void* workspace, size_t workspace_bytes,
                                 void* stream);
-
-/* ------------------------------------------------------------------------------------------
- * Stage timing (measurement aid, host side).  When enabled, grpo_masked_actor_step and the
- * selection calls record HIP events on `stream` between their kernels; pcm_profile_collect
- * waits for the last recorded event and adds each stage's elapsed time to a running total.
- * Disabled by default; enabling it does not change any result.
- * ------------------------------------------------------------------------------------------ */
-PCM_API int pcm_profile_enable(int on);                 /* returns PCM_OK; resets totals when turned on */
-PCM_API int pcm_profile_stage_count(void);
-PCM_API const char* pcm_profile_stage_name(int stage);  /* NULL if out of range */
-/* host arrays of pcm_profile_stage_count() entries: total milliseconds and launch counts */
-PCM_API int pcm_profile_collect(double* total_ms, int64_t* launches);
-
-/* ------------------------------------------------------------------------------------------
- * Measurement aid (host side; the one entry point that allocates: two small device buffers for its
- * own use, freed before it returns; it synchronises the device).  Runs bf16 matrix instructions
- * (v_mfma_f32_32x32x16_bf16, fp32 accumulation) from registers on every CU of device 0 for about
- * `milliseconds`, with all-zero operands (random_operands = 0) or roughly normal random operands,
- * and reports the sustained rate in TFLOP/s and the mean shader clock in GHz (clock_ghz may be
- * NULL).  The chip is power-limited under matrix load and the rate depends on the data, so this
- * is the ceiling a bf16 GEMM on such data can approach; the nominal peak assumes the top clock.
- * ------------------------------------------------------------------------------------------ */
-PCM_API int pcm_measure_mfma_rate(int random_operands, int milliseconds, double* tflops, double* clock_ghz);
 
 #ifdef __cplusplus
 }

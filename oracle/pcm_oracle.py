@@ -83,7 +83,9 @@ def phase_scores(actions, phase, reward, n_chunks, n_groups, G, K):
     Euclidean norm of the difference of the two sets' mean action vectors (each
     chunk's action is its L*D values flattened).  A (group, phase) pair lacking
     either outcome is skipped (App. D.2).  The batch score is the unweighted mean
-    over the groups that contributed; valid_c says whether any did.
+    over the groups that contributed; valid_c says whether any did.  The paper's
+    labelling assigns every chunk one of the K phases; an id >= K (outside that
+    domain) is counted as phase K-1 here and in the sampler alike.
 
     Arithmetic convention shared with the GPU library so that the sampler
     downstream sees identical keep probabilities: each action enters as the
@@ -114,7 +116,7 @@ def phase_scores(actions, phase, reward, n_chunks, n_groups, G, K):
         for i in rows:
             o = int(reward[i])
             for k in range(int(n_chunks[i])):
-                c = int(phase[i, k])
+                c = min(int(phase[i, k]), K - 1)        # an id beyond the last phase counts as the last
                 S[o, c] += q[i, k]
                 n[o, c] += 1
         for c in range(K):

@@ -13,7 +13,9 @@ import torch
 PCM_F32, PCM_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpcm.so")
+_MEASURE_LIB_PATH = os.path.join(_HERE, "libpcm_measure.so")
 _lib = None
+_measure_lib = None
 
 
 class PcmError(RuntimeError):
@@ -70,7 +72,6 @@ def lib() -> C.CDLL:
     _sig(L.pcm_adamw_clip_step, i32,
          [i32, C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i64,
           f64, f64, f64, f64, f64, f64, vp, vp, sz, vp])
-    _sig(L.pcm_measure_mfma_rate, i32, [i32, i32, C.POINTER(f64), C.POINTER(f64)])
     _sig(L.pcm_profile_enable, i32, [i32])
     _sig(L.pcm_profile_stage_count, i32, [])
     _sig(L.pcm_profile_stage_name, C.c_char_p, [i32])
@@ -346,9 +347,17 @@ def pcm_adamw_clip_step(grads, weights, m, v, step: int, lr: float = 1e-5, beta1
 
 
 def pcm_measure_mfma_rate(random_operands: bool = True, milliseconds: int = 100) -> Tuple[float, float]:
-    """-> (TFLOP/s, shader clock in GHz) that the bf16 matrix cores sustain on their own, on zeros or random data."""
+    """-> (TFLOP/s, shader clock in GHz) that the bf16 matrix cores sustain on their own, on zeros or random data.
+
+    A measurement aid from its own library (libpcm_measure.so, include/pcm_measure.h), not a step of the path."""
+    global _measure_lib
+    if _measure_lib is None:
+        if not os.path.exists(_MEASURE_LIB_PATH):
+            raise PcmError(f"{_MEASURE_LIB_PATH} is missing: build it with `python -m paper_2605_16154_amd.build`")
+        _measure_lib = C.CDLL(_MEASURE_LIB_PATH)
+        _sig(_measure_lib.pcm_measure_mfma_rate, C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)])
     tf, clk = C.c_double(0.0), C.c_double(0.0)
-    _check(lib().pcm_measure_mfma_rate(int(random_operands), milliseconds, C.byref(tf), C.byref(clk)),
+    _check(_measure_lib.pcm_measure_mfma_rate(int(random_operands), milliseconds, C.byref(tf), C.byref(clk)),
            "pcm_measure_mfma_rate")
     return tf.value, clk.value
 

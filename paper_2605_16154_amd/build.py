@@ -1,4 +1,5 @@
-"""Builds libpcm.so (the C-ABI library of include/pcm.h) for gfx950 with hipcc, in-tree."""
+"""Builds libpcm.so (the C-ABI library of include/pcm.h) and libpcm_measure.so (the stand-alone
+matrix-core rate probe of include/pcm_measure.h) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
 import os
@@ -10,10 +11,12 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpcm.so")
+MEASURE_LIB = os.path.join(PKG, "libpcm_measure.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
 SOURCES = ["runtime.hip", "score.hip", "keep_probs.hip", "sample.hip", "gather.hip",
-           "actor_f32.hip", "actor_bf16.hip", "actor_api.hip", "optimizer.hip", "labeler.hip", "ceiling.hip"]
+           "actor_f32.hip", "actor_bf16.hip", "actor_api.hip", "optimizer.hip", "labeler.hip"]
+MEASURE_SOURCES = ["measure/mfma_rate.hip"]
 # the fp64 tails of the selection stage are specified without fused multiply-add
 NO_CONTRACT = {"score.hip", "keep_probs.hip"}
 
@@ -30,7 +33,7 @@ def _hipcc() -> str:
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+    obj = os.path.join(OBJ_DIR, src.replace("/", "_").replace(".hip", ".o"))
     cmd = [_hipcc(), *COMMON, "-c", os.path.join(CSRC, src), "-o", obj]
     if src in NO_CONTRACT:
         cmd.insert(1, "-ffp-contract=off")
@@ -47,11 +50,12 @@ def _compile(src: str) -> str:
 def build_library(jobs: int = 8) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stderr)
+        objs = list(ex.map(_compile, SOURCES + MEASURE_SOURCES))
+    for lib, part in ((LIB, objs[:len(SOURCES)]), (MEASURE_LIB, objs[len(SOURCES):])):
+        cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *part]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr)
     return LIB
 
 

@@ -73,15 +73,15 @@ int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void*
 // Sums the per-row loss terms and statistics in a fixed order (one workgroup, fp64 accumulators).
 int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipStream_t s);
 
-// Per-chunk ratio: from the per-row dlogp, one ratio, one clipped term and one dz factor per chunk
+// Per-chunk ratio: from the per-row dlogp, one ratio, one clipped term and one dz factor per kept chunk
 // (written to every row of the chunk; the term only to its first row).
 int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t rows_pad,
                        hipStream_t s);
 
-// dz[r, :] = coef[r] * dz[r, :] (+ extra[r, :] if extra is given), rows [0, rows_pad) of V columns;
+// dz[r, :] = coef[r] * dz[r, :] (+ extra[r, :] if extra is given) for the live rows r (V columns each);
 // elem_bytes is 2 (bf16) or 4 (fp32).
-int launch_scale_rows(void* dz, const void* extra, const float* coef, int64_t rows_pad, int V, int elem_bytes,
-                      hipStream_t s);
+int launch_scale_rows(const ActorShape& sh, const ActorIO& io, void* dz, const void* extra, const float* coef,
+                      int64_t rows_pad, int elem_bytes, hipStream_t s);
 
 // Number of live rows from the device-side kept count.
 __device__ inline int64_t live_rows(const int32_t* n_kept, int max_chunks, int A) {

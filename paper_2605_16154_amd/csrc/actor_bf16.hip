@@ -245,7 +245,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         rc = launch_chunk_ratio(sh, io, w.meta, w.out, Mp, s);
         if (rc != PCM_OK) return rc;
         if (bwd) {
-            rc = launch_scale_rows(w.dz, io.opt.entropy_coef != 0.f ? w.dz_extra : nullptr, w.out.coef, Mp, V, 2, s);
+            rc = launch_scale_rows(sh, io, w.dz, io.opt.entropy_coef != 0.f ? w.dz_extra : nullptr, w.out.coef, Mp, 2, s);
             if (rc != PCM_OK) return rc;
         }
     }

@@ -3,7 +3,10 @@
 // This path exists for small heads and for checking the method at fp32 accuracy; it is bound by
 // the fp32 vector ALUs, not by the matrix cores.  One LDS-tiled GEMM kernel with general strides
 // serves all nine products of the forward and backward pass; reductions over the row dimension
-// (the weight gradients) are split across workgroups and combined with fp32 atomics.
+// (the weight gradients) are split across workgroups into partial products that a second kernel
+// adds in slice order, so the results are the same from run to run (no atomics).
+#include <algorithm>
+
 #include "actor.h"
 
 namespace pcm {
@@ -13,11 +16,11 @@ constexpr int kThreads = 256;
 constexpr int BM = 64, BN = 64, BK = 16;
 
 // C[m,n] (+)= sum_k A[m*sam + k*sak] * B[k*sbk + n*sbn]; grid = (tiles_n, tiles_m, splits).
-// splits > 1: each z-slice adds its partial product with atomics (C must hold the base value).
+// splits > 1: z-slice q stores its partial product at C + q * split_stride (the caller sums the slices).
 __global__ __launch_bounds__(kThreads) void sgemm(const float* __restrict__ A, int64_t sam, int64_t sak,
                                                   const float* __restrict__ B, int64_t sbk, int64_t sbn,
                                                   float* __restrict__ C, int64_t ldc, int M, int N, int K,
-                                                  int k_per_split, int accumulate) {
+                                                  int k_per_split, int accumulate, int64_t split_stride) {
     __shared__ float As[BK][BM + 4];
     __shared__ float Bs[BK][BN + 4];
     const int tid = threadIdx.x;
@@ -66,17 +69,21 @@ __global__ __launch_bounds__(kThreads) void sgemm(const float* __restrict__ A, i
         for (int j = 0; j < 4; ++j) {
             const int gn = n0 + tn + j;
             if (gn >= N) continue;
-            float* c = C + gm * ldc + gn;
-            if (gridDim.z > 1) atomicAdd(c, acc[i][j]);
-            else if (accumulate) *c += acc[i][j];
+            float* c = C + (int64_t)blockIdx.z * split_stride + gm * ldc + gn;
+            if (accumulate) *c += acc[i][j];
             else *c = acc[i][j];
         }
     }
 }
 
-__global__ void fill_zero(float* p, size_t n) {
+// out[i] = parts[0][i] + parts[1][i] + ... in slice order (parts are n floats apart).
+__global__ void sum_slices(const float* __restrict__ parts, int n_parts, size_t n, float* __restrict__ out) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.f;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        float acc = parts[i];
+        for (int q = 1; q < n_parts; ++q) acc += parts[(size_t)q * n + i];
+        out[i] = acc;
+    }
 }
 
 __global__ void swiglu_forward(const float* __restrict__ u, const float* __restrict__ v, float* __restrict__ a,
@@ -174,9 +181,28 @@ __global__ __launch_bounds__(kThreads) void loss_rows(float* __restrict__ z, flo
     }
 }
 
+// Reduction split of a product with a small output and a long reduction: enough slices to fill the
+// chip, at least four 16-wide steps each.  Returns the slice length; `splits` the number of slices.
+int split_of(int M, int N, int K, int& splits) {
+    const int tiles = ceil_div(M, BM) * ceil_div(N, BN);
+    splits = ceil_div(1024, tiles);
+    const int max_splits = ceil_div(K, 4 * BK);
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    const int k_per = ceil_div(ceil_div(K, splits), BK) * BK;
+    splits = ceil_div(K, k_per);
+    return k_per;
+}
+size_t split_floats(int M, int N, int K) {
+    int splits;
+    split_of(M, N, K, splits);
+    return splits > 1 ? (size_t)splits * M * N : 0;
+}
+
 struct F32Workspace {
     float *X, *u, *v, *a, *y, *z, *z_extra, *dy, *da;
     float *Wdo, *G;   // composed evaluation: Wd Wo and a^T dz, both [ff, V]
+    float* parts;     // partial products of the split reductions
     RowMeta meta;
     RowOut out;
     size_t bytes;
@@ -207,37 +233,40 @@ F32Workspace carve(void* ws, const ActorShape& sh, bool grads) {
         w.z_extra = c.take<float>(M * sh.V);
         w.dy = c.take<float>(M * sh.d);
         w.da = c.take<float>(M * sh.ff);
+        const int rows = (int)M;
+        size_t parts = split_floats(sh.d, sh.V, rows);                       // dWo = y^T dz
+        parts = std::max(parts, split_floats(sh.ff, sh.d, rows));             // dWd = a^T dy
+        parts = std::max(parts, split_floats(sh.d, sh.ff, rows));             // dWg, dWu
+        parts = std::max(parts, split_floats(sh.ff, sh.V, rows));             // composed: G = a^T dz
+        parts = std::max(parts, split_floats(sh.d, sh.V, sh.ff));             // composed: dWo = Wd^T G
+        w.parts = c.take<float>(parts);
     }
     w.bytes = c.used();
     return w;
 }
 
-enum Layout { kRowMajor, kTransposed };
-
 // C[M,N] (+)= op(A) op(B) with A given as [M,K] row-major (or [K,M] if a_t) and B as [K,N]
 // row-major (or [N,K] if b_t).
 void gemm(hipStream_t s, const float* A, bool a_t, const float* B, bool b_t, float* C, int M, int N, int K,
-          int splits, bool accumulate) {
+          bool accumulate) {
     const int64_t sam = a_t ? 1 : K, sak = a_t ? M : 1;
     const int64_t sbk = b_t ? 1 : N, sbn = b_t ? K : 1;
-    if (splits < 1) splits = 1;
-    int k_per = ceil_div(ceil_div(K, splits), BK) * BK;
-    splits = ceil_div(K, k_per);
+    dim3 grid(ceil_div(N, BN), ceil_div(M, BM), 1);
+    sgemm<<<grid, kThreads, 0, s>>>(A, sam, sak, B, sbk, sbn, C, N, M, N, K, ceil_div(K, BK) * BK, accumulate ? 1 : 0, 0);
+}
+
+// C[M,N] = A^T B with A [K,M], B [K,N] row-major: the weight-gradient shape (reduction over rows).
+void gemm_reduce_rows(hipStream_t s, const float* A, const float* B, float* C, int M, int N, int K, float* parts) {
+    int splits;
+    const int k_per = split_of(M, N, K, splits);
     dim3 grid(ceil_div(N, BN), ceil_div(M, BM), splits);
-    sgemm<<<grid, kThreads, 0, s>>>(A, sam, sak, B, sbk, sbn, C, N, M, N, K, k_per, accumulate ? 1 : 0);
-}
-
-int pick_splits(int M, int N, int K) {
-    const int tiles = ceil_div(M, BM) * ceil_div(N, BN);
-    int splits = ceil_div(1024, tiles);
-    const int max_splits = ceil_div(K, 4 * BK);
-    if (splits > max_splits) splits = max_splits;
-    return splits < 1 ? 1 : splits;
-}
-
-void zero(hipStream_t s, float* p, size_t n) {
-    const unsigned blocks = (unsigned)((n + 1023) / 1024);
-    fill_zero<<<blocks < 2048 ? (blocks ? blocks : 1) : 2048, 256, 0, s>>>(p, n);
+    const size_t n = (size_t)M * N;
+    float* dst = splits > 1 ? parts : C;
+    sgemm<<<grid, kThreads, 0, s>>>(A, 1, M, B, N, 1, dst, N, M, N, K, k_per, 0, (int64_t)n);
+    if (splits > 1) {
+        const unsigned blocks = (unsigned)((n + 255) / 256);
+        sum_slices<<<blocks < 4096 ? blocks : 4096, 256, 0, s>>>(parts, splits, n, C);
+    }
 }
 
 }  // namespace
@@ -262,15 +291,15 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
     if (rc != PCM_OK) return rc;
     {
         StageTimer t(ST_F32_FORWARD, s);
-        gemm(s, w.X, false, Wg, false, w.u, M, ff, d, 1, false);
-        gemm(s, w.X, false, Wu, false, w.v, M, ff, d, 1, false);
+        gemm(s, w.X, false, Wg, false, w.u, M, ff, d, false);
+        gemm(s, w.X, false, Wu, false, w.v, M, ff, d, false);
         swiglu_forward<<<ew_blocks, 256, 0, s>>>(w.u, w.v, w.a, n_ff);
         if (io.composed) {
-            gemm(s, Wd, false, Wo, false, w.Wdo, ff, V, d, 1, false);                           // W_do = Wd Wo
-            gemm(s, w.a, false, w.Wdo, false, w.z, M, V, ff, 1, false);                         // z = a W_do
+            gemm(s, Wd, false, Wo, false, w.Wdo, ff, V, d, false);                           // W_do = Wd Wo
+            gemm(s, w.a, false, w.Wdo, false, w.z, M, V, ff, false);                         // z = a W_do
         } else {
-            gemm(s, w.a, false, Wd, false, w.y, M, d, ff, 1, false);
-            gemm(s, w.y, false, Wo, false, w.z, M, V, d, 1, false);
+            gemm(s, w.a, false, Wd, false, w.y, M, d, ff, false);
+            gemm(s, w.y, false, Wo, false, w.z, M, V, d, false);
         }
     }
     {
@@ -283,7 +312,7 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
         rc = launch_chunk_ratio(sh, io, w.meta, w.out, M, s);
         if (rc != PCM_OK) return rc;
         if (bwd) {
-            rc = launch_scale_rows(w.z, io.opt.entropy_coef != 0.f ? w.z_extra : nullptr, w.out.coef, M, V, 4, s);
+            rc = launch_scale_rows(sh, io, w.z, io.opt.entropy_coef != 0.f ? w.z_extra : nullptr, w.out.coef, M, 4, s);
             if (rc != PCM_OK) return rc;
         }
     }
@@ -294,36 +323,30 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
         StageTimer t(ST_F32_BACKWARD, s);
         float* dz = w.z;
         if (io.want_grads()) {
-            zero(s, io.dWo, (size_t)d * V);
-            zero(s, io.dWd, (size_t)ff * d);
-            zero(s, io.dWg, (size_t)d * ff);
-            zero(s, io.dWu, (size_t)d * ff);
             if (io.composed) {
-                zero(s, w.G, (size_t)ff * V);
-                gemm(s, w.a, true, dz, false, w.G, ff, V, M, pick_splits(ff, V, M), false);   // G = a^T dz
-                gemm(s, w.G, false, Wo, true, io.dWd, ff, d, V, 1, false);                    // dWd = G Wo^T
-                gemm(s, Wd, true, w.G, false, io.dWo, d, V, ff, pick_splits(d, V, ff), false); // dWo = Wd^T G
+                gemm_reduce_rows(s, w.a, dz, w.G, ff, V, M, w.parts);                           // G = a^T dz
+                gemm(s, w.G, false, Wo, true, io.dWd, ff, d, V, false);                         // dWd = G Wo^T
+                gemm_reduce_rows(s, Wd, w.G, io.dWo, d, V, ff, w.parts);                        // dWo = Wd^T G
             } else {
-                gemm(s, w.y, true, dz, false, io.dWo, d, V, M, pick_splits(d, V, M), false);  // dWo = y^T dz
+                gemm_reduce_rows(s, w.y, dz, io.dWo, d, V, M, w.parts);                         // dWo = y^T dz
             }
         }
         if (io.composed) {
-            gemm(s, dz, false, w.Wdo, true, w.da, M, ff, V, 1, false);                          // da = dz W_do^T
+            gemm(s, dz, false, w.Wdo, true, w.da, M, ff, V, false);                             // da = dz W_do^T
         } else {
-            gemm(s, dz, false, Wo, true, w.dy, M, d, V, 1, false);                              // dy = dz Wo^T
-            if (io.want_grads())
-                gemm(s, w.a, true, w.dy, false, io.dWd, ff, d, M, pick_splits(ff, d, M), false);  // dWd = a^T dy
-            gemm(s, w.dy, false, Wd, true, w.da, M, ff, d, 1, false);                           // da = dy Wd^T
+            gemm(s, dz, false, Wo, true, w.dy, M, d, V, false);                                 // dy = dz Wo^T
+            if (io.want_grads()) gemm_reduce_rows(s, w.a, w.dy, io.dWd, ff, d, M, w.parts);     // dWd = a^T dy
+            gemm(s, w.dy, false, Wd, true, w.da, M, ff, d, false);                              // da = dy Wd^T
         }
         swiglu_backward<<<ew_blocks, 256, 0, s>>>(w.u, w.v, w.da, n_ff);                        // u <- du, v <- dv
         if (io.want_grads()) {
-            gemm(s, w.X, true, w.u, false, io.dWg, d, ff, M, pick_splits(d, ff, M), false);   // dWg = X^T du
-            gemm(s, w.X, true, w.v, false, io.dWu, d, ff, M, pick_splits(d, ff, M), false);   // dWu = X^T dv
+            gemm_reduce_rows(s, w.X, w.u, io.dWg, d, ff, M, w.parts);                           // dWg = X^T du
+            gemm_reduce_rows(s, w.X, w.v, io.dWu, d, ff, M, w.parts);                           // dWu = X^T dv
         }
         if (io.dX) {
             float* dX = static_cast<float*>(io.dX);
-            gemm(s, w.u, false, Wg, true, dX, M, d, ff, 1, false);                              // dX = du Wg^T
-            gemm(s, w.v, false, Wu, true, dX, M, d, ff, 1, true);                               //    + dv Wu^T
+            gemm(s, w.u, false, Wg, true, dX, M, d, ff, false);                              // dX = du Wg^T
+            gemm(s, w.v, false, Wu, true, dX, M, d, ff, true);                               //    + dv Wu^T
         }
     }
     return launch_status();

@@ -133,13 +133,7 @@ __global__ __launch_bounds__(256) void chunk_ratio_rows(const float* __restrict_
     if (r0 >= rows_pad) return;
     const int64_t rows = live_rows(n_kept, max_chunks, A);
     const int64_t r1 = r0 + A < rows_pad ? r0 + A : rows_pad;
-    if (r0 >= rows) {                                   // padding rows: no contribution
-        for (int64_t r = r0; r < r1; ++r) {
-            term[r] = 0.f;
-            coef[r] = 0.f;
-        }
-        return;
-    }
+    if (r0 >= rows) return;                             // beyond the kept chunks: nothing reads these rows
     float sum = 0.f;
     for (int64_t r = r0; r < r1; ++r) sum -= dlogp[r];
     const float w = opt.chunk_weight ? opt.chunk_weight[c] : 1.f;
@@ -165,9 +159,15 @@ __device__ inline float from_f32<float>(float x) { return x; }
 template <>
 __device__ inline bf16 from_f32<bf16>(float x) { return __float2bfloat16(x); }
 
+// Rows [0, live rows) only: rows beyond them hold zeros (or, in row tiles that the logit product
+// skipped, nothing) and are not read by anything downstream.
 template <typename T>
 __global__ __launch_bounds__(256) void scale_rows(T* __restrict__ dz, const T* __restrict__ extra,
-                                                   const float* __restrict__ coef, int64_t n, int V) {
+                                                   const float* __restrict__ coef, const int32_t* __restrict__ n_kept,
+                                                   int max_chunks, int A, int64_t rows_pad, int V) {
+    int64_t rows = live_rows(n_kept, max_chunks, A);
+    rows = rows < rows_pad ? rows : rows_pad;
+    const int64_t n = rows * V;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         float x = coef[i / V] * to_f32<T>(dz[i]);
@@ -215,15 +215,17 @@ int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, Ro
     return launch_status();
 }
 
-int launch_scale_rows(void* dz, const void* extra, const float* coef, int64_t rows_pad, int V, int elem_bytes,
-                      hipStream_t s) {
+int launch_scale_rows(const ActorShape& sh, const ActorIO& io, void* dz, const void* extra, const float* coef,
+                      int64_t rows_pad, int elem_bytes, hipStream_t s) {
     StageTimer t(ST_REDUCE, s);
-    const int64_t n = rows_pad * V;
+    const int64_t n = rows_pad * sh.V;
     unsigned blocks = (unsigned)(ceil_div64(n, 256) < 4096 ? ceil_div64(n, 256) : 4096);
     if (elem_bytes == 2)
-        scale_rows<bf16><<<blocks, 256, 0, s>>>(static_cast<bf16*>(dz), static_cast<const bf16*>(extra), coef, n, V);
+        scale_rows<bf16><<<blocks, 256, 0, s>>>(static_cast<bf16*>(dz), static_cast<const bf16*>(extra), coef, io.n_kept,
+                                                sh.max_chunks, sh.A, rows_pad, sh.V);
     else
-        scale_rows<float><<<blocks, 256, 0, s>>>(static_cast<float*>(dz), static_cast<const float*>(extra), coef, n, V);
+        scale_rows<float><<<blocks, 256, 0, s>>>(static_cast<float*>(dz), static_cast<const float*>(extra), coef,
+                                                 io.n_kept, sh.max_chunks, sh.A, rows_pad, sh.V);
     return launch_status();
 }
 

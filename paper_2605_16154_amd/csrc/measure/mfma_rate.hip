@@ -1,8 +1,11 @@
-// Measurement aid: the rate the matrix cores sustain on their own (no memory traffic) under the
+// Stand-alone measurement aid (its own small library, not part of libpcm.so): the rate the matrix cores sustain on their own (no memory traffic) under the
 // chip's power limit, which depends on the operand data: with all-zero operands the clock stays
 // near its maximum, with random operands the power limit pulls it down by about a quarter.  The
 // benchmark reports the GEMMs against this figure as well as against the nominal peak.
-#include "common.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pcm_measure.h"
 
 namespace pcm {
 namespace {
@@ -59,9 +62,10 @@ using namespace pcm;
 
 extern "C" int pcm_measure_mfma_rate(int random_operands, int milliseconds, double* tflops, double* clock_ghz) {
     if (!tflops || milliseconds < 1 || milliseconds > 2000) return PCM_EINVAL;
-    int n_cu = 0, wall_khz = 0;
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, 0) != hipSuccess || n_cu < 1) return PCM_EHIP;
-    if (hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, 0) != hipSuccess) wall_khz = 0;
+    int n_cu = 0, wall_khz = 0, device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return PCM_EHIP;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || n_cu < 1) return PCM_EHIP;
+    if (hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, device) != hipSuccess) wall_khz = 0;
     float* out = nullptr;
     long long* ticks = nullptr;
     if (hipMalloc(&out, (size_t)n_cu * 256 * sizeof(float)) != hipSuccess) return PCM_EHIP;

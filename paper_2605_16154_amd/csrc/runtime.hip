@@ -3,6 +3,7 @@
 #include <vector>
 
 #include "common.h"
+#include "pcm_measure.h"
 
 namespace pcm {
 namespace {

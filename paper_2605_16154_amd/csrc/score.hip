@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kThreads) void score_accumulate(
         const float* row = actions + (size_t)i * N * A + (size_t)jv * VEC;
         const uint8_t* ph = phase + (size_t)i * N;
         for (int k = k0 + cs; k < k1; k += CPI) {
-            const int c = (int)ph[k] - c0;              // outside [0, kb): not this workgroup's (or no phase at all)
+            const int c = min((int)ph[k], K - 1) - c0;  // ids beyond the last phase count as the last; outside [0, kb): another block's
             ActionVec<VEC> x;
             x.load(row + (size_t)k * A);
             if (c != cur) {

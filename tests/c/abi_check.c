@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include "pcm.h"
+#include "pcm_measure.h"
 
 int main(void) {
     int64_t numel[2] = {4096 * 3 + 1, 5};

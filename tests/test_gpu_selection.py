@@ -94,6 +94,22 @@ def test_score_phases_degenerate_shapes(pcm):
     assert not valid.cpu().numpy().any() and not C.cpu().numpy().any() and not act.cpu().numpy().any()
 
 
+def test_phase_ids_beyond_the_last_phase_follow_one_rule(pcm):
+    # ids >= K count as phase K - 1 in the score and in the sampler (and in the N_c / b_c weights)
+    cfg = CONFIGS["cfg2"]
+    ro = make_rollouts(cfg, 1)
+    K = cfg.K - 2                                               # the batch holds ids up to K + 1
+    phase = ro["phase"].copy()
+    phase[::3, ::5] = 200                                       # and some far out of range
+    C_o, valid_o = O.phase_scores(ro["actions"], phase, ro["reward"], ro["n_chunks"], cfg.n_groups, cfg.G, K)
+    C, valid, adv, act = pcm.pcm_score_phases(dev(ro["actions"]), dev(phase), dev(ro["reward"]), dev(ro["n_chunks"]),
+                                              cfg.n_groups, cfg.G, K, 1e-6)
+    assert np.array_equal(bits(C.cpu().numpy()), bits(C_o)) and np.array_equal(valid.cpu().numpy(), valid_o)
+    assert valid_o[K - 1]                                       # the last phase did collect the strays
+    _sample_both(pcm, np.array([0.2, 1.0, 0.45]), phase, ro["n_chunks"], act.cpu().numpy(), cfg.B, seed=3, step=8,
+                 weights=True)
+
+
 def test_keep_probs_chain_bit_exact(pcm):
     rng = np.random.default_rng(5)
     K = 7

@@ -1,4 +1,5 @@
-"""The built C-ABI library loads and exports every function that include/pcm.h declares.
+"""The built C-ABI libraries load and export every function that include/*.h declares: libpcm.so everything of
+pcm.h plus the stage timer of pcm_measure.h, libpcm_measure.so the stand-alone matrix-core rate probe.
 
 No GPU work is issued here: only host-side queries are called.
 """
@@ -10,17 +11,19 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "pcm.h")
+MEASURE_HEADER = os.path.join(ROOT, "include", "pcm_measure.h")
 LIB = os.path.join(ROOT, "paper_2605_16154_amd", "libpcm.so")
+MEASURE_LIB = os.path.join(ROOT, "paper_2605_16154_amd", "libpcm_measure.so")
 
 
-def _declared():
-    text = open(HEADER).read()
+def _declared(header=HEADER):
+    text = open(header).read()
     return sorted(set(re.findall(r"^PCM_API\s+[\w\s\*]+?\b((?:pcm|grpo)_\w+)\s*\(", text, flags=re.M)))
 
 
 @pytest.fixture(scope="module")
 def cdll():
-    if not os.path.exists(LIB):
+    if not (os.path.exists(LIB) and os.path.exists(MEASURE_LIB)):
         import __graft_entry__
         __graft_entry__.build()
     return ctypes.CDLL(LIB)
@@ -36,6 +39,17 @@ def test_header_declares_the_four_calls():
 def test_every_declared_symbol_is_exported(cdll):
     for name in _declared():
         assert hasattr(cdll, name), name
+    measure = ctypes.CDLL(MEASURE_LIB)
+    for name in _declared(MEASURE_HEADER):
+        assert hasattr(measure if name == "pcm_measure_mfma_rate" else cdll, name), name
+
+
+def test_training_header_has_no_measurement_exports_and_product_library_no_probe(cdll):
+    # the calls of pcm.h never allocate or synchronise; the probe that does lives in its own library
+    names = _declared()
+    assert not [n for n in names if "measure" in n or "profile" in n]
+    assert not hasattr(cdll, "pcm_measure_mfma_rate")
+    assert "pcm_score_phases_static" in names
 
 
 def test_host_side_queries(cdll):

@@ -151,6 +151,24 @@ def test_phase_absent_from_one_outcome_is_skipped():
     assert np.array_equal(valid, [1, 0]) and C[1] == 0.0
 
 
+def test_phase_ids_beyond_the_last_phase_count_as_the_last():
+    # One rule for input outside the labelling's range, in the score and in the sampler alike: an id >= K is
+    # read as K - 1.  Pinned by relabelling the input by hand and calling the functions on in-range labels.
+    cfg = CONFIGS["cfg1"]
+    ro = make_rollouts(cfg, 2)
+    K = cfg.K - 1                                               # the batch holds ids 0 .. K, one more than announced
+    assert ro["phase"].max() == K
+    relabelled = np.minimum(ro["phase"], K - 1)
+    args = (ro["reward"], ro["n_chunks"], cfg.n_groups, cfg.G, K)
+    C, valid = O.phase_scores(ro["actions"], ro["phase"], *args)
+    C_ref, valid_ref = O.phase_scores(ro["actions"], relabelled, *args)
+    assert np.array_equal(C, C_ref) and np.array_equal(valid, valid_ref)
+    p = np.array([1.0, 0.3, 0.6])
+    got = O.sample_chunks(p, ro["phase"], ro["n_chunks"], None, cfg.B, 5, 1)
+    want = O.sample_chunks(p, relabelled, ro["n_chunks"], None, cfg.B, 5, 1)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+
+
 # ---------------------------------------------------------------- Eq. 7-9 keep probabilities
 
 def _read_golden(path):
