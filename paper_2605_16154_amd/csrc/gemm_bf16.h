@@ -101,21 +101,27 @@ __device__ inline int unswizzle_unit(int phys, int k_low2) {
 }
 
 // Workgroup id -> (tile_m, tile_n), or false if the workgroup has no tile.  Consecutive hardware
-// workgroup ids go to different XCDs, each with its own L2, so ids are first regrouped so that one
-// XCD works on a contiguous range of tiles, then tiles are walked in column-major bands of 8
-// row-tiles to reuse operand panels.  Of the n_wg workgroups launched only tiles_m * tiles_n have a
-// tile (the row dimension may be cut short by a device-side count): the live tiles are dealt out
-// evenly over the XCDs, so that a short batch does not leave some XCDs without work.
+// workgroup ids go to different XCDs (id mod 8), each with its own L2.  The live tiles are numbered
+// in column-major bands of 4 row-tiles, so that 32 consecutive numbers are a block of 4 x 8 tiles
+// (12 operand panels between them); such blocks are dealt to the XCDs in turn.  The 32 workgroups
+// that run together on one XCD then share their panels in that XCD's L2, and the eight XCDs work
+// side by side on the same band at the same time, so that a panel one of them has brought in from
+// HBM is found in the memory-side cache by the others.  (Giving each XCD a contiguous range of tiles
+// instead costs 3 % on the gate/up shape: the XCDs then stream eight different bands through the
+// memory-side cache at once.)  Of the n_wg workgroups launched only tiles_m * tiles_n have a tile
+// (the row dimension may be cut short by a device-side count); only those are numbered, so a short
+// batch still spreads over all XCDs.
 __device__ inline bool tile_of_workgroup(int wg, int n_wg, int tiles_m, int tiles_n, int& tm, int& tn) {
+    (void)n_wg;
+    constexpr int kBlock = 32;                      // tiles per XCD block = workgroups resident on one XCD
     const int n_live = tiles_m * tiles_n;
-    const int per_xcd = (n_live + kNumXcd - 1) / kNumXcd;
-    int logical = wg;
-    if (kNumXcd * per_xcd <= n_wg) {
-        if (wg / kNumXcd >= per_xcd) return false;
-        logical = (wg % kNumXcd) * per_xcd + wg / kNumXcd;
-    }
+    const int xcd = wg % kNumXcd, idx = wg / kNumXcd;
+    const int full = n_live / (kBlock * kNumXcd);   // rounds in which every XCD gets a whole block
+    int logical;
+    if (idx < full * kBlock) logical = ((idx / kBlock) * kNumXcd + xcd) * kBlock + idx % kBlock;
+    else logical = full * kBlock * kNumXcd + (idx - full * kBlock) * kNumXcd + xcd;   // the rest, tile by tile
     if (logical >= n_live) return false;
-    constexpr int kBand = 8;
+    constexpr int kBand = 4;
     const int band_size = kBand * tiles_n;
     const int band = logical / band_size;
     const int first = band * kBand;
@@ -344,23 +350,26 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
             else if (n == 4) read_frag_b(set, rs_b, ks, 3);
             else if (n < 8) read_frag_a(set, rs_a, ks, n - 4);
         };
+        // The 16 MFMAs of a slice walk the 4 x 4 tiles in serpentine order, so that consecutive
+        // instructions always share one operand fragment.
+        auto col = [](int g, int j) { return (g & 1) ? 3 - j : j; };
         auto slice = [&](int set, const LoadCtx& c, uint32_t half, uint32_t rs_a, uint32_t rs_b, int ks, auto hook) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                one_mfma(set, g, 0);
+                one_mfma(set, g, col(g, 0));
                 __builtin_amdgcn_sched_barrier(0);
                 issue_loads(c, half * 4 + g, 1);
                 __builtin_amdgcn_sched_barrier(0);
-                one_mfma(set, g, 1);
+                one_mfma(set, g, col(g, 1));
                 __builtin_amdgcn_sched_barrier(0);
                 if (g < 3) read_next(set ^ 1, rs_a, rs_b, ks, 3 * g);
                 __builtin_amdgcn_sched_barrier(0);
-                one_mfma(set, g, 2);
+                one_mfma(set, g, col(g, 2));
                 __builtin_amdgcn_sched_barrier(0);
                 if (g < 3) read_next(set ^ 1, rs_a, rs_b, ks, 3 * g + 1);
                 else hook(0);
                 __builtin_amdgcn_sched_barrier(0);
-                one_mfma(set, g, 3);
+                one_mfma(set, g, col(g, 3));
                 __builtin_amdgcn_sched_barrier(0);
                 if (g < 3) read_next(set ^ 1, rs_a, rs_b, ks, 3 * g + 2);
                 else hook(1);
