@@ -302,6 +302,12 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
  *              chunk's phase in its trajectory over those kept)
  *   stats_out  device f32 [5] or NULL: as grpo_masked_actor_step (with a per-chunk ratio, entries 0
  *              and 1 use the chunk's ratio for each of its rows), then the mean row entropy
+ * Precision of PCM_RATIO_CHUNK with dtype PCM_BF16: the log-probabilities of a chunk's A rows add up in the
+ * exponent of its ratio, and so would their bf16 errors (about 2e-3 each, 2e-2 for A = 56).  The forward pass
+ * therefore carries a and y as pairs of bf16 values (value + rounding remainder) through the down and the logit
+ * product (twice the multiply-adds of those two products; workspace for the two remainders), which keeps the
+ * gradients within the 2e-2 bound of the per-token form at any A.  That pass exists for PCM_HEAD_AS_WRITTEN only:
+ * PCM_RATIO_CHUNK with PCM_HEAD_COMPOSED and PCM_BF16 returns PCM_EUNSUPPORTED.
  * Errors: PCM_EINVAL also for options == NULL, an unknown normalisation, ratio_level or
  * head_evaluation, NaN coefficients.
  * ------------------------------------------------------------------------------------------ */
@@ -318,6 +324,9 @@ typedef struct {
     int head_evaluation;        /* pcm_head_evaluation */
 } pcm_loss_options;
 
+/* Workspace of grpo_masked_actor_step_ex for these options (the per-chunk ratio needs more than the plain step). */
+PCM_API size_t grpo_masked_actor_step_ex_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V, int dtype,
+                                                 int want_grads, const pcm_loss_options* options);
 PCM_API int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* tokens, const float* logp_old,
                               const float* adv, const int32_t* kept_idx, const int32_t* n_kept,
                               int max_kept_chunks, int T, int N, int A, int d, int ff, int V,

@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
     _sig(L.pcm_sample_chunks_ex, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, sz, vp])
     _sig(L.pcm_importance_weights, i32, [vp, vp, vp, vp, i32, i32, i32, vp, vp])
     _sig(L.grpo_masked_actor_step_workspace_bytes, sz, [i32] * 7)
+    _sig(L.grpo_masked_actor_step_ex_workspace_bytes, sz, [i32] * 7 + [C.POINTER(LossOptions)])
     _sig(L.grpo_masked_actor_step, i32,
          [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, f32, f32, f32,
           vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp])
@@ -286,7 +287,17 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
         grads = [buf("dWg", (d, ff), torch.float32), buf("dWu", (d, ff), torch.float32),
                  buf("dWd", (ff, d), torch.float32), buf("dWo", (d, V), torch.float32)]
     dX = buf("dX", (rows, d), hidden.dtype) if want_dX else None
-    need = grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, want_grads or want_dX)
+    extended = token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None or composed_head
+    opt = None
+    if extended:
+        if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
+            raise PcmError("chunk_weight is shorter than max_kept_chunks")
+        opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
+                          _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head))
+        need = lib().grpo_masked_actor_step_ex_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype,
+                                                               int(want_grads or want_dX), C.byref(opt))
+    else:
+        need = grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, want_grads or want_dX)
     if need == 0:
         raise PcmError("grpo_masked_actor_step: unsupported shape or dtype for this path")
     ws, ws_bytes = _workspace(need, dev)
@@ -297,11 +308,7 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
     tail = (_ptr(loss, torch.float32, "loss"), _ptr(logp, torch.float32, "logp"),
             *[_ptr(g, torch.float32, "dW") for g in grads], _ptr(dX, None, "dX"), _ptr(stats, torch.float32, "stats"),
             ws, ws_bytes, _stream())
-    if token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None or composed_head:
-        if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
-            raise PcmError("chunk_weight is shorter than max_kept_chunks")
-        opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
-                          _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head))
+    if extended:
         rc = lib().grpo_masked_actor_step_ex(*head, C.byref(opt), *tail)
         _check(rc, "grpo_masked_actor_step_ex")
     else:

@@ -124,7 +124,7 @@ __device__ inline LossRow loss_row(float logp, float logp_old, float adv, float 
 // actor_f32.hip / actor_bf16.hip ---------------------------------------------------------------
 size_t actor_f32_workspace_bytes(const ActorShape& sh, bool want_grads);
 int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
-size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads);
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio);
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
 
 }  // namespace pcm

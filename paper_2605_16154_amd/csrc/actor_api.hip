@@ -18,12 +18,24 @@ bool shape_valid(const ActorShape& sh) {
 
 }  // namespace
 
+namespace {
+size_t workspace_need(const ActorShape& sh, int dtype, bool bwd, bool chunk_ratio) {
+    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd, chunk_ratio);
+}
+}  // namespace
+
 extern "C" size_t grpo_masked_actor_step_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V,
                                                          int dtype, int want_grads) {
     ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
     if (!shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
-    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, want_grads != 0)
-                            : actor_bf16_workspace_bytes(sh, want_grads != 0);
+    return workspace_need(sh, dtype, want_grads != 0, false);
+}
+
+extern "C" size_t grpo_masked_actor_step_ex_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V, int dtype,
+                                                            int want_grads, const pcm_loss_options* options) {
+    ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
+    if (!options || !shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
+    return workspace_need(sh, dtype, want_grads != 0, options->ratio_level == PCM_RATIO_CHUNK);
 }
 
 namespace {
@@ -46,7 +58,9 @@ int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_
     if (dtype != PCM_F32 && dtype != PCM_BF16) return PCM_EINVAL;
     if (!shape_supported(sh, dtype)) return PCM_EUNSUPPORTED;
     const bool bwd = n_grad == 4 || dX != nullptr;
-    const size_t need = dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd);
+    // the split-precision forward pass of the per-chunk ratio exists for the evaluation as written only
+    if (dtype == PCM_BF16 && opt.chunk_ratio && composed) return PCM_EUNSUPPORTED;
+    const size_t need = workspace_need(sh, dtype, bwd, opt.chunk_ratio != 0);
     if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
 
     ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, opt,

@@ -97,6 +97,7 @@ __global__ void sum_parts_bf16(const float* parts, int n_parts, size_t n, bf16* 
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
     bf16 *X, *fu, *fv, *a, *y, *dz, *dz_extra;   // fu, fv: SwiGLU derivative factors, then du, dv
+    bf16 *a_lo, *y_lo;                           // per-chunk ratio: rounding remainders of a and y
     bf16* dy;
     bf16 *Wdo, *G;  // composed evaluation: Wd Wo and a^T dz, both [ff, V]
     float* parts;   // partial products of split reductions
@@ -106,7 +107,7 @@ struct Bf16Workspace {
     size_t bytes;
 };
 
-Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
+Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, bool split = true) {
     Carver c(ws);
     Bf16Workspace w{};
     const size_t Mp = (size_t)ceil_div64(sh.rows_max(), kTileM) * kTileM;
@@ -120,6 +121,8 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads) {
     if (bwd) w.fu = c.take<bf16>(Mp * ff);
     if (bwd) w.fv = c.take<bf16>(Mp * ff);
     w.y = c.take<bf16>(Mp * d);
+    if (split) w.a_lo = c.take<bf16>(Mp * ff);
+    if (split) w.y_lo = c.take<bf16>(Mp * d);
     w.dz = c.take<bf16>(Mp * V);
     w.meta.token = c.take<uint8_t>(Mp);
     w.meta.logp_old = c.take<float>(Mp);
@@ -193,14 +196,18 @@ GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int 
 
 }  // namespace
 
-size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads) {
-    return carve(nullptr, sh, want_grads, want_grads).bytes;
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio) {
+    return carve(nullptr, sh, want_grads, want_grads, chunk_ratio).bytes;
 }
 
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s) {
     const bool grads = io.want_grads();
     const bool bwd = grads || io.dX != nullptr;
-    Bf16Workspace w = carve(ws, sh, bwd, grads);
+    // With one ratio per chunk the log-probabilities of a chunk's A rows add up in the exponent, and so do their
+    // errors: the forward pass then carries a and y as pairs of bf16 values (value and rounding remainder) through
+    // the down and the logit product, which brings the error of a log-probability from about 2e-3 down to 1e-5.
+    const bool split = io.opt.chunk_ratio != 0;
+    Bf16Workspace w = carve(ws, sh, bwd, grads, split);
     const int Mp = (int)w.Mp;
     const int d = sh.d, ff = sh.ff, V = sh.V;
     const bf16* Wg = static_cast<const bf16*>(io.Wg);
@@ -225,12 +232,20 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     {
         StageTimer t(ST_GEMM_GATE_UP, s);
         const GemmProblem p = problem(w.X, d, w.WguT, d, Mp, 2 * ff, d, kr, kRowsAreM);
-        if (bwd) launch_gemm(p, EpiSwigluForward<true>{w.fu, w.fv, w.a, ff}, s);
-        else launch_gemm(p, EpiSwigluForward<false>{nullptr, nullptr, w.a, ff}, s);
+        if (split && bwd) launch_gemm(p, EpiSwigluForward<true, true>{w.fu, w.fv, w.a, w.a_lo, ff}, s);
+        else if (split) launch_gemm(p, EpiSwigluForward<false, true>{nullptr, nullptr, w.a, w.a_lo, ff}, s);
+        else if (bwd) launch_gemm(p, EpiSwigluForward<true>{w.fu, w.fv, w.a, nullptr, ff}, s);
+        else launch_gemm(p, EpiSwigluForward<false>{nullptr, nullptr, w.a, nullptr, ff}, s);
     }
     if (!io.composed) {
         StageTimer t(ST_GEMM_DOWN, s);
-        launch_gemm(problem(w.a, ff, w.WdT, ff, Mp, d, ff, kr, kRowsAreM), EpiStoreBf16{w.y, d, Mp}, s);
+        GemmProblem p = problem(w.a, ff, w.WdT, ff, Mp, d, ff, kr, kRowsAreM);
+        if (split) {                                       // y = [a | a_lo] [Wd; Wd], kept as y + y_lo
+            p.A2 = w.a_lo; p.B2 = w.WdT; p.K2 = ff;
+            launch_gemm(p, EpiStoreBf16Split{w.y, w.y_lo, d, Mp}, s);
+        } else {
+            launch_gemm(p, EpiStoreBf16{w.y, d, Mp}, s);
+        }
     }
     {
         StageTimer t(ST_GEMM_LOGITS_LOSS, s);
@@ -238,8 +253,11 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
                           io.opt, bwd ? w.dz : nullptr, w.dz_extra, io.logp_out, w.out};
         if (io.composed)   // z = a W_do, W_do read as [K][rows]
             launch_gemm<kRowsByK, kKByRows>(problem(w.a, ff, w.Wdo, V, Mp, V, ff, kr, kRowsAreM), epi, s);
-        else
-            launch_gemm(problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM), epi, s);
+        else {
+            GemmProblem p = problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM);
+            if (split) { p.A2 = w.y_lo; p.B2 = w.WoT; p.K2 = d; }   // z = [y | y_lo] [Wo; Wo]
+            launch_gemm(p, epi, s);
+        }
     }
     if (io.opt.chunk_ratio) {
         rc = launch_chunk_ratio(sh, io, w.meta, w.out, Mp, s);

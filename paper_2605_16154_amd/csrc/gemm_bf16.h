@@ -523,6 +523,50 @@ struct EpiStoreBf16 {
     }
 };
 
+// C (row-major) = acc as the sum of two bf16 matrices: hi = bf16(acc), lo = bf16(acc - hi), which together
+// carry 16 bits of significand.  A following product that reads [hi | lo] as two reduction segments against the
+// same second operand sees the value to about 2^-17 instead of 2^-9.  Rows at and beyond row_limit are not written.
+struct EpiStoreBf16Split {
+    bf16 *hi, *lo;
+    int64_t ldc;
+    int row_limit;
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        constexpr int kStride = 520;                       // [hi 128 | lo 128] bf16 + 8 bytes
+        char* st = wave_stage(tc, lds);
+        const int col_base = tc.n0 + tc.wn * 128;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {             // 64 rows per pass
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii) {
+                const int i = half * 2 + ii;
+                char* row = st + (ii * 32 + (tc.lane & 31)) * kStride;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        float r[4];
+                        bf16x4 h;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float x = acc[i][j][4 * q + t];
+                            h[t] = (__bf16)x;
+                            r[t] = x - (float)h[t];
+                        }
+                        char* at = row + (j * 32 + 8 * q + 4 * (tc.lane >> 5)) * 2;
+                        *reinterpret_cast<bf16x4*>(at) = h;
+                        *reinterpret_cast<bf16x4*>(at + 256) = to_bf16x4(r[0], r[1], r[2], r[3]);
+                    }
+            }
+            __builtin_amdgcn_wave_barrier();
+            const int row_base = tc.m0 + tc.wm * 128 + half * 64;
+            const int64_t at = (int64_t)row_base * ldc + col_base;
+            copy_rows_out<64, 256>(st, kStride, reinterpret_cast<char*>(hi + at), ldc * 2, row_limit - row_base, tc.lane);
+            copy_rows_out<64, 256>(st + 256, kStride, reinterpret_cast<char*>(lo + at), ldc * 2, row_limit - row_base, tc.lane);
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+};
+
 // C (fp32, row-major) = acc.  With a split reduction, part s goes to C + s * split_stride (its own
 // M x N matrix; the caller sums the parts), so no atomics are needed and the sum is reproducible.
 struct EpiStoreF32 {
@@ -557,12 +601,16 @@ struct EpiStoreF32 {
 // are u (gate) and j = 2, 3 the matching v (up).  Writes a = silu(u) * v (bf16, [M, ff]) and, for
 // a backward pass to come, the two factors it will need, computed here where the sigmoid is at
 // hand: fu = v * silu'(u) (so du = da * fu) and fv = silu(u) (so dv = da * fv).
-template <bool kKeepFactors>
+// With kKeepLow the rounding remainder of a is written as well (a_lo = bf16(a - bf16(a))), for products
+// that need the activation to more than bf16 precision (they read [a | a_lo] as two reduction segments).
+template <bool kKeepFactors, bool kKeepLow = false>
 struct EpiSwigluForward {
-    bf16 *fu, *fv, *a;
+    bf16 *fu, *fv, *a, *a_lo;
     int64_t ld;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
-        constexpr int kStride = kKeepFactors ? 392 : 136;  // [a 64 | fu 64 | fv 64] bf16 + 8 bytes
+        // staged row: [a 64 | fu 64 | fv 64 | a_lo 64] bf16 (the parts that are kept) + 8 bytes
+        constexpr int kLowAt = kKeepFactors ? 384 : 128;
+        constexpr int kStride = 8 + 128 * (1 + (kKeepFactors ? 2 : 0) + (kKeepLow ? 1 : 0));
         char* st = wave_stage(tc, lds);
         const int col_base = ((tc.n0 + tc.wn * 128) / 128) * 64;
 #pragma unroll
@@ -579,18 +627,22 @@ struct EpiSwigluForward {
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const float x = acc[i][j][4 * q + t], y = acc[i][j + 2][4 * q + t];
-                            const float sg = fast_sigmoid(x);
+                            const float sg = kKeepLow ? 1.f / (1.f + expf(-x)) : fast_sigmoid(x);   // full accuracy where it is kept
                             fvv[t] = x * sg;
                             av[t] = fvv[t] * y;
                             const float ys = y * sg;
                             fuv[t] = __builtin_fmaf(ys, x - fvv[t], ys);     // y sg (1 + x (1 - sg))
                         }
                         char* at = row + (j * 32 + 8 * q + 4 * (tc.lane >> 5)) * 2;
-                        *reinterpret_cast<bf16x4*>(at) = to_bf16x4(av[0], av[1], av[2], av[3]);
+                        const bf16x4 a4 = to_bf16x4(av[0], av[1], av[2], av[3]);
+                        *reinterpret_cast<bf16x4*>(at) = a4;
                         if (kKeepFactors) {
                             *reinterpret_cast<bf16x4*>(at + 128) = to_bf16x4(fuv[0], fuv[1], fuv[2], fuv[3]);
                             *reinterpret_cast<bf16x4*>(at + 256) = to_bf16x4(fvv[0], fvv[1], fvv[2], fvv[3]);
                         }
+                        if (kKeepLow)
+                            *reinterpret_cast<bf16x4*>(at + kLowAt) = to_bf16x4(av[0] - (float)a4[0], av[1] - (float)a4[1],
+                                                                             av[2] - (float)a4[2], av[3] - (float)a4[3]);
                     }
             }
             __builtin_amdgcn_wave_barrier();
@@ -601,6 +653,7 @@ struct EpiSwigluForward {
                 copy_rows_out<64, 128>(st + 128, kStride, reinterpret_cast<char*>(fu + at), ld * 2, 64, tc.lane);
                 copy_rows_out<64, 128>(st + 256, kStride, reinterpret_cast<char*>(fv + at), ld * 2, 64, tc.lane);
             }
+            if (kKeepLow) copy_rows_out<64, 128>(st + kLowAt, kStride, reinterpret_cast<char*>(a_lo + at), ld * 2, 64, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
