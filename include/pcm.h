@@ -147,7 +147,7 @@ PCM_API int pcm_score_phases(const float* actions, const uint8_t* phase, const u
  * All calls on one GPU share that GPU's array: two calls that may overlap (different streams
  * without an ordering between them, or different host threads) race; order them.
  * ------------------------------------------------------------------------------------------ */
-#define PCM_SCORE_STATIC_MAX_BYTES (4u << 20)
+#define PCM_SCORE_STATIC_MAX_BYTES (4u << 20)   /* 4 MiB */
 PCM_API int pcm_score_phases_static(const float* actions, const uint8_t* phase, const uint8_t* reward,
                      const int32_t* n_chunks, int n_groups, int G, int N, int A, int K,
                      double adv_eps, double* C_out, uint8_t* valid_out, float* adv_out,

@@ -1,13 +1,16 @@
 // pcm_sample_chunks: fixed-budget weighted sampling without replacement (Eq. 10) and the
 // compaction that expresses physical shrinking (Sec. 4.5; Algorithm 1, inner loop).
 //
-// Two launches:
-//   scan     per-trajectory kept counts min(B, N_i) (0 if inactive) are known before any draw;
-//            one workgroup turns them into exclusive offsets with an LDS prefix scan
-//   compact  one wavefront per trajectory: integer weights in LDS, lanes own contiguous runs of
-//            chunk slots, an inclusive wave scan of lane sums is kept up to date across the
-//            min(B, N_i) successive draws, then kept slots are written in ascending order at the
-//            trajectory's offset (wave prefix of per-lane popcounts)
+// One launch (two for very many trajectories and for the top-phase selector):
+//   compact  one wavefront per trajectory.  The per-trajectory kept counts min(B, N_i) (0 if inactive)
+//            are known before any draw, so every workgroup adds up the counts of the trajectories
+//            before its own to find where its output starts (a few KB of reads; for more than
+//            kFusedScanMax trajectories, and for the top-phase selector whose counts need a pass over
+//            the phases, a separate one-workgroup scan kernel writes the offsets first).  Lanes own
+//            contiguous runs of chunk slots with their integer weights in registers (in LDS when a
+//            lane owns more than eight), an inclusive wave scan of lane sums is kept up to date
+//            across the min(B, N_i) successive draws, then kept slots are written in ascending order
+//            at the trajectory's offset (wave prefix of per-lane popcounts)
 //
 // All arithmetic after the weight quantisation is integer, and the random bits depend only on
 // (seed, step, trajectory, round), so the kept set is a pure function of the inputs.
@@ -18,6 +21,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / kWave;
+constexpr int kFusedScanMax = 4096;   // trajectories up to which every workgroup sums the earlier counts itself
 
 // Philox-4x32, 10 rounds (Salmon et al., SC'11): multipliers and Weyl key increments as published.
 constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
@@ -106,13 +110,29 @@ __global__ __launch_bounds__(kThreads) void sample_scan(const double* __restrict
 }
 
 // LDS: K quantised phase weights, then one N-entry weight array per wavefront.
+// kRegs > 0: a lane owns at most kRegs chunk slots and keeps their weights in registers; kRegs == 0: any
+// N, weights in LDS.  kFusedScan: the workgroup computes its own output offset (and writes kept_offsets,
+// n_kept) instead of reading offsets written by sample_scan.
+template <int kRegs, bool kFusedScan>
 __global__ __launch_bounds__(kThreads) void sample_compact(
     const double* __restrict__ keep_probs, const uint8_t* __restrict__ phase,
     const int32_t* __restrict__ n_chunks, const uint8_t* __restrict__ active, int T, int N, int K, int B,
-    int selector, uint64_t seed, uint64_t step, const int32_t* __restrict__ kept_offsets, int32_t* kept_idx) {
+    int selector, uint64_t seed, uint64_t step, int32_t* kept_offsets, int32_t* n_kept, int32_t* kept_idx) {
     extern __shared__ uint32_t lds[];
     uint32_t* qtab = lds;
     const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
+    // This lane's phase bytes are requested first (their address depends on the launch geometry only), so that they
+    // travel while the weights table and the output offset are worked out.
+    uint8_t my_phase[kRegs > 0 ? kRegs : 1];
+    if (kRegs > 0) {
+        const int i_early = blockIdx.x * (blockDim.x / kWave) + wv;
+        const int per_lane_early = (N + kWave - 1) / kWave;
+#pragma unroll
+        for (int j = 0; j < kRegs; ++j) {
+            const int k = lane * per_lane_early + j;
+            my_phase[j] = (i_early < T && j < per_lane_early && k < N) ? phase[(size_t)i_early * N + k] : 0;
+        }
+    }
     uint32_t* w = lds + PCM_MAX_PHASES + (size_t)wv * (N + 2 * PCM_MAX_PHASES);
     int* n_in_phase = reinterpret_cast<int*>(w + N);      // stratified selector: chunks per phase, then budgets
     int* budget = n_in_phase + PCM_MAX_PHASES;
@@ -133,9 +153,39 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
     __syncthreads();
 
     const int i = blockIdx.x * waves_per_block + wv;
-    if (i >= T) return;                       // no barrier below this point
-    const int m = kept_count(n_chunks, active, phase, i, N, K, B, only);
-    if (m == 0) return;
+    const int m = i < T ? kept_count(n_chunks, active, phase, i, N, K, B, only) : 0;
+    int offset = 0;
+    if (kFusedScan) {
+        // kept chunks of all trajectories before this workgroup's first, then of the earlier wavefronts
+        __shared__ int part[kWavesPerBlock + 1][kWavesPerBlock];
+        const int i0 = blockIdx.x * waves_per_block;
+        int before = 0;
+        if (n_chunks == nullptr && active == nullptr) {
+            before = i0 * (N < B ? N : B);                                   // every trajectory keeps min(B, N)
+        } else {
+            int mine = 0;
+            for (int j = tid; j < i0; j += blockDim.x) mine += kept_count(n_chunks, active, phase, j, N, K, B, -1);
+#pragma unroll
+            for (int off = kWave / 2; off > 0; off >>= 1) mine += __shfl_xor(mine, off, kWave);
+            if (lane == 0) part[0][wv] = mine;
+        }
+        if (lane == 0) part[1][wv] = m;
+        __syncthreads();
+        if (!(n_chunks == nullptr && active == nullptr))
+            for (int q = 0; q < waves_per_block; ++q) before += part[0][q];
+        for (int q = 0; q < wv; ++q) before += part[1][q];
+        offset = before;
+        if (i < T && lane == 0) {
+            kept_offsets[i] = offset;
+            if (i == T - 1) {
+                kept_offsets[T] = offset + m;
+                *n_kept = offset + m;
+            }
+        }
+    } else if (i < T) {
+        offset = kept_offsets[i];
+    }
+    if (i >= T || m == 0) return;             // no workgroup barrier below this point
     int Ni = n_chunks ? n_chunks[i] : N;
     Ni = Ni > N ? N : Ni;
 
@@ -203,6 +253,7 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
     }
 
     uint64_t mask = 0;
+    uint32_t wreg[kRegs > 0 ? kRegs : 1];     // this lane's weights (kRegs > 0)
     const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
     const uint32_t s0 = (uint32_t)step, s1 = (uint32_t)(step >> 32);
     uint32_t x_lo = 0, x_hi = 0;              // lane l holds the random bits of round (r & ~63) + l
@@ -211,26 +262,37 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
         const int draws = selector == PCM_SELECT_STRATIFIED ? budget[pass] : m;
         if (draws == 0) continue;
         uint32_t lane_sum = 0;
-        for (int j = 0; j < per_lane; ++j) {
-            const int k = k_lo + j;
-            uint32_t wk = 0;
-            if (k < Ni) {
-                const int c = phase_of(k);
-                wk = selector == PCM_SELECT_STRATIFIED ? (c == pass ? 1u : 0u) : qtab[c];
+        auto weight_of_phase = [&](int k, int c) -> uint32_t {
+            if (k >= Ni) return 0u;
+            c = c < K ? c : K - 1;
+            return selector == PCM_SELECT_STRATIFIED ? (c == pass ? 1u : 0u) : qtab[c];
+        };
+        auto weight_of = [&](int k) -> uint32_t { return k < Ni ? weight_of_phase(k, ph[k]) : 0u; };
+        if (kRegs > 0) {
+#pragma unroll
+            for (int j = 0; j < kRegs; ++j) {
+                wreg[j] = j < per_lane ? weight_of_phase(k_lo + j, my_phase[j]) : 0u;
+                lane_sum += wreg[j];
             }
-            if (k < N) w[k] = wk;
-            lane_sum += wk;
+        } else {
+            for (int j = 0; j < per_lane; ++j) {
+                const int k = k_lo + j;
+                const uint32_t wk = weight_of(k);
+                if (k < N) w[k] = wk;
+                lane_sum += wk;
+            }
         }
         uint32_t incl = (uint32_t)wave_inclusive_scan((int)lane_sum, lane);
-        uint32_t W_rem = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+        uint32_t W_rem = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
         for (int d = 0; d < draws; ++d, ++r) {
             if ((r & (kWave - 1)) == 0) {     // the draws of the next 64 rounds, one per lane, in parallel
                 const uint64_t mine = philox_bits((uint32_t)i, (uint32_t)((r & ~(kWave - 1)) + lane), s0, s1, k0, k1);
                 x_lo = (uint32_t)mine;
                 x_hi = (uint32_t)(mine >> 32);
             }
-            const uint64_t x = (uint64_t)(uint32_t)__shfl((int)x_lo, r & (kWave - 1), kWave) |
-                               ((uint64_t)(uint32_t)__shfl((int)x_hi, r & (kWave - 1), kWave) << 32);
+            const int src = __builtin_amdgcn_readfirstlane(r & (kWave - 1));      // wave-uniform: a lane read, no shuffle
+            const uint64_t x = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)x_lo, src) |
+                               ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)x_hi, src) << 32);
             const uint32_t t = (uint32_t)__umul64hi(x, (uint64_t)W_rem);   // in [0, W_rem)
             const uint64_t over = __ballot(incl > t);
             if (over == 0) break;             // cannot happen while W_rem > 0; keeps the loop total
@@ -238,28 +300,41 @@ __global__ __launch_bounds__(kThreads) void sample_compact(
             uint32_t picked_w = 0;
             if (lane == L) {
                 uint32_t run = incl - lane_sum;
-                for (int j = 0; j < per_lane; ++j) {
-                    const int k = k_lo + j;
-                    if (k >= N) break;
-                    const uint32_t wk = w[k];
-                    run += wk;
-                    if (wk > 0 && run > t) {
-                        picked_w = wk;
-                        w[k] = 0;
-                        mask |= (uint64_t)1 << j;
-                        break;
+                if (kRegs > 0) {
+#pragma unroll
+                    for (int j = 0; j < kRegs; ++j) {
+                        const uint32_t wk = wreg[j];
+                        run += wk;
+                        if (picked_w == 0 && wk > 0 && run > t) {   // the first slot whose running weight exceeds t
+                            picked_w = wk;
+                            wreg[j] = 0;
+                            mask |= (uint64_t)1 << j;
+                        }
+                    }
+                } else {
+                    for (int j = 0; j < per_lane; ++j) {
+                        const int k = k_lo + j;
+                        if (k >= N) break;
+                        const uint32_t wk = w[k];
+                        run += wk;
+                        if (wk > 0 && run > t) {
+                            picked_w = wk;
+                            w[k] = 0;
+                            mask |= (uint64_t)1 << j;
+                            break;
+                        }
                     }
                 }
                 lane_sum -= picked_w;
             }
-            picked_w = (uint32_t)__shfl((int)picked_w, L, kWave);
+            picked_w = (uint32_t)__builtin_amdgcn_readlane((int)picked_w, __builtin_amdgcn_readfirstlane(L));
             if (lane >= L) incl -= picked_w;
             W_rem -= picked_w;
         }
     }
 
     const int mine = __popcll(mask);
-    int pos = kept_offsets[i] + wave_inclusive_scan(mine, lane) - mine;
+    int pos = offset + wave_inclusive_scan(mine, lane) - mine;
     while (mask) {
         const int j = __ffsll((long long)mask) - 1;
         mask &= mask - 1;
@@ -293,7 +368,11 @@ int run_sample(const double* keep_probs, const uint8_t* phase, const int32_t* n_
         selector != PCM_SELECT_STRATIFIED)
         return PCM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    {
+    // Every workgroup can find its own output offset from the counts min(B, N_i) of the trajectories before it;
+    // beyond kFusedScanMax trajectories that is too much repeated reading, and the top-phase selector's counts
+    // need a pass over the phases: then one workgroup scans the counts first.
+    const bool fused = T <= kFusedScanMax && selector != PCM_SELECT_TOP_PHASE;
+    if (!fused) {
         StageTimer t(ST_SAMPLE_SCAN, s);
         sample_scan<<<1, kThreads, 0, s>>>(keep_probs, phase, n_chunks, active, T, N, K, B, selector, kept_offsets,
                                            n_kept);
@@ -303,8 +382,21 @@ int run_sample(const double* keep_probs, const uint8_t* phase, const int32_t* n_
         // one weight array per wavefront must fit the 64 KB a workgroup may take by default
         const int waves = N > 2048 ? 2 : kWavesPerBlock;
         const size_t lds_bytes = (PCM_MAX_PHASES + (size_t)waves * (N + 2 * PCM_MAX_PHASES)) * sizeof(uint32_t);
-        sample_compact<<<ceil_div(T, waves), waves * kWave, lds_bytes, s>>>(
-            keep_probs, phase, n_chunks, active, T, N, K, B, selector, seed, step, kept_offsets, kept_idx);
+        const int per_lane = ceil_div(N, kWave);
+        const dim3 grid(ceil_div(T, waves)), block(waves * kWave);
+#define PCM_SAMPLE(REGS, FUSED)                                                                                       \
+    sample_compact<REGS, FUSED><<<grid, block, lds_bytes, s>>>(keep_probs, phase, n_chunks, active, T, N, K, B, selector, \
+                                                              seed, step, kept_offsets, n_kept, kept_idx)
+        if (fused) {
+            if (per_lane <= 2) PCM_SAMPLE(2, true);
+            else if (per_lane <= 4) PCM_SAMPLE(4, true);
+            else if (per_lane <= 8) PCM_SAMPLE(8, true);
+            else PCM_SAMPLE(0, true);
+        } else {
+            if (per_lane <= 4) PCM_SAMPLE(4, false);
+            else PCM_SAMPLE(0, false);
+        }
+#undef PCM_SAMPLE
     }
     return launch_status();
 }
