@@ -232,6 +232,22 @@ PCM_API int pcm_importance_weights(const uint8_t* phase, const int32_t* n_chunks
                            void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * pcm_kept_phase_counts -- the realised allocation of the budget over the phases (Sec. 5.2, the
+ * per-phase view of which chunks were kept): a statistic for logging, not a step of the update.
+ *
+ *   phase, n_chunks, active   device, as given to pcm_sample_chunks (n_chunks, active may be NULL)
+ *   kept_idx, n_kept          device, as written by pcm_sample_chunks; *n_kept is clamped to
+ *                             [0, max_kept_chunks], ids outside [0, T*N) are not counted
+ *   kept_per_phase    device i32 [K]: kept chunks of each phase (ids >= K count as K-1)
+ *   chunks_per_phase  device i32 [K] or NULL: chunk slots the sampler could have kept (slots
+ *                     k < n_chunks[i] of active trajectories) of each phase
+ * One workgroup; meant for batches of up to a few million chunk slots.
+ * ------------------------------------------------------------------------------------------ */
+PCM_API int pcm_kept_phase_counts(const uint8_t* phase, const int32_t* n_chunks, const uint8_t* active,
+                          const int32_t* kept_idx, const int32_t* n_kept, int max_kept_chunks, int T, int N,
+                          int K, int32_t* kept_per_phase, int32_t* chunks_per_phase, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * grpo_masked_actor_step -- Eq. 11 (Eq. 2 when kept_idx lists every chunk), with the PPO
  * clipping the paper leaves out of Eq. 2 for clarity (thresholds as in App. D).
  *
@@ -302,6 +318,12 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
  *              chunk's phase in its trajectory over those kept)
  *   stats_out  device f32 [5] or NULL: as grpo_masked_actor_step (with a per-chunk ratio, entries 0
  *              and 1 use the chunk's ratio for each of its rows), then the mean row entropy
+ * Row panels (dtype PCM_BF16, PCM_HEAD_AS_WRITTEN; grpo_masked_actor_step does the same with the default
+ * height): a batch longer than a panel and a quarter is worked through in panels of the largest common multiple
+ * of 256 and A that does not exceed the target height: gather, forward, loss and backward run panel by panel
+ * over the same activation buffers, every panel after the first adds its weight gradients to the earlier ones'
+ * (fp32), the loss is reduced once at the end.  The workspace is bounded by the panel, not by the batch.
+ *
  * Precision of PCM_RATIO_CHUNK with dtype PCM_BF16: the log-probabilities of a chunk's A rows add up in the
  * exponent of its ratio, and so would their bf16 errors (about 2e-3 each, 2e-2 for A = 56).  The forward pass
  * therefore carries a and y as pairs of bf16 values (value + rounding remainder) through the down and the logit
@@ -309,7 +331,7 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
  * gradients within the 2e-2 bound of the per-token form at any A.  That pass exists for PCM_HEAD_AS_WRITTEN only:
  * PCM_RATIO_CHUNK with PCM_HEAD_COMPOSED and PCM_BF16 returns PCM_EUNSUPPORTED.
  * Errors: PCM_EINVAL also for options == NULL, an unknown normalisation, ratio_level or
- * head_evaluation, NaN coefficients.
+ * head_evaluation, NaN coefficients, negative panel_rows.
  * ------------------------------------------------------------------------------------------ */
 typedef enum { PCM_NORM_SCALE = 0, PCM_NORM_TOKEN_MEAN = 1 } pcm_normalisation;
 typedef enum { PCM_RATIO_TOKEN = 0, PCM_RATIO_CHUNK = 1 } pcm_ratio_level;
@@ -322,6 +344,8 @@ typedef struct {
     int ratio_level;            /* pcm_ratio_level */
     const float* chunk_weight;  /* device, or NULL */
     int head_evaluation;        /* pcm_head_evaluation */
+    int panel_rows;             /* dtype PCM_BF16: target height of the row panels a long batch is worked through in;
+                                   0 = the library's choice (57,344 rows).  See "Row panels" above. */
 } pcm_loss_options;
 
 /* Workspace of grpo_masked_actor_step_ex for these options (the per-chunk ratio needs more than the plain step). */

@@ -18,6 +18,8 @@ Parity status of each function (what pins it is in tests/test_oracle_*.py):
   sample_chunks       pinned: brute-force Plackett-Luce enumeration on tiny inputs
   compact / sample    pinned: set properties (|K_i| = min(B, N_i), ascending, unique)
   label_phases        pinned: hand-labelled gripper traces, one per rule and per overlap of windows
+  kept_phase_counts   pinned: hand example, totals (kept sums to the kept count, eligible to the valid
+                      slots of active trajectories), agreement with a histogram of the kept chunks' labels
   selectors, weights  pinned: uniform inclusion frequencies of "random", phase purity and counts of
                       "top_phase", sum of N_c / b_c over a phase's kept chunks = N_c, hand example
   actor_step          pinned: head forward against explicit loops over the definition, log-softmax
@@ -457,6 +459,26 @@ def importance_weights(phase, n_chunks, kept_idx, K):
         b = sum(1 for kk in kept_here if min(int(phase[i, kk]), K - 1) == c)
         out[j] = np.float32(len(in_phase)) / np.float32(b)
     return out
+
+
+def kept_phase_counts(phase, n_chunks, active, kept_idx, K):
+    """Realised allocation of the budget over the phases (Sec. 5.2, the per-phase view of which chunks
+    the sampler kept over training): for every phase the number of kept chunks, and the number of
+    chunks the sampler could have kept (valid chunk slots of active trajectories).  Phase ids >= K
+    count as K - 1, as everywhere.  Returns (kept i32[K], eligible i32[K])."""
+    phase = np.asarray(phase)
+    T, N = phase.shape
+    n_chunks = np.full(T, N, dtype=np.int64) if n_chunks is None else np.asarray(n_chunks, dtype=np.int64)
+    kept = np.zeros(K, dtype=np.int32)
+    eligible = np.zeros(K, dtype=np.int32)
+    for g in np.asarray(kept_idx, dtype=np.int64):
+        kept[min(int(phase[int(g) // N, int(g) % N]), K - 1)] += 1
+    for i in range(T):
+        if active is not None and not active[i]:
+            continue
+        for k in range(min(max(int(n_chunks[i]), 0), N)):
+            eligible[min(int(phase[i, k]), K - 1)] += 1
+    return kept, eligible
 
 
 # ----------------------------------------------------------------------------------------

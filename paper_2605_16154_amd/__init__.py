@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     library_path,
     pcm_adamw_clip_step,
     pcm_importance_weights,
+    pcm_kept_phase_counts,
     pcm_label_phases,
     pcm_measure_mfma_rate,
     pcm_profile_collect,

@@ -26,6 +26,7 @@ struct LossOptions {
     int token_mean;              // scale = loss_scale / (kept rows) instead of loss_scale
     int chunk_ratio;             // one ratio (and one clipped term) per chunk instead of per token
     const float* chunk_weight;   // device [max_chunks] or null: multiplies the terms of a chunk
+    int panel_rows;              // bf16 path: target height of the row panels (0 = the library's choice)
 };
 
 struct ActorIO {
@@ -67,7 +68,10 @@ struct RowOut {
 // gather.hip ---------------------------------------------------------------------------------
 // Copies the kept chunks' hidden rows into X [rows_pad, d] (rows at and beyond n_kept*A are
 // zero-filled) and fills the row metadata.  elem_bytes is 2 (bf16) or 4 (fp32).
-int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t rows_pad,
+// With row_offset > 0 the rows are those of a panel of the batch that starts at that row: X and the metadata
+// arrays are the panel's own, `rows_pad` its height.  The same holds for the two per-chunk-ratio launches below
+// (row_offset a multiple of A, so no chunk straddles two panels).
+int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t row_offset, int64_t rows_pad,
                   RowMeta meta, hipStream_t s);
 
 // Sums the per-row loss terms and statistics in a fixed order (one workgroup, fp64 accumulators).
@@ -75,13 +79,13 @@ int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipS
 
 // Per-chunk ratio: from the per-row dlogp, one ratio, one clipped term and one dz factor per kept chunk
 // (written to every row of the chunk; the term only to its first row).
-int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t rows_pad,
-                       hipStream_t s);
+int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t row_offset,
+                       int64_t rows_pad, hipStream_t s);
 
 // dz[r, :] = coef[r] * dz[r, :] (+ extra[r, :] if extra is given) for the live rows r (V columns each);
 // elem_bytes is 2 (bf16) or 4 (fp32).
 int launch_scale_rows(const ActorShape& sh, const ActorIO& io, void* dz, const void* extra, const float* coef,
-                      int64_t rows_pad, int elem_bytes, hipStream_t s);
+                      int64_t row_offset, int64_t rows_pad, int elem_bytes, hipStream_t s);
 
 // Number of live rows from the device-side kept count.
 __device__ inline int64_t live_rows(const int32_t* n_kept, int max_chunks, int A) {
@@ -124,7 +128,7 @@ __device__ inline LossRow loss_row(float logp, float logp_old, float adv, float 
 // actor_f32.hip / actor_bf16.hip ---------------------------------------------------------------
 size_t actor_f32_workspace_bytes(const ActorShape& sh, bool want_grads);
 int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
-size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio);
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio, bool composed, int panel_target);
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
 
 }  // namespace pcm

@@ -19,8 +19,9 @@ bool shape_valid(const ActorShape& sh) {
 }  // namespace
 
 namespace {
-size_t workspace_need(const ActorShape& sh, int dtype, bool bwd, bool chunk_ratio) {
-    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd, chunk_ratio);
+size_t workspace_need(const ActorShape& sh, int dtype, bool bwd, bool chunk_ratio, bool composed, int panel_rows) {
+    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd)
+                            : actor_bf16_workspace_bytes(sh, bwd, chunk_ratio, composed, panel_rows);
 }
 }  // namespace
 
@@ -28,14 +29,15 @@ extern "C" size_t grpo_masked_actor_step_workspace_bytes(int max_kept_chunks, in
                                                          int dtype, int want_grads) {
     ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
     if (!shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
-    return workspace_need(sh, dtype, want_grads != 0, false);
+    return workspace_need(sh, dtype, want_grads != 0, false, false, 0);
 }
 
 extern "C" size_t grpo_masked_actor_step_ex_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V, int dtype,
                                                             int want_grads, const pcm_loss_options* options) {
     ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
     if (!options || !shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
-    return workspace_need(sh, dtype, want_grads != 0, options->ratio_level == PCM_RATIO_CHUNK);
+    return workspace_need(sh, dtype, want_grads != 0, options->ratio_level == PCM_RATIO_CHUNK,
+                          options->head_evaluation == PCM_HEAD_COMPOSED, options->panel_rows);
 }
 
 namespace {
@@ -53,14 +55,14 @@ int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_
     ActorShape sh{max_kept_chunks, T, N, A, d, ff, V};
     if (!shape_valid(sh) || T < 1 || N < 1 || (int64_t)T * N >= (int64_t)1 << 31) return PCM_EINVAL;
     if (!(opt.eps_low >= 0.f) || !(opt.eps_high >= 0.f) || opt.loss_scale != opt.loss_scale ||
-        opt.entropy_coef != opt.entropy_coef)
+        opt.entropy_coef != opt.entropy_coef || opt.panel_rows < 0)
         return PCM_EINVAL;
     if (dtype != PCM_F32 && dtype != PCM_BF16) return PCM_EINVAL;
     if (!shape_supported(sh, dtype)) return PCM_EUNSUPPORTED;
     const bool bwd = n_grad == 4 || dX != nullptr;
     // the split-precision forward pass of the per-chunk ratio exists for the evaluation as written only
     if (dtype == PCM_BF16 && opt.chunk_ratio && composed) return PCM_EUNSUPPORTED;
-    const size_t need = workspace_need(sh, dtype, bwd, opt.chunk_ratio != 0);
+    const size_t need = workspace_need(sh, dtype, bwd, opt.chunk_ratio != 0, composed, opt.panel_rows);
     if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
 
     ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, opt,
@@ -78,7 +80,7 @@ extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens,
                                       float eps_low, float eps_high, float loss_scale, float* loss_out,
                                       float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
                                       float* stats_out, void* workspace, size_t workspace_bytes, void* stream) {
-    const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr};
+    const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0};
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
                           Wu, Wd, Wo, opt, false, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 4, workspace,
                           workspace_bytes, stream);
@@ -98,7 +100,7 @@ extern "C" int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* toke
         return PCM_EINVAL;
     const LossOptions opt{options->eps_low, options->eps_high, options->loss_scale, options->entropy_coef,
                           options->normalisation == PCM_NORM_TOKEN_MEAN, options->ratio_level == PCM_RATIO_CHUNK,
-                          options->chunk_weight};
+                          options->chunk_weight, options->panel_rows};
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
                           Wu, Wd, Wo, opt, options->head_evaluation == PCM_HEAD_COMPOSED, loss_out, logp_out, dWg, dWu,
                           dWd, dWo, dX, stats_out, 5, workspace, workspace_bytes, stream);

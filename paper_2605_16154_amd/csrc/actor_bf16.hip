@@ -19,6 +19,13 @@
 //
 // Rows are padded to a multiple of 256; padding rows are zero with zero advantage, so they
 // contribute nothing to any output.
+//
+// A long batch is worked through in row panels (kPanelRows rows, a multiple of both the tile height
+// and the chunk length): gather, forward, loss and backward run panel by panel over the same
+// activation buffers, the weight gradients of every panel after the first are added to what the
+// earlier ones left, and the per-row loss terms are reduced once at the end.  The workspace is then
+// bounded by the panel (about 5 GB at d = 4096, ff = 11008) instead of growing with the batch, and
+// a panel's activations are still in the memory-side cache when its backward pass reads them.
 #include "gemm_bf16.h"
 
 namespace pcm {
@@ -94,36 +101,55 @@ __global__ void sum_parts_bf16(const float* parts, int n_parts, size_t n, bf16* 
     }
 }
 
+constexpr int64_t kPanelRows = 57344;   // target height of a row panel (224 row tiles)
+
+// Height of the row panels a batch of `sh.rows_max()` rows is worked through in: the whole (padded) batch if it
+// is at most a panel and a quarter, or if the head is evaluated in composed form; otherwise the largest common
+// multiple of the tile height and the chunk length that does not exceed the target (the caller's, else kPanelRows).
+int64_t panel_rows(const ActorShape& sh, bool composed, int target) {
+    const int64_t Mp = ceil_div64(sh.rows_max(), kTileM) * kTileM;
+    if (composed) return Mp;
+    const int64_t want = target > 0 ? target : kPanelRows;
+    int64_t x = kTileM, y = sh.A;
+    while (y != 0) { const int64_t t = x % y; x = y; y = t; }             // gcd
+    const int64_t unit = (int64_t)kTileM / x * sh.A;                        // lcm(256, A)
+    const int64_t rp = unit * (want / unit > 0 ? want / unit : 1);
+    return Mp <= rp + rp / 4 ? Mp : rp;
+}
+
 struct Bf16Workspace {
     bf16 *WguT, *WdT, *WoT;
-    bf16 *X, *fu, *fv, *a, *y, *dz, *dz_extra;   // fu, fv: SwiGLU derivative factors, then du, dv
+    bf16 *X, *fu, *fv, *a, *y, *dz, *dz_extra;   // one panel each; fu, fv: SwiGLU derivative factors, then du, dv
     bf16 *a_lo, *y_lo;                           // per-chunk ratio: rounding remainders of a and y
     bf16* dy;
     bf16 *Wdo, *G;  // composed evaluation: Wd Wo and a^T dz, both [ff, V]
     float* parts;   // partial products of split reductions
-    RowMeta meta;
-    RowOut out;
-    int64_t Mp;
+    RowMeta meta;   // whole batch
+    RowOut out;     // whole batch
+    int64_t Mp;     // padded rows of the batch
+    int64_t Rp;     // rows of a panel
     size_t bytes;
 };
 
-Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, bool split = true) {
+Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, bool split, bool composed, int panel_target) {
     Carver c(ws);
     Bf16Workspace w{};
     const size_t Mp = (size_t)ceil_div64(sh.rows_max(), kTileM) * kTileM;
+    const size_t Rp = (size_t)panel_rows(sh, composed, panel_target);
     const size_t d = sh.d, ff = sh.ff, V = sh.V;
     w.Mp = (int64_t)Mp;
+    w.Rp = (int64_t)Rp;
     w.WguT = c.take<bf16>(2 * ff * d);
     w.WdT = c.take<bf16>(d * ff);
     w.WoT = c.take<bf16>(V * d);
-    w.X = c.take<bf16>(Mp * d);
-    w.a = c.take<bf16>(Mp * ff);
-    if (bwd) w.fu = c.take<bf16>(Mp * ff);
-    if (bwd) w.fv = c.take<bf16>(Mp * ff);
-    w.y = c.take<bf16>(Mp * d);
-    if (split) w.a_lo = c.take<bf16>(Mp * ff);
-    if (split) w.y_lo = c.take<bf16>(Mp * d);
-    w.dz = c.take<bf16>(Mp * V);
+    w.X = c.take<bf16>(Rp * d);
+    w.a = c.take<bf16>(Rp * ff);
+    if (bwd) w.fu = c.take<bf16>(Rp * ff);
+    if (bwd) w.fv = c.take<bf16>(Rp * ff);
+    w.y = c.take<bf16>(Rp * d);
+    if (split) w.a_lo = c.take<bf16>(Rp * ff);
+    if (split) w.y_lo = c.take<bf16>(Rp * d);
+    w.dz = c.take<bf16>(Rp * V);
     w.meta.token = c.take<uint8_t>(Mp);
     w.meta.logp_old = c.take<float>(Mp);
     w.meta.adv = c.take<float>(Mp);
@@ -133,8 +159,8 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, bool s
     w.out.clipped = c.take<uint8_t>(Mp);
     w.out.entropy = c.take<float>(Mp);
     w.out.coef = c.take<float>(Mp);
-    if (bwd) w.dz_extra = c.take<bf16>(Mp * V);
-    if (bwd) w.dy = c.take<bf16>(Mp * d);
+    if (bwd) w.dz_extra = c.take<bf16>(Rp * V);
+    if (bwd) w.dy = c.take<bf16>(Rp * d);
     w.Wdo = c.take<bf16>(ff * V);
     if (grads) w.G = c.take<bf16>(ff * V);
     w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
@@ -154,34 +180,52 @@ int pick_splits(int tiles, int steps) {
     return s < 1 ? 1 : s;
 }
 
-// Which GEMM dimension runs over the kept rows, so that work beyond the device-side count is skipped.
+// Which GEMM dimension runs over the kept rows, so that work beyond the device-side count is skipped; the rows
+// are those of a panel that starts at batch row `row_offset`.
 struct KeptRows {
     const int32_t* kept;
     int kept_max, rows_per_kept;
+    int row_offset;
 };
+
+// sum_parts_f32 that adds to `out` instead of overwriting it.
+__global__ void add_parts_f32(const float* parts, int n_parts, size_t n, float* out) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
+        float4 acc = *reinterpret_cast<const float4*>(out + i);
+        for (int s = 0; s < n_parts; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(parts + (size_t)s * n + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+        *reinterpret_cast<float4*>(out + i) = acc;
+    }
+}
 
 // C[M, N] = product of p with a long reduction and possibly a small output: fp32 (C32) or rounded to bf16
 // (C16), exactly one of the two given.  A small output is computed as several partial products over slices of
 // the reduction, summed by a second kernel (no atomics).  The weight gradients are the case
 // kLayA = kLayB = kKByRows: A^T B over the kept rows with both operands stored [rows][features].
+// accumulate (fp32 output only): the product is added to C.
 template <int kLayA, int kLayB>
-void launch_reduction_gemm(GemmProblem p, float* C32, bf16* C16, float* parts, int stage, hipStream_t s) {
+void launch_reduction_gemm(GemmProblem p, float* C32, bf16* C16, float* parts, bool accumulate, int stage, hipStream_t s) {
     p.splits = pick_splits((p.M / kTileM) * (p.N / kTileN), p.K1 / kTileK);
     StageTimer t(stage, s);
     if (p.splits == 1) {
-        if (C32) launch_gemm<kLayA, kLayB>(p, EpiStoreF32{C32, p.N, 0}, s);
+        p.skip_if_empty = accumulate ? 1 : 0;
+        if (C32) launch_gemm<kLayA, kLayB>(p, EpiStoreF32{C32, p.N, 0, accumulate ? 1 : 0}, s);
         else launch_gemm<kLayA, kLayB>(p, EpiStoreBf16{C16, p.N, p.M}, s);
         return;
     }
     const size_t n = (size_t)p.M * p.N;
-    launch_gemm<kLayA, kLayB>(p, EpiStoreF32{parts, p.N, (int64_t)n}, s);
+    launch_gemm<kLayA, kLayB>(p, EpiStoreF32{parts, p.N, (int64_t)n, 0}, s);
     size_t blocks = (n / 4 + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    if (C32) sum_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32);
+    if (C32 && accumulate) add_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32);
+    else if (C32) sum_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32);
     else sum_parts_bf16<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C16);
 }
-void launch_weight_grad(const GemmProblem& p, float* C, float* parts, int stage, hipStream_t s) {
-    launch_reduction_gemm<kKByRows, kKByRows>(p, C, nullptr, parts, stage, s);
+void launch_weight_grad(const GemmProblem& p, float* C, float* parts, bool accumulate, int stage, hipStream_t s) {
+    launch_reduction_gemm<kKByRows, kKByRows>(p, C, nullptr, parts, accumulate, stage, s);
 }
 
 GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
@@ -191,13 +235,14 @@ GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int 
     p.A2 = A; p.B2 = B;
     p.M = M; p.N = N; p.K1 = K; p.K2 = 0; p.splits = 1;
     p.kept = kr.kept; p.kept_max = kr.kept_max; p.rows_per_kept = kr.rows_per_kept; p.rows_role = rows_role;
+    p.row_offset = kr.row_offset; p.skip_if_empty = 0;
     return p;
 }
 
 }  // namespace
 
-size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio) {
-    return carve(nullptr, sh, want_grads, want_grads, chunk_ratio).bytes;
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio, bool composed, int panel_target) {
+    return carve(nullptr, sh, want_grads, want_grads, chunk_ratio, composed, panel_target).bytes;
 }
 
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s) {
@@ -207,107 +252,122 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     // errors: the forward pass then carries a and y as pairs of bf16 values (value and rounding remainder) through
     // the down and the logit product, which brings the error of a log-probability from about 2e-3 down to 1e-5.
     const bool split = io.opt.chunk_ratio != 0;
-    Bf16Workspace w = carve(ws, sh, bwd, grads, split);
-    const int Mp = (int)w.Mp;
+    Bf16Workspace w = carve(ws, sh, bwd, grads, split, io.composed, io.opt.panel_rows);
     const int d = sh.d, ff = sh.ff, V = sh.V;
     const bf16* Wg = static_cast<const bf16*>(io.Wg);
     const bf16* Wu = static_cast<const bf16*>(io.Wu);
     const bf16* Wd = static_cast<const bf16*>(io.Wd);
     const bf16* Wo = static_cast<const bf16*>(io.Wo);
-    const KeptRows kr{io.n_kept, sh.max_chunks, sh.A};
 
     transpose(s, Wg, d, ff, w.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);   // [d, ff] -> packed rows of [2 ff, d]
     transpose(s, Wu, d, ff, w.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
-    const KeptRows all_rows{nullptr, 0, 0};
+    const KeptRows all_rows{nullptr, 0, 0, 0};
     if (io.composed) {
         // W_do = Wd Wo [ff, V], from the weights as given (Wd [rows][K], Wo [K][rows])
         launch_reduction_gemm<kRowsByK, kKByRows>(problem(Wd, d, Wo, V, ff, V, d, all_rows, kRowsUnused), nullptr, w.Wdo,
-                                                  w.parts, ST_WEIGHT_LAYOUT, s);
+                                                  w.parts, false, ST_WEIGHT_LAYOUT, s);
     } else {
         transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
         transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
     }
-    int rc = launch_gather(sh, io, 2, w.X, Mp, w.meta, s);
-    if (rc != PCM_OK) return rc;
-    {
-        StageTimer t(ST_GEMM_GATE_UP, s);
-        const GemmProblem p = problem(w.X, d, w.WguT, d, Mp, 2 * ff, d, kr, kRowsAreM);
-        if (split && bwd) launch_gemm(p, EpiSwigluForward<true, true>{w.fu, w.fv, w.a, w.a_lo, ff}, s);
-        else if (split) launch_gemm(p, EpiSwigluForward<false, true>{nullptr, nullptr, w.a, w.a_lo, ff}, s);
-        else if (bwd) launch_gemm(p, EpiSwigluForward<true>{w.fu, w.fv, w.a, nullptr, ff}, s);
-        else launch_gemm(p, EpiSwigluForward<false>{nullptr, nullptr, w.a, nullptr, ff}, s);
-    }
-    if (!io.composed) {
-        StageTimer t(ST_GEMM_DOWN, s);
-        GemmProblem p = problem(w.a, ff, w.WdT, ff, Mp, d, ff, kr, kRowsAreM);
-        if (split) {                                       // y = [a | a_lo] [Wd; Wd], kept as y + y_lo
-            p.A2 = w.a_lo; p.B2 = w.WdT; p.K2 = ff;
-            launch_gemm(p, EpiStoreBf16Split{w.y, w.y_lo, d, Mp}, s);
-        } else {
-            launch_gemm(p, EpiStoreBf16{w.y, d, Mp}, s);
-        }
-    }
-    {
-        StageTimer t(ST_GEMM_LOGITS_LOSS, s);
-        EpiLogitsLoss epi{w.meta.token, w.meta.logp_old, w.meta.adv, io.n_kept, sh.max_chunks, sh.A,
-                          io.opt, bwd ? w.dz : nullptr, w.dz_extra, io.logp_out, w.out};
-        if (io.composed)   // z = a W_do, W_do read as [K][rows]
-            launch_gemm<kRowsByK, kKByRows>(problem(w.a, ff, w.Wdo, V, Mp, V, ff, kr, kRowsAreM), epi, s);
-        else {
-            GemmProblem p = problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM);
-            if (split) { p.A2 = w.y_lo; p.B2 = w.WoT; p.K2 = d; }   // z = [y | y_lo] [Wo; Wo]
-            launch_gemm(p, epi, s);
-        }
-    }
-    if (io.opt.chunk_ratio) {
-        rc = launch_chunk_ratio(sh, io, w.meta, w.out, Mp, s);
+
+    int rc = PCM_OK;
+    for (int64_t row0 = 0; row0 < w.Mp; row0 += w.Rp) {
+        // this panel: batch rows [row0, row0 + Mp); all row-indexed arrays below are its parts
+        const int Mp = (int)(w.Mp - row0 < w.Rp ? w.Mp - row0 : w.Rp);
+        const bool first = row0 == 0;
+        const KeptRows kr{io.n_kept, sh.max_chunks, sh.A, (int)row0};
+        const RowMeta meta{w.meta.token + row0, w.meta.logp_old + row0, w.meta.adv + row0};
+        const RowOut out{w.out.term + row0, w.out.ratio + row0, w.out.dlogp + row0, w.out.clipped + row0,
+                         w.out.entropy + row0, w.out.coef + row0};
+        rc = launch_gather(sh, io, 2, w.X, row0, Mp, meta, s);
         if (rc != PCM_OK) return rc;
-        if (bwd) {
-            rc = launch_scale_rows(sh, io, w.dz, io.opt.entropy_coef != 0.f ? w.dz_extra : nullptr, w.out.coef, Mp, 2, s);
+        {
+            StageTimer t(ST_GEMM_GATE_UP, s);
+            const GemmProblem p = problem(w.X, d, w.WguT, d, Mp, 2 * ff, d, kr, kRowsAreM);
+            if (split && bwd) launch_gemm(p, EpiSwigluForward<true, true>{w.fu, w.fv, w.a, w.a_lo, ff}, s);
+            else if (split) launch_gemm(p, EpiSwigluForward<false, true>{nullptr, nullptr, w.a, w.a_lo, ff}, s);
+            else if (bwd) launch_gemm(p, EpiSwigluForward<true>{w.fu, w.fv, w.a, nullptr, ff}, s);
+            else launch_gemm(p, EpiSwigluForward<false>{nullptr, nullptr, w.a, nullptr, ff}, s);
+        }
+        if (!io.composed) {
+            StageTimer t(ST_GEMM_DOWN, s);
+            GemmProblem p = problem(w.a, ff, w.WdT, ff, Mp, d, ff, kr, kRowsAreM);
+            if (split) {                                       // y = [a | a_lo] [Wd; Wd], kept as y + y_lo
+                p.A2 = w.a_lo; p.B2 = w.WdT; p.K2 = ff;
+                launch_gemm(p, EpiStoreBf16Split{w.y, w.y_lo, d, Mp}, s);
+            } else {
+                launch_gemm(p, EpiStoreBf16{w.y, d, Mp}, s);
+            }
+        }
+        {
+            StageTimer t(ST_GEMM_LOGITS_LOSS, s);
+            EpiLogitsLoss epi{meta.token, meta.logp_old, meta.adv, io.n_kept, sh.max_chunks, sh.A, (int)row0,
+                              io.opt, bwd ? w.dz : nullptr, w.dz_extra, io.logp_out ? io.logp_out + row0 : nullptr, out};
+            if (io.composed) {   // z = a W_do, W_do read as [K][rows]
+                launch_gemm<kRowsByK, kKByRows>(problem(w.a, ff, w.Wdo, V, Mp, V, ff, kr, kRowsAreM), epi, s);
+            } else {
+                GemmProblem p = problem(w.y, d, w.WoT, d, Mp, V, d, kr, kRowsAreM);
+                if (split) { p.A2 = w.y_lo; p.B2 = w.WoT; p.K2 = d; }   // z = [y | y_lo] [Wo; Wo]
+                launch_gemm(p, epi, s);
+            }
+        }
+        if (io.opt.chunk_ratio) {
+            rc = launch_chunk_ratio(sh, io, meta, out, row0, Mp, s);
             if (rc != PCM_OK) return rc;
+            if (bwd) {
+                rc = launch_scale_rows(sh, io, w.dz, io.opt.entropy_coef != 0.f ? w.dz_extra : nullptr, out.coef, row0, Mp,
+                                       2, s);
+                if (rc != PCM_OK) return rc;
+            }
+        }
+        if (!bwd) continue;
+
+        if (io.composed) {      // one panel: nothing to add to
+            if (grads) {
+                // G = a^T dz [ff, V] over the kept rows, rounded to bf16 as the operand of the two products below
+                launch_reduction_gemm<kKByRows, kKByRows>(problem(w.a, ff, w.dz, V, ff, V, Mp, kr, kRowsAreK), nullptr, w.G,
+                                                          w.parts, false, ST_GEMM_DWD, s);
+                {
+                    StageTimer t(ST_GEMM_DWD, s);                                                                 // dWd = G Wo^T
+                    launch_gemm<kRowsByK, kRowsByK>(problem(w.G, V, Wo, V, ff, d, V, all_rows, kRowsUnused),
+                                                    EpiStoreF32{io.dWd, d, 0, 0}, s);
+                }
+                launch_weight_grad(problem(Wd, d, w.G, V, d, V, ff, all_rows, kRowsUnused), io.dWo, w.parts, false,
+                                   ST_GEMM_DWO, s);                                                               // dWo = Wd^T G
+            }
+            StageTimer t(ST_GEMM_DA, s);                                                                          // da = dz W_do^T
+            launch_gemm(problem(w.dz, V, w.Wdo, V, Mp, ff, V, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);
+        } else {
+            {
+                StageTimer t(ST_GEMM_DY, s);
+                launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);          // dy = dz Wo^T
+            }
+            if (grads) {
+                launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, !first, ST_GEMM_DWO,
+                                   s);                                                                            // dWo (+)= y^T dz
+                launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, !first, ST_GEMM_DWD,
+                                   s);                                                                            // dWd (+)= a^T dy
+            }
+            StageTimer t(ST_GEMM_DA, s);
+            launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);   // fu <- du, fv <- dv
+        }
+        if (grads) {
+            launch_weight_grad(problem(w.X, d, w.fu, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, !first, ST_GEMM_DWG_DWU,
+                               s);                                                                                // dWg (+)= X^T du
+            launch_weight_grad(problem(w.X, d, w.fv, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, !first, ST_GEMM_DWG_DWU,
+                               s);                                                                                // dWu (+)= X^T dv
+        }
+        if (io.dX) {
+            StageTimer t(ST_GEMM_DX, s);
+            GemmProblem p = problem(w.fu, ff, Wg, ff, Mp, d, ff, kr, kRowsAreM);                                 // dX = du Wg^T + dv Wu^T
+            p.A2 = w.fv; p.B2 = Wu; p.K2 = ff;
+            const int64_t rows_left = sh.rows_max() - row0;
+            launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX) + row0 * d, d, (int)(rows_left < Mp ? rows_left : Mp)}, s);
         }
     }
     rc = launch_loss_reduce(sh, io, w.out, s);
     if (rc != PCM_OK) return rc;
-    if (!bwd) return launch_status();
-
-    if (io.composed) {
-        if (grads) {
-            // G = a^T dz [ff, V] over the kept rows, rounded to bf16 as the operand of the two products below
-            launch_reduction_gemm<kKByRows, kKByRows>(problem(w.a, ff, w.dz, V, ff, V, Mp, kr, kRowsAreK), nullptr, w.G,
-                                                      w.parts, ST_GEMM_DWD, s);
-            {
-                StageTimer t(ST_GEMM_DWD, s);                                                                     // dWd = G Wo^T
-                launch_gemm<kRowsByK, kRowsByK>(problem(w.G, V, Wo, V, ff, d, V, all_rows, kRowsUnused),
-                                                EpiStoreF32{io.dWd, d, 0}, s);
-            }
-            launch_weight_grad(problem(Wd, d, w.G, V, d, V, ff, all_rows, kRowsUnused), io.dWo, w.parts, ST_GEMM_DWO,
-                               s);                                                                                // dWo = Wd^T G
-        }
-        StageTimer t(ST_GEMM_DA, s);                                                                              // da = dz W_do^T
-        launch_gemm(problem(w.dz, V, w.Wdo, V, Mp, ff, V, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);
-    } else {
-        {
-            StageTimer t(ST_GEMM_DY, s);
-            launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);             // dy = dz Wo^T
-        }
-        if (grads) {
-            launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, ST_GEMM_DWO, s);   // dWo = y^T dz
-            launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, ST_GEMM_DWD, s); // dWd = a^T dy
-        }
-        StageTimer t(ST_GEMM_DA, s);
-        launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);    // fu <- du, fv <- dv
-    }
-    if (grads) {
-        launch_weight_grad(problem(w.X, d, w.fu, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, ST_GEMM_DWG_DWU, s);   // dWg = X^T du
-        launch_weight_grad(problem(w.X, d, w.fv, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, ST_GEMM_DWG_DWU, s);   // dWu = X^T dv
-    }
-    if (io.dX) {
-        StageTimer t(ST_GEMM_DX, s);
-        GemmProblem p = problem(w.fu, ff, Wg, ff, Mp, d, ff, kr, kRowsAreM);                                     // dX = du Wg^T + dv Wu^T
-        p.A2 = w.fv; p.B2 = Wu; p.K2 = ff;
-        launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX), d, (int)sh.rows_max()}, s);
-    }
     return launch_status();
 }
 

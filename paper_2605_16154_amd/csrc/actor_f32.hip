@@ -287,7 +287,7 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
     const size_t n_ff = (size_t)M * ff;
     const unsigned ew_blocks = (unsigned)((n_ff + 1023) / 1024) < 4096 ? (unsigned)((n_ff + 1023) / 1024) : 4096;
 
-    int rc = launch_gather(sh, io, 4, w.X, M, w.meta, s);
+    int rc = launch_gather(sh, io, 4, w.X, 0, M, w.meta, s);
     if (rc != PCM_OK) return rc;
     {
         StageTimer t(ST_F32_FORWARD, s);
@@ -309,10 +309,10 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
             bwd ? 1 : 0, io.logp_out, w.out);
     }
     if (io.opt.chunk_ratio) {
-        rc = launch_chunk_ratio(sh, io, w.meta, w.out, M, s);
+        rc = launch_chunk_ratio(sh, io, w.meta, w.out, 0, M, s);
         if (rc != PCM_OK) return rc;
         if (bwd) {
-            rc = launch_scale_rows(sh, io, w.z, io.opt.entropy_coef != 0.f ? w.z_extra : nullptr, w.out.coef, M, 4, s);
+            rc = launch_scale_rows(sh, io, w.z, io.opt.entropy_coef != 0.f ? w.z_extra : nullptr, w.out.coef, 0, M, 4, s);
             if (rc != PCM_OK) return rc;
         }
     }

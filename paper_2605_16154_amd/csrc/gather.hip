@@ -27,19 +27,20 @@ template <typename Vec>
 __global__ __launch_bounds__(kThreads) void gather_rows(
     const Vec* __restrict__ hidden, const uint8_t* __restrict__ tokens, const float* __restrict__ logp_old,
     const float* __restrict__ adv, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ n_kept,
-    int max_chunks, int T, int N, int A, int V, int vec_per_row, int64_t rows_pad, Vec* __restrict__ X,
-    uint8_t* m_token, float* m_logp_old, float* m_adv) {
+    int max_chunks, int T, int N, int A, int V, int vec_per_row, int64_t row_offset, int64_t rows_pad,
+    Vec* __restrict__ X, uint8_t* m_token, float* m_logp_old, float* m_adv) {
+    // rows are those of a panel that starts at batch row row_offset; X and the m_ arrays are the panel's
     __shared__ int64_t src_row[kRowsPerBlock];
     int nk = *n_kept;
     nk = nk < 0 ? 0 : (nk > max_chunks ? max_chunks : nk);
-    const int64_t rows_valid = (int64_t)nk * A;
+    const int64_t rows_valid = (int64_t)nk * A - row_offset;
     const int64_t r0 = (int64_t)blockIdx.x * kRowsPerBlock;
     const int tid = threadIdx.x;
     if (tid < kRowsPerBlock) {
         const int64_t r = r0 + tid;
         int64_t src = -1;
         if (r < rows_valid) {
-            const int ci = (int)(r / A), tok = (int)(r % A);
+            const int ci = (int)((r + row_offset) / A), tok = (int)((r + row_offset) % A);
             int id = kept_idx[ci];
             float a = 0.f;
             if (id >= 0 && (int64_t)id < (int64_t)T * N) a = adv[id / N];
@@ -125,19 +126,21 @@ __global__ __launch_bounds__(1024) void loss_reduce(const float* __restrict__ te
 __global__ __launch_bounds__(256) void chunk_ratio_rows(const float* __restrict__ dlogp,
                                                         const float* __restrict__ adv_row,
                                                         const int32_t* __restrict__ n_kept, int max_chunks, int A,
-                                                        int64_t rows_pad, LossOptions opt, float* __restrict__ term,
-                                                        float* __restrict__ ratio, uint8_t* __restrict__ clipped,
-                                                        float* __restrict__ coef) {
+                                                        int64_t row_offset, int64_t rows_pad, LossOptions opt,
+                                                        float* __restrict__ term, float* __restrict__ ratio,
+                                                        uint8_t* __restrict__ clipped, float* __restrict__ coef) {
+    // chunk slots of a panel that starts at batch row row_offset (a multiple of A); the arrays are the panel's
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t r0 = c * A;
     if (r0 >= rows_pad) return;
-    const int64_t rows = live_rows(n_kept, max_chunks, A);
+    const int64_t rows_batch = live_rows(n_kept, max_chunks, A);
+    const int64_t rows = rows_batch - row_offset;
     const int64_t r1 = r0 + A < rows_pad ? r0 + A : rows_pad;
     if (r0 >= rows) return;                             // beyond the kept chunks: nothing reads these rows
     float sum = 0.f;
     for (int64_t r = r0; r < r1; ++r) sum -= dlogp[r];
-    const float w = opt.chunk_weight ? opt.chunk_weight[c] : 1.f;
-    const LossRow lr = loss_from_ratio(expf(sum), adv_row[r0], w, opt, objective_scale(opt, rows));
+    const float w = opt.chunk_weight ? opt.chunk_weight[c + row_offset / A] : 1.f;
+    const LossRow lr = loss_from_ratio(expf(sum), adv_row[r0], w, opt, objective_scale(opt, rows_batch));
     for (int64_t r = r0; r < r1; ++r) {
         term[r] = r == r0 ? lr.term : 0.f;
         ratio[r] = lr.ratio;
@@ -164,8 +167,8 @@ __device__ inline bf16 from_f32<bf16>(float x) { return __float2bfloat16(x); }
 template <typename T>
 __global__ __launch_bounds__(256) void scale_rows(T* __restrict__ dz, const T* __restrict__ extra,
                                                    const float* __restrict__ coef, const int32_t* __restrict__ n_kept,
-                                                   int max_chunks, int A, int64_t rows_pad, int V) {
-    int64_t rows = live_rows(n_kept, max_chunks, A);
+                                                   int max_chunks, int A, int64_t row_offset, int64_t rows_pad, int V) {
+    int64_t rows = live_rows(n_kept, max_chunks, A) - row_offset;
     rows = rows < rows_pad ? rows : rows_pad;
     const int64_t n = rows * V;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(256) void scale_rows(T* __restrict__ dz, const T* _
 
 }  // namespace
 
-int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t rows_pad,
+int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t row_offset, int64_t rows_pad,
                   RowMeta meta, hipStream_t s) {
     StageTimer t(ST_GATHER, s);
     const int64_t row_bytes = (int64_t)sh.d * elem_bytes;
@@ -189,7 +192,7 @@ int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void*
     gather_rows<Vec><<<blocks, kThreads, 0, s>>>(static_cast<const Vec*>(io.hidden), io.tokens,          \
                                                  io.logp_old, io.adv, io.kept_idx, io.n_kept,            \
                                                  sh.max_chunks, sh.T, sh.N, sh.A, sh.V, (int)(vpr),      \
-                                                 rows_pad, static_cast<Vec*>(X), meta.token,             \
+                                                 row_offset, rows_pad, static_cast<Vec*>(X), meta.token, \
                                                  meta.logp_old, meta.adv)
     if (aligned16) PCM_GATHER(uint4, row_bytes / 16);
     else if (elem_bytes == 4) PCM_GATHER(uint32_t, sh.d);
@@ -205,27 +208,27 @@ int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipS
     return launch_status();
 }
 
-int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t rows_pad,
-                       hipStream_t s) {
+int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, RowOut out, int64_t row_offset,
+                       int64_t rows_pad, hipStream_t s) {
     StageTimer t(ST_REDUCE, s);
     const int64_t slots = ceil_div64(rows_pad, sh.A);
     chunk_ratio_rows<<<(unsigned)ceil_div64(slots, 256), 256, 0, s>>>(out.dlogp, meta.adv, io.n_kept, sh.max_chunks,
-                                                                      sh.A, rows_pad, io.opt, out.term, out.ratio,
-                                                                      out.clipped, out.coef);
+                                                                      sh.A, row_offset, rows_pad, io.opt, out.term,
+                                                                      out.ratio, out.clipped, out.coef);
     return launch_status();
 }
 
 int launch_scale_rows(const ActorShape& sh, const ActorIO& io, void* dz, const void* extra, const float* coef,
-                      int64_t rows_pad, int elem_bytes, hipStream_t s) {
+                      int64_t row_offset, int64_t rows_pad, int elem_bytes, hipStream_t s) {
     StageTimer t(ST_REDUCE, s);
     const int64_t n = rows_pad * sh.V;
     unsigned blocks = (unsigned)(ceil_div64(n, 256) < 4096 ? ceil_div64(n, 256) : 4096);
     if (elem_bytes == 2)
         scale_rows<bf16><<<blocks, 256, 0, s>>>(static_cast<bf16*>(dz), static_cast<const bf16*>(extra), coef, io.n_kept,
-                                                sh.max_chunks, sh.A, rows_pad, sh.V);
+                                                sh.max_chunks, sh.A, row_offset, rows_pad, sh.V);
     else
         scale_rows<float><<<blocks, 256, 0, s>>>(static_cast<float*>(dz), static_cast<const float*>(extra), coef,
-                                                 io.n_kept, sh.max_chunks, sh.A, rows_pad, sh.V);
+                                                 io.n_kept, sh.max_chunks, sh.A, row_offset, rows_pad, sh.V);
     return launch_status();
 }
 

@@ -61,8 +61,12 @@ struct GemmProblem {
     // rows of the row dimension carry data.  rows_role says which GEMM dimension that is:
     // kRowsAreM: row tiles entirely beyond the count exit at once; kRowsAreK: the reduction stops at
     // the count rounded up to a whole step (rows up to there are valid, zero-padded).
+    // With row_offset the operand rows are a panel of a longer batch: the panel's live rows are the batch's live
+    // rows beyond row_offset.  skip_if_empty: a workgroup whose reduction range is empty leaves without running the
+    // epilogue (for epilogues that add to what is already there).
     const int32_t* kept;
     int kept_max, rows_per_kept, rows_role;
+    int row_offset, skip_if_empty;
 };
 enum RowsRole : int { kRowsUnused = 0, kRowsAreM = 1, kRowsAreK = 2 };
 
@@ -181,7 +185,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
     if (p.kept != nullptr) {
         int nk = *p.kept;
         nk = nk < 0 ? 0 : (nk > p.kept_max ? p.kept_max : nk);
-        const int rows = nk * p.rows_per_kept;
+        const int rows = max(0, nk * p.rows_per_kept - p.row_offset);
         if (p.rows_role == kRowsAreM) live_m = min(tiles_m, (rows + kTileM - 1) / kTileM);
         if (p.rows_role == kRowsAreK) k1 = min(k1, (rows + kTileK - 1) / kTileK * kTileK);
     }
@@ -422,6 +426,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         __syncthreads();
     }
 
+    if (p.skip_if_empty && step_begin >= step_end) return;    // nothing to add (uniform over the workgroup)
     TileCoord tc{m0, n0, wm, wn, lane, split};
     epi(tc, acc, reinterpret_cast<char*>(smem));
 }
@@ -480,6 +485,23 @@ __device__ inline void copy_rows_out(const char* st, int stride, char* dst, int6
             out += out_step;
             r += kRowsPerPass;
         }
+    }
+}
+// The same for fp32 rows that are added to what global memory holds (16 bytes = 4 floats per lane).
+template <int kRows, int kRowBytes>
+__device__ inline void add_rows_out(const char* st, int stride, char* dst, int64_t ld_bytes, int lane) {
+    constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
+    const char* src = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+    char* out = dst + (lane / kLanesPerRow) * ld_bytes + (lane % kLanesPerRow) * 16;
+    const int64_t out_step = kRowsPerPass * ld_bytes;
+#pragma unroll 8
+    for (int pass = 0; pass < kRows / kRowsPerPass; ++pass) {
+        const f32x4 add = *reinterpret_cast<const f32x4*>(src);
+        f32x4 cur = *reinterpret_cast<const f32x4*>(out);
+        cur += add;
+        *reinterpret_cast<f32x4*>(out) = cur;
+        src += kRowsPerPass * stride;
+        out += out_step;
     }
 }
 // Global memory -> staging area, the mirror image of copy_rows_out (all kRows rows), in two halves so
@@ -569,10 +591,12 @@ struct EpiStoreBf16Split {
 
 // C (fp32, row-major) = acc.  With a split reduction, part s goes to C + s * split_stride (its own
 // M x N matrix; the caller sums the parts), so no atomics are needed and the sum is reproducible.
+// accumulate: C += acc instead (a batch processed in row panels adds every panel's weight gradient).
 struct EpiStoreF32 {
     float* C;
     int64_t ldc;
     int64_t split_stride;
+    int accumulate;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
         float* const C = this->C + tc.split * split_stride;
         constexpr int kStride = 528;                       // 128 fp32 + 16 bytes: conflict-free 16-byte accesses
@@ -590,7 +614,9 @@ struct EpiStoreF32 {
                 }
             __builtin_amdgcn_wave_barrier();
             const int row_base = tc.m0 + tc.wm * 128 + i * 32;
-            copy_rows_out<32, 512>(st, kStride, reinterpret_cast<char*>(C + (int64_t)row_base * ldc + col_base), ldc * 4, 32, tc.lane);
+            char* const dst = reinterpret_cast<char*>(C + (int64_t)row_base * ldc + col_base);
+            if (accumulate) add_rows_out<32, 512>(st, kStride, dst, ldc * 4, tc.lane);
+            else copy_rows_out<32, 512>(st, kStride, dst, ldc * 4, 32, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }
@@ -724,6 +750,7 @@ struct EpiLogitsLoss {
     const float* adv_row;
     const int32_t* n_kept;
     int max_chunks, A;
+    int row_offset;    // batch row of the panel's row 0 (the per-row arrays below are the panel's parts)
     LossOptions opt;
     bf16* dz;          // [M, 256] or nullptr
     bf16* dz_extra;    // [M, 256]: entropy part, per-chunk ratio only
@@ -734,8 +761,9 @@ struct EpiLogitsLoss {
         float* ex_a = reinterpret_cast<float*>(lds);
         float* ex_b = ex_a + 512;
         float* ex_c = ex_b + 512;
-        const int64_t rows_live = live_rows(n_kept, max_chunks, A);
-        const float scale = objective_scale(opt, rows_live);
+        const int64_t rows_batch = live_rows(n_kept, max_chunks, A);
+        const float scale = objective_scale(opt, rows_batch);
+        const int64_t rows_live = rows_batch - row_offset;          // live rows of this panel (may be <= 0)
         const int lrow_base = tc.wm * 128 + (tc.lane & 31);
 
         float mx[4];
@@ -802,7 +830,7 @@ struct EpiLogitsLoss {
             const int m = tc.row(i);
             const bool live = m < rows_live;
             const float lp = ztok[i] - lse[i];
-            const float w = (opt.chunk_weight && live) ? opt.chunk_weight[m / A] : 1.f;
+            const float w = (opt.chunk_weight && live) ? opt.chunk_weight[(m + row_offset) / A] : 1.f;
             const LossRow lr = loss_row(lp, logp_old[m], adv_row[m], w, opt, scale);
             if (tc.wn == 0 && tc.lane < 32) {
                 out.dlogp[m] = lr.dlogp;

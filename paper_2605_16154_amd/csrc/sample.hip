@@ -443,7 +443,59 @@ __global__ __launch_bounds__(kThreads) void importance_weights(const uint8_t* __
     }
 }
 
+// One workgroup: histograms in LDS of the kept chunks' phases and of the phases of all chunk slots the sampler
+// could have kept, written out as they are (nothing to clear, no atomics in memory).
+__global__ __launch_bounds__(1024) void kept_phase_counts(const uint8_t* __restrict__ phase,
+                                                          const int32_t* __restrict__ n_chunks,
+                                                          const uint8_t* __restrict__ active,
+                                                          const int32_t* __restrict__ kept_idx,
+                                                          const int32_t* __restrict__ n_kept, int max_kept, int T, int N,
+                                                          int K, int32_t* kept_out, int32_t* eligible_out) {
+    __shared__ int hist[2][PCM_MAX_PHASES];
+    const int tid = threadIdx.x;
+    if (tid < 2 * PCM_MAX_PHASES) hist[tid / PCM_MAX_PHASES][tid % PCM_MAX_PHASES] = 0;
+    __syncthreads();
+    int nk = *n_kept;
+    nk = nk < 0 ? 0 : (nk > max_kept ? max_kept : nk);
+    const int64_t slots = (int64_t)T * N;
+    for (int j = tid; j < nk; j += 1024) {
+        const int id = kept_idx[j];
+        if (id >= 0 && id < slots) {
+            const int c = phase[id];
+            atomicAdd(&hist[0][c < K ? c : K - 1], 1);
+        }
+    }
+    if (eligible_out) {
+        for (int64_t e = tid; e < slots; e += 1024) {
+            const int i = (int)(e / N), k = (int)(e % N);
+            int Ni = n_chunks ? n_chunks[i] : N;
+            Ni = Ni > N ? N : Ni;
+            if (k < Ni && (!active || active[i])) {
+                const int c = phase[e];
+                atomicAdd(&hist[1][c < K ? c : K - 1], 1);
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < K) {
+        kept_out[tid] = hist[0][tid];
+        if (eligible_out) eligible_out[tid] = hist[1][tid];
+    }
+}
+
 }  // namespace
+
+extern "C" int pcm_kept_phase_counts(const uint8_t* phase, const int32_t* n_chunks, const uint8_t* active,
+                                     const int32_t* kept_idx, const int32_t* n_kept, int max_kept_chunks, int T, int N,
+                                     int K, int32_t* kept_per_phase, int32_t* chunks_per_phase, void* stream) {
+    if (!phase || !kept_idx || !n_kept || !kept_per_phase || max_kept_chunks < 0) return PCM_EINVAL;
+    if (!shape_ok(T, N, K, 1)) return PCM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    StageTimer t(ST_SAMPLE_COMPACT, s);
+    kept_phase_counts<<<1, 1024, 0, s>>>(phase, n_chunks, active, kept_idx, n_kept, max_kept_chunks, T, N, K, kept_per_phase,
+                                         chunks_per_phase);
+    return launch_status();
+}
 
 extern "C" int pcm_sample_chunks(const double* keep_probs, const uint8_t* phase, const int32_t* n_chunks,
                                  const uint8_t* active, int T, int N, int K, int B, uint64_t seed,

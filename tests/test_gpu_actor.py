@@ -286,6 +286,33 @@ def conditioned_logp_old(hidden_rows, tokens_rows, lp_old_rows, adv_chunks, A, W
     return condition_logp_old(lp_old_rows, cur["logp"], np.arange(len(lp_old_rows)), eps[0], eps[1], margin)
 
 
+@pytest.mark.parametrize("n_kept,variants", [(120, {}), (101, dict(chunk_ratio=True, entropy_coef=0.01, token_mean=True))])
+def test_bf16_row_panels_add_up_to_the_whole_batch(pcm, n_kept, variants):
+    """A batch worked through in row panels (here: panels of 1792 rows = 32 chunks, so 120 kept chunks are three full
+    panels and a ragged fourth, 101 chunks end inside the fourth): every panel adds its weight gradients to the
+    earlier ones', per-row outputs land at the panel's offset, the loss is reduced once over all rows.  Against the
+    checker on the whole batch, and bit for bit against itself with a different kept count below the capacity."""
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=8, N=16, K=4, B=8, d=512, ff=768, seed=31)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, cfg.seed, 0)
+    assert len(kept) == 128
+    pr = make_problem(cfg, wstd=0.05, margin=0.08, kept=kept[:n_kept], old_rel=0.1, eps=(0.2, 0.4))
+    if variants.get("chunk_ratio"):
+        from test_gpu_actor_variants import condition_chunks
+        pr = condition_chunks(pr, (0.2, 0.4), 0.02)
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), torch_dtype=torch.bfloat16, max_kept=128, variants=variants, panel_rows=1792)
+    assert 0.05 < ref["stats"][0] < 0.95
+    check(ref, got, BF16_TOL, len(ref["rows"]), stats_tol=5e-2)
+    # one panel for everything (the default height) gives the same rows bit for bit; the weight gradients differ only
+    # by the order of fp32 additions
+    _, whole = run_both(pcm, pr, eps=(0.2, 0.4), torch_dtype=torch.bfloat16, max_kept=128, variants=variants)
+    n = len(ref["rows"])
+    assert np.array_equal(whole["logp"][:n], got["logp"][:n]) and np.array_equal(whole["dX"][:n], got["dX"][:n])
+    for k in GRADS:
+        assert rel(got[k], whole[k]) <= 1e-5, k
+
+
 @pytest.mark.timeout(1200)
 def test_bf16_full_size_head_whole_batch_against_checker(pcm, composed):
     """LIBERO-shaped head (d = 4096, ff = 11008) in the launch configuration the benchmark times: the whole

@@ -140,6 +140,11 @@ def _sample_both(pcm, p, phase, n_chunks, active, B, seed, step, selector="pcm",
     assert int(nk.item()) == nk_o
     assert np.array_equal(off.cpu().numpy(), off_o)
     assert np.array_equal(kept.cpu().numpy()[:nk_o], kept_o)
+    # realised allocation per phase (Sec. 5.2): exact counts
+    d_act = None if active is None else dev(active)
+    got_kept, got_elig = pcm.pcm_kept_phase_counts(dev(phase), d_nch, d_act, kept, nk, len(p))
+    ref_kept, ref_elig = O.kept_phase_counts(phase, n_chunks, active, kept_o, len(p))
+    assert np.array_equal(got_kept.cpu().numpy(), ref_kept) and np.array_equal(got_elig.cpu().numpy(), ref_elig)
     if weights:
         w = pcm.pcm_importance_weights(dev(phase), d_nch, kept, off, len(p))
         torch.cuda.synchronize()

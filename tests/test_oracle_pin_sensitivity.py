@@ -35,6 +35,9 @@ MISTAKES = [
     ("importance weight inverted", "np.float32(len(in_phase)) / np.float32(b)", "np.float32(b) / np.float32(len(in_phase))", SEL),
     ("allocation ignores the phase sizes", "weight = [int(n_c[c]) * int(q[c]) for c in range(K)]", "weight = [int(q[c]) for c in range(K)]", SEL),
     ("allocation ties to the higher index", "key=lambda c: (-rem[c], c)", "key=lambda c: (-rem[c], -c)", SEL),
+    ("allocation counts inactive trajectories", "        if active is not None and not active[i]:\n            continue\n", "", SEL),
+    ("out-of-range phase ids dropped from the score", "                c = min(int(phase[i, k]), K - 1)        # an id beyond the last phase counts as the last\n",
+     "                c = int(phase[i, k])\n                if c >= K:\n                    continue\n", SEL),
     ("top phase picks the smallest probability", "if keep_probs[c] > keep_probs[best]:", "if keep_probs[c] < keep_probs[best]:", SEL),
     ("grasp threshold 0.5 instead of 0.75", "sustained = [4 * c >= 3 * L for c in count]", "sustained = [2 * c >= L for c in count]", LAB),
     ("windows two chunks wide", "range(j + 1, min(j + 4, Ni))", "range(j + 1, min(j + 3, Ni))", LAB),

@@ -468,3 +468,25 @@ def test_stratified_selector_budgets_uniformity_and_unbiased_weights():
         full = sum(f[i, phase[i] == c].sum() for c in covered)
         spread = np.abs(f[i]).sum() * N / B
         assert abs(est[i] / steps - full) < 5 * spread / math.sqrt(steps)
+
+
+def test_kept_phase_counts_hand_example_and_totals():
+    # Sec. 5.2's realised allocation: kept chunks per phase next to the chunks that could have been kept
+    phase = np.array([[0, 0, 1, 2], [1, 1, 2, 2], [0, 1, 1, 9]], dtype=np.uint8)      # 9 is out of range: read as K - 1
+    kept = np.array([0, 2, 5, 7, 11])                                              # phases 0, 1, 1, 2, 2
+    got, eligible = O.kept_phase_counts(phase, np.array([4, 3, 4]), np.array([1, 1, 1], np.uint8), kept, 3)
+    assert np.array_equal(got, [1, 2, 2])
+    assert np.array_equal(eligible, [3, 5, 3])                                     # trajectory 1 has 3 valid slots
+    got, eligible = O.kept_phase_counts(phase, None, np.array([1, 0, 1], np.uint8), kept[[0, 1, 4]], 3)
+    assert np.array_equal(got, [1, 1, 1]) and np.array_equal(eligible, [3, 3, 2])  # the inactive trajectory drops out
+    cfg = CONFIGS["cfg2"]
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    p = np.array([1.0, 0.1, 0.5, 0.1, 0.3])
+    kept, _, nk = O.sample_chunks(p, ro["phase"], ro["n_chunks"], active, cfg.B, cfg.seed, 0)
+    got, eligible = O.kept_phase_counts(ro["phase"], ro["n_chunks"], active, kept, cfg.K)
+    assert got.sum() == nk and np.array_equal(got, np.bincount(ro["phase"].reshape(-1)[kept], minlength=cfg.K))
+    assert eligible.sum() == ro["n_chunks"][active.astype(bool)].sum() and np.all(got <= eligible)
+    # the phase with keep probability 1 receives a larger share of its chunks than the ones at the floor
+    share = got / np.maximum(eligible, 1)
+    assert share[0] > share[1] and share[0] > share[3]
