@@ -6,6 +6,8 @@
                                                                   # HBM-side bytes per launch of one kernel
   python -m paper_2605_16154_amd.profile_summary tail <dir> <kernel substring> <n>
                                                                   # mean duration of a kernel's last n launches
+  python -m paper_2605_16154_amd.profile_summary table <fetch_dir> <write_dir> <kernel substring> [...]
+                                                                  # HBM-side bytes per launch of several kernels, one row each
 """
 from __future__ import annotations
 
@@ -107,7 +109,26 @@ def traffic(fetch_dir: str, write_dir: str, kernel_substr: str) -> str:
             f"source_hash={kernel_source_hash()}\n")
 
 
+def table(fetch_dir: str, write_dir: str, kernels) -> str:
+    """One row per kernel: launches, FETCH_SIZE and WRITE_SIZE per launch scaled to bytes with the factors that the
+    1 GiB elementwise calibration kernel of the same runs gives."""
+    cal_f, _ = _mean_counter(fetch_dir, "FETCH_SIZE", "CUDAFunctorOnSelf_add<double>")
+    cal_w, _ = _mean_counter(write_dir, "WRITE_SIZE", "CUDAFunctorOnSelf_add<double>")
+    gib = float(1 << 20)
+    sf, sw = gib / cal_f, gib / cal_w
+    out = [f"# scale_fetch={sf:.4f} scale_write={sw:.4f} (FETCH_SIZE / WRITE_SIZE of a kernel that reads and writes exactly 1 GiB)",
+           f"{'kernel':34s} {'launches':>8s} {'read_MB':>12s} {'written_MB':>12s}"]
+    for k in kernels:
+        f, nf = _mean_counter(fetch_dir, "FETCH_SIZE", k)
+        w, _ = _mean_counter(write_dir, "WRITE_SIZE", k)
+        out.append(f"{k:34s} {nf:8d} {f * sf * 1024 / 1e6:12.3f} {w * sw * 1024 / 1e6:12.3f}")
+    return "\n".join(out) + "\n"
+
+
 if __name__ == "__main__":
+    if len(sys.argv) >= 5 and sys.argv[1] == "table":
+        sys.stdout.write(table(sys.argv[2], sys.argv[3], sys.argv[4:]))
+        sys.exit(0)
     if len(sys.argv) == 5 and sys.argv[1] == "traffic":
         sys.stdout.write(traffic(sys.argv[2], sys.argv[3], sys.argv[4]))
         sys.exit(0)
