@@ -87,6 +87,9 @@ class Workload:
                 b["logp_old"][c0 * cfg.A:(c0 + n) * cfg.A] = out["logp"][:n * cfg.A]
         del W_old, zeros
         self.state = pcm.pcm_state_init(cfg.K, device)
+        # the forward products' operand layouts of the weights, written once: they change with the weights (once per
+        # optimizer step), not with the batch
+        self.packed = pcm.pcm_pack_head_weights(self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"]) if cfg.dtype == "bf16" else None
         self.sel_out = None
         self.samp_out = None
         self.act_out = {}
@@ -105,7 +108,9 @@ class Workload:
         kept, off, nk = self.samp_out
         self.act_out = pcm.grpo_masked_actor_step(self.hidden, b["tokens"], b["logp_old"], adv, kept, nk, cfg.T, cfg.N,
                                                   cfg.A, self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"],
-                                                  0.2, 0.4, 1.0 / cfg.T, out=self.act_out, **loss_variants)
+                                                  0.2, 0.4, 1.0 / cfg.T, out=self.act_out,
+                                                  packed_weights=None if loss_variants.get("composed_head") else self.packed,
+                                                  **loss_variants)
         return nk
 
 
@@ -298,6 +303,29 @@ def graph_replay_timing(wl, steps):
             "note": "each graph replays its batch with the step index it was captured with"}
 
 
+def vendor_yardstick(wl, rows, iters=20):
+    """The vendor BLAS (through torch.matmul) on the gate/up shape with operands of the same distribution: a yardstick
+    for what this chip sustains on that shape with a plain bf16 store, never a dependency of the library.  Timed over
+    `iters` launches after a warm-up; reported beside `value`, never part of it."""
+    torch, cfg = wl.torch, wl.cfg
+    x = wl.hidden[:rows].contiguous()
+    w = torch.cat([wl.W["Wg"], wl.W["Wu"]], dim=1).t().contiguous()          # [2 ff, d], reduction index contiguous
+    out = torch.empty((rows, 2 * cfg.ff), dtype=torch.bfloat16, device=wl.dev)
+    for _ in range(5):
+        torch.matmul(x, w.t(), out=out)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(iters):
+        torch.matmul(x, w.t(), out=out)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / iters
+    flops = 2.0 * rows * cfg.d * 2 * cfg.ff
+    return {"shape": [rows, 2 * cfg.ff, cfg.d], "ms_per_launch": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+            "frac_of_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "note": "vendor BLAS via torch.matmul, plain bf16 store (no fused activation, one output)"}
+
+
 def optimizer_step_timing(wl, iters=10):
     """The optimizer step that would follow the actor gradients (App. D: clipping at 2.0 + AdamW), timed on
     the head's real tensors: not part of `value`, reported beside it.  HBM-bound: per parameter the norm pass
@@ -341,6 +369,8 @@ def main():
     ap.add_argument("--extras", action="store_true",
                     help="also time the loss variants, the composed head evaluation, HIP-graph replay and sample board "
                          "power and clock (none of them enters `value`)")
+    ap.add_argument("--yardstick", action="store_true",
+                    help="also time the vendor BLAS on the gate/up shape (a yardstick beside the roofline, not part of `value`)")
     ap.add_argument("--cpu-sample-chunks", type=int, default=384)
     ap.add_argument("--selection-only", action="store_true",
                     help="time only the three selection calls of --config and print their bytes and GB/s")
@@ -496,6 +526,8 @@ def main():
     if cfg.dtype == "bf16" and not args.no_extras:
         wl.step(0)                                  # leaves fresh gradients of the masked step in wl.act_out
         result["optimizer_step"] = optimizer_step_timing(wl)
+    if args.yardstick and cfg.dtype == "bf16":
+        result["vendor_blas_yardstick"] = vendor_yardstick(wl, rows)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, kept_host, args.cpu_sample_chunks)
     print(json.dumps(result))

@@ -331,7 +331,8 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
  * gradients within the 2e-2 bound of the per-token form at any A.  That pass exists for PCM_HEAD_AS_WRITTEN only:
  * PCM_RATIO_CHUNK with PCM_HEAD_COMPOSED and PCM_BF16 returns PCM_EUNSUPPORTED.
  * Errors: PCM_EINVAL also for options == NULL, an unknown normalisation, ratio_level or
- * head_evaluation, NaN coefficients, negative panel_rows.
+ * head_evaluation, NaN coefficients, negative panel_rows, misaligned packed_weights; PCM_EUNSUPPORTED for
+ * packed_weights with dtype PCM_F32 or PCM_HEAD_COMPOSED.
  * ------------------------------------------------------------------------------------------ */
 typedef enum { PCM_NORM_SCALE = 0, PCM_NORM_TOKEN_MEAN = 1 } pcm_normalisation;
 typedef enum { PCM_RATIO_TOKEN = 0, PCM_RATIO_CHUNK = 1 } pcm_ratio_level;
@@ -346,7 +347,28 @@ typedef struct {
     int head_evaluation;        /* pcm_head_evaluation */
     int panel_rows;             /* dtype PCM_BF16: target height of the row panels a long batch is worked through in;
                                    0 = the library's choice (57,344 rows).  See "Row panels" above. */
+    const void* packed_weights; /* device, or NULL: the operand layouts of the four weight matrices as written by
+                                   pcm_pack_head_weights for these d, ff, V (dtype PCM_BF16, PCM_HEAD_AS_WRITTEN
+                                   only).  The step then skips its own re-layout of Wg, Wu, Wd, Wo, which otherwise
+                                   runs in every call although the weights change once per optimizer step.  The
+                                   caller re-packs after every change of the weights; Wg, Wu, Wd, Wo must still be
+                                   given (the backward pass reads them as they are). */
 } pcm_loss_options;
+
+/* ------------------------------------------------------------------------------------------
+ * pcm_pack_head_weights -- the bf16 operand layouts that the forward products of the head read: gate and up
+ * projection transposed and interleaved in blocks of 64 output columns ([2 ff, d], so that the gated activation
+ * can be fused into the product), down projection transposed ([d, ff]), logit projection transposed ([V, d]).
+ * The actor step builds them in its workspace on every call; a caller that keeps them (one pack per optimizer
+ * step, after pcm_adamw_clip_step has written the bf16 weights) passes them in pcm_loss_options.packed_weights.
+ *
+ *   Wg, Wu device bf16 [d, ff];  Wd device bf16 [ff, d];  Wo device bf16 [d, V]
+ *   packed  device, 256-byte aligned, pcm_packed_head_bytes(d, ff, V) bytes (0 = unsupported shape)
+ * Requires d % 256 == 0, ff % 256 == 0, V == 256 (the shapes of the bf16 path).
+ * ------------------------------------------------------------------------------------------ */
+PCM_API size_t pcm_packed_head_bytes(int d, int ff, int V);
+PCM_API int pcm_pack_head_weights(const void* Wg, const void* Wu, const void* Wd, const void* Wo, int d, int ff, int V,
+                          void* packed, void* stream);
 
 /* Workspace of grpo_masked_actor_step_ex for these options (the per-chunk ratio needs more than the plain step). */
 PCM_API size_t grpo_masked_actor_step_ex_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V, int dtype,

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     pcm_kept_phase_counts,
     pcm_label_phases,
     pcm_measure_mfma_rate,
+    pcm_pack_head_weights,
     pcm_profile_collect,
     pcm_profile_enable,
     pcm_sample_chunks,

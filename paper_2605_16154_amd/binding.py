@@ -30,7 +30,8 @@ class LossOptions(C.Structure):
     """pcm_loss_options of include/pcm.h."""
     _fields_ = [("eps_low", C.c_float), ("eps_high", C.c_float), ("loss_scale", C.c_float),
                 ("entropy_coef", C.c_float), ("normalisation", C.c_int), ("ratio_level", C.c_int),
-                ("chunk_weight", C.c_void_p), ("head_evaluation", C.c_int), ("panel_rows", C.c_int)]
+                ("chunk_weight", C.c_void_p), ("head_evaluation", C.c_int), ("panel_rows", C.c_int),
+                ("packed_weights", C.c_void_p)]
 
 
 def _sig(fn, res, args):
@@ -62,6 +63,8 @@ def lib() -> C.CDLL:
     _sig(L.pcm_sample_chunks_ex, i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, u64, u64, vp, vp, vp, vp, sz, vp])
     _sig(L.pcm_importance_weights, i32, [vp, vp, vp, vp, i32, i32, i32, vp, vp])
     _sig(L.pcm_kept_phase_counts, i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp])
+    _sig(L.pcm_packed_head_bytes, sz, [i32] * 3)
+    _sig(L.pcm_pack_head_weights, i32, [vp, vp, vp, vp, i32, i32, i32, vp, vp])
     _sig(L.grpo_masked_actor_step_workspace_bytes, sz, [i32] * 7)
     _sig(L.grpo_masked_actor_step_ex_workspace_bytes, sz, [i32] * 7 + [C.POINTER(LossOptions)])
     _sig(L.grpo_masked_actor_step, i32,
@@ -245,6 +248,22 @@ def pcm_kept_phase_counts(phase, n_chunks, active, kept_idx, n_kept, K: int, out
     return out
 
 
+def pcm_pack_head_weights(Wg, Wu, Wd, Wo, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """bf16 [d, ff], [d, ff], [ff, d], [d, V] -> u8 buffer holding the forward products' operand layouts."""
+    d, ff = Wg.shape
+    V = Wo.shape[1]
+    nbytes = lib().pcm_packed_head_bytes(d, ff, V)
+    if nbytes == 0:
+        raise PcmError("pcm_pack_head_weights: unsupported head shape")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=Wg.device)
+    rc = lib().pcm_pack_head_weights(_ptr(Wg, torch.bfloat16, "Wg"), _ptr(Wu, torch.bfloat16, "Wu"),
+                                     _ptr(Wd, torch.bfloat16, "Wd"), _ptr(Wo, torch.bfloat16, "Wo"), d, ff, V,
+                                     _ptr(out, torch.uint8, "packed"), _stream())
+    _check(rc, "pcm_pack_head_weights")
+    return out
+
+
 def grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, want_grads) -> int:
     return lib().grpo_masked_actor_step_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype, int(want_grads))
 
@@ -255,13 +274,15 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                            out: Optional[Dict[str, torch.Tensor]] = None, token_mean: bool = False,
                            entropy_coef: float = 0.0, chunk_ratio: bool = False,
                            chunk_weight: Optional[torch.Tensor] = None,
-                           composed_head: bool = False, panel_rows: int = 0) -> Dict[str, torch.Tensor]:
+                           composed_head: bool = False, panel_rows: int = 0,
+                           packed_weights: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
     """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[5], and if requested dWg, dWu, dWd, dWo, dX).
 
     `out` may carry preallocated tensors under those names (they are reused, not reallocated).  With none of
     token_mean, entropy_coef, chunk_ratio, chunk_weight, composed_head set this is grpo_masked_actor_step
     (stats[4] stays 0); otherwise grpo_masked_actor_step_ex.  composed_head = PCM_HEAD_COMPOSED (down and logit
-    projection applied as one matrix); panel_rows = target height of the row panels of the bf16 path (0: default).
+    projection applied as one matrix); panel_rows = target height of the row panels of the bf16 path (0: default);
+    packed_weights = the operand layouts from pcm_pack_head_weights (the step then skips its own weight re-layout).
     """
     dev = hidden.device
     d, ff = Wg.shape
@@ -303,13 +324,14 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                  buf("dWd", (ff, d), torch.float32), buf("dWo", (d, V), torch.float32)]
     dX = buf("dX", (rows, d), hidden.dtype) if want_dX else None
     extended = (token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None or composed_head
-                or panel_rows != 0)
+                or panel_rows != 0 or packed_weights is not None)
     opt = None
     if extended:
         if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
             raise PcmError("chunk_weight is shorter than max_kept_chunks")
         opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
-                          _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head), int(panel_rows))
+                          _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head), int(panel_rows),
+                          _ptr(packed_weights, torch.uint8, "packed_weights"))
         need = lib().grpo_masked_actor_step_ex_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype,
                                                                int(want_grads or want_dX), C.byref(opt))
     else:

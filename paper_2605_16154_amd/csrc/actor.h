@@ -27,6 +27,7 @@ struct LossOptions {
     int chunk_ratio;             // one ratio (and one clipped term) per chunk instead of per token
     const float* chunk_weight;   // device [max_chunks] or null: multiplies the terms of a chunk
     int panel_rows;              // bf16 path: target height of the row panels (0 = the library's choice)
+    const void* packed_weights;  // bf16 path: operand layouts written by pcm_pack_head_weights, or null
 };
 
 struct ActorIO {
@@ -130,5 +131,8 @@ size_t actor_f32_workspace_bytes(const ActorShape& sh, bool want_grads);
 int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
 size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio, bool composed, int panel_target);
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
+size_t packed_head_bytes(int d, int ff, int V);
+int pack_head_weights(const void* Wg, const void* Wu, const void* Wd, const void* Wo, int d, int ff, int V, void* packed,
+                      hipStream_t s);
 
 }  // namespace pcm

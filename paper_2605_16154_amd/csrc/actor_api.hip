@@ -60,6 +60,10 @@ int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_
     if (dtype != PCM_F32 && dtype != PCM_BF16) return PCM_EINVAL;
     if (!shape_supported(sh, dtype)) return PCM_EUNSUPPORTED;
     const bool bwd = n_grad == 4 || dX != nullptr;
+    if (opt.packed_weights != nullptr) {
+        if (reinterpret_cast<uintptr_t>(opt.packed_weights) & 255u) return PCM_EINVAL;
+        if (dtype != PCM_BF16 || composed) return PCM_EUNSUPPORTED;
+    }
     // the split-precision forward pass of the per-chunk ratio exists for the evaluation as written only
     if (dtype == PCM_BF16 && opt.chunk_ratio && composed) return PCM_EUNSUPPORTED;
     const size_t need = workspace_need(sh, dtype, bwd, opt.chunk_ratio != 0, composed, opt.panel_rows);
@@ -80,7 +84,7 @@ extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens,
                                       float eps_low, float eps_high, float loss_scale, float* loss_out,
                                       float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
                                       float* stats_out, void* workspace, size_t workspace_bytes, void* stream) {
-    const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0};
+    const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0, nullptr};
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
                           Wu, Wd, Wo, opt, false, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 4, workspace,
                           workspace_bytes, stream);
@@ -100,8 +104,23 @@ extern "C" int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* toke
         return PCM_EINVAL;
     const LossOptions opt{options->eps_low, options->eps_high, options->loss_scale, options->entropy_coef,
                           options->normalisation == PCM_NORM_TOKEN_MEAN, options->ratio_level == PCM_RATIO_CHUNK,
-                          options->chunk_weight, options->panel_rows};
+                          options->chunk_weight, options->panel_rows, options->packed_weights};
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
                           Wu, Wd, Wo, opt, options->head_evaluation == PCM_HEAD_COMPOSED, loss_out, logp_out, dWg, dWu,
                           dWd, dWo, dX, stats_out, 5, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t pcm_packed_head_bytes(int d, int ff, int V) {
+    ActorShape sh{1, 1, 1, 1, d, ff, V};
+    if (d < 1 || ff < 1 || V < 1 || !shape_supported(sh, PCM_BF16)) return 0;
+    return packed_head_bytes(d, ff, V);
+}
+
+extern "C" int pcm_pack_head_weights(const void* Wg, const void* Wu, const void* Wd, const void* Wo, int d, int ff, int V,
+                                     void* packed, void* stream) {
+    if (!Wg || !Wu || !Wd || !Wo || !packed || d < 1 || ff < 1 || V < 1) return PCM_EINVAL;
+    if (reinterpret_cast<uintptr_t>(packed) & 255u) return PCM_EINVAL;
+    ActorShape sh{1, 1, 1, 1, d, ff, V};
+    if (!shape_supported(sh, PCM_BF16)) return PCM_EUNSUPPORTED;
+    return pack_head_weights(Wg, Wu, Wd, Wo, d, ff, V, packed, static_cast<hipStream_t>(stream));
 }

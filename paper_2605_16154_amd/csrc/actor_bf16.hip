@@ -101,6 +101,21 @@ __global__ void sum_parts_bf16(const float* parts, int n_parts, size_t n, bf16* 
     }
 }
 
+// The forward products' operand layouts of the four weight matrices, in one buffer.
+struct PackedHead {
+    bf16 *WguT, *WdT, *WoT;
+    size_t bytes;
+};
+PackedHead carve_packed(void* base, int d, int ff, int V) {
+    Carver c(base);
+    PackedHead p;
+    p.WguT = c.take<bf16>((size_t)2 * ff * d);
+    p.WdT = c.take<bf16>((size_t)d * ff);
+    p.WoT = c.take<bf16>((size_t)V * d);
+    p.bytes = c.used();
+    return p;
+}
+
 constexpr int64_t kPanelRows = 57344;   // target height of a row panel (224 row tiles)
 
 // Height of the row panels a batch of `sh.rows_max()` rows is worked through in: the whole (padded) batch if it
@@ -241,6 +256,18 @@ GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int 
 
 }  // namespace
 
+size_t packed_head_bytes(int d, int ff, int V) { return carve_packed(nullptr, d, ff, V).bytes; }
+
+int pack_head_weights(const void* Wg, const void* Wu, const void* Wd, const void* Wo, int d, int ff, int V, void* packed,
+                      hipStream_t s) {
+    const PackedHead p = carve_packed(packed, d, ff, V);
+    transpose(s, static_cast<const bf16*>(Wg), d, ff, p.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);
+    transpose(s, static_cast<const bf16*>(Wu), d, ff, p.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
+    transpose(s, static_cast<const bf16*>(Wd), ff, d, p.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);
+    transpose(s, static_cast<const bf16*>(Wo), d, V, p.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);
+    return launch_status();
+}
+
 size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio, bool composed, int panel_target) {
     return carve(nullptr, sh, want_grads, want_grads, chunk_ratio, composed, panel_target).bytes;
 }
@@ -259,16 +286,21 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     const bf16* Wd = static_cast<const bf16*>(io.Wd);
     const bf16* Wo = static_cast<const bf16*>(io.Wo);
 
-    transpose(s, Wg, d, ff, w.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);   // [d, ff] -> packed rows of [2 ff, d]
-    transpose(s, Wu, d, ff, w.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
     const KeptRows all_rows{nullptr, 0, 0, 0};
-    if (io.composed) {
-        // W_do = Wd Wo [ff, V], from the weights as given (Wd [rows][K], Wo [K][rows])
-        launch_reduction_gemm<kRowsByK, kKByRows>(problem(Wd, d, Wo, V, ff, V, d, all_rows, kRowsUnused), nullptr, w.Wdo,
-                                                  w.parts, false, ST_WEIGHT_LAYOUT, s);
+    if (io.opt.packed_weights != nullptr) {               // layouts kept by the caller: nothing to re-lay-out
+        const PackedHead ph = carve_packed(const_cast<void*>(io.opt.packed_weights), d, ff, V);
+        w.WguT = ph.WguT; w.WdT = ph.WdT; w.WoT = ph.WoT;
     } else {
-        transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
-        transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
+        transpose(s, Wg, d, ff, w.WguT, d, kPackGate, ST_WEIGHT_LAYOUT);   // [d, ff] -> packed rows of [2 ff, d]
+        transpose(s, Wu, d, ff, w.WguT, d, kPackUp, ST_WEIGHT_LAYOUT);
+        if (io.composed) {
+            // W_do = Wd Wo [ff, V], from the weights as given (Wd [rows][K], Wo [K][rows])
+            launch_reduction_gemm<kRowsByK, kKByRows>(problem(Wd, d, Wo, V, ff, V, d, all_rows, kRowsUnused), nullptr, w.Wdo,
+                                                      w.parts, false, ST_WEIGHT_LAYOUT, s);
+        } else {
+            transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
+            transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
+        }
     }
 
     int rc = PCM_OK;

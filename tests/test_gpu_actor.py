@@ -254,6 +254,32 @@ def test_bf16_all_kept_and_forward_only(pcm, composed):
         assert not zero[k].any()
 
 
+def test_bf16_packed_weights_give_the_same_step(pcm):
+    """The operand layouts of the weights written once by pcm_pack_head_weights and handed to the step: the same
+    kernels read the same bytes, so every output is bit for bit what the step computes when it lays the weights out
+    itself; stale layouts (weights changed, not re-packed) are the caller's responsibility and do change the result."""
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=4, N=16, K=4, B=5, d=512, ff=768, seed=12)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, 12, 0)
+    pr = make_problem(cfg, wstd=0.05, margin=0.08, kept=kept[:37], old_rel=0.1)
+    ref, own = run_both(pcm, pr, torch_dtype=torch.bfloat16, max_kept=40)
+    W = {k: dev(v, torch.bfloat16) for k, v in pr["W"].items()}
+    packed = pcm.pcm_pack_head_weights(W["Wg"], W["Wu"], W["Wd"], W["Wo"])
+    _, given = run_both(pcm, pr, torch_dtype=torch.bfloat16, max_kept=40, packed_weights=packed)
+    n = len(ref["rows"])                                        # rows beyond the kept ones are left untouched
+    for k in GRADS + ("loss",):
+        assert np.array_equal(given[k], own[k]), k
+    assert np.array_equal(given["stats"][:4], own["stats"][:4])     # the extended entry point also fills stats[4]
+    assert np.array_equal(given["logp"][:n], own["logp"][:n]) and np.array_equal(given["dX"][:n], own["dX"][:n])
+    check(ref, given, BF16_TOL, n, stats_tol=5e-2)
+    stale = pcm.pcm_pack_head_weights(W["Wg"] * 2, W["Wu"], W["Wd"], W["Wo"])
+    _, other = run_both(pcm, pr, torch_dtype=torch.bfloat16, max_kept=40, packed_weights=stale)
+    assert not np.array_equal(other["logp"][:n], own["logp"][:n])
+    with pytest.raises(pcm.PcmError, match="unsupported"):
+        run_both(pcm, pr, torch_dtype=torch.bfloat16, max_kept=40, packed_weights=packed, composed_head=True)
+
+
 def test_bf16_short_kept_list_after_a_long_one(pcm, composed):
     """The kept count lives on the device: a call that keeps few chunks after one that kept many (same
     buffers, same workspace) must not see anything the earlier call left behind in the skipped row tiles."""
