@@ -55,7 +55,7 @@ def gemm_flops_per_launch(M, d, ff, V):
 class Workload:
     """Device-resident inputs of `n_batches` consecutive training steps plus the head."""
 
-    def __init__(self, cfg, device, n_batches):
+    def __init__(self, cfg, device, n_batches, policy_drift=0.01):
         import torch
         from workloads import make_head_torch, make_hidden_torch, make_rollouts, perturb_torch
         import paper_2605_16154_amd as pcm
@@ -67,7 +67,22 @@ class Workload:
             b["tokens"] = t(ro["tokens"].reshape(-1))
         self.hidden = make_hidden_torch(cfg, device)
         self.W = make_head_torch(cfg, device)
-        W_old = perturb_torch(cfg, self.W)
+        self.set_old_policy(policy_drift)
+        self.state = pcm.pcm_state_init(cfg.K, device)
+        # the forward products' operand layouts of the weights, written once: they change with the weights (once per
+        # optimizer step), not with the batch
+        self.packed = pcm.pcm_pack_head_weights(self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"]) if cfg.dtype == "bf16" else None
+        self.sel_out = None
+        self.samp_out = None
+        self.act_out = {}
+        torch.cuda.synchronize()
+
+    def set_old_policy(self, policy_drift):
+        """Old-policy log-probabilities of every action token from weights `policy_drift` (noise standard deviation)
+        away from the current ones."""
+        from workloads import perturb_torch
+        cfg, pcm, torch, device = self.cfg, self.pcm, self.torch, self.dev
+        W_old = perturb_torch(cfg, self.W, std=policy_drift)
         # old-policy log-probabilities of every action token: forward-only passes with the old weights,
         # T*B chunks at a time (the same launch shape as the timed step)
         per_call = cfg.T * min(cfg.B, cfg.N)
@@ -86,13 +101,6 @@ class Workload:
                                                  want_grads=False, want_dX=False)
                 b["logp_old"][c0 * cfg.A:(c0 + n) * cfg.A] = out["logp"][:n * cfg.A]
         del W_old, zeros
-        self.state = pcm.pcm_state_init(cfg.K, device)
-        # the forward products' operand layouts of the weights, written once: they change with the weights (once per
-        # optimizer step), not with the batch
-        self.packed = pcm.pcm_pack_head_weights(self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"]) if cfg.dtype == "bf16" else None
-        self.sel_out = None
-        self.samp_out = None
-        self.act_out = {}
         torch.cuda.synchronize()
 
     def step(self, t, B=None, **loss_variants):
@@ -372,6 +380,9 @@ def main():
     ap.add_argument("--yardstick", action="store_true",
                     help="also time the vendor BLAS on the gate/up shape (a yardstick beside the roofline, not part of `value`)")
     ap.add_argument("--cpu-sample-chunks", type=int, default=384)
+    ap.add_argument("--policy-drift", type=float, default=0.01,
+                    help="standard deviation of the weight noise that separates the old policy (whose log-probabilities "
+                         "enter the ratio) from the current one; weights themselves have standard deviation 0.02")
     ap.add_argument("--selection-only", action="store_true",
                     help="time only the three selection calls of --config and print their bytes and GB/s")
     ap.add_argument("--scale-groups", type=int, default=1,
@@ -398,7 +409,7 @@ def main():
             cfg = cfg.with_(n_groups=cfg.n_groups * args.scale_groups)
         print(json.dumps(selection_only(cfg, dev, max(args.steps, 50), args.warmup)))
         return
-    wl = Workload(cfg, dev, cfg.n_steps)
+    wl = Workload(cfg, dev, cfg.n_steps, args.policy_drift)
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.float64, device=dev)
         dst = torch.empty_like(src)
@@ -421,7 +432,7 @@ def main():
     # mean ratio, mean old-minus-new log-probability, rows) and its loss
     st = wl.act_out["stats"].cpu().tolist()
     step_stats = {"clip_fraction": st[0], "mean_ratio": st[1], "mean_logp_old_minus_logp": st[2], "rows": st[3],
-                  "loss": float(wl.act_out["loss"].item())}
+                  "loss": float(wl.act_out["loss"].item()), "policy_drift": args.policy_drift}
     # second pass over the same steps with the stage timer on: per-kernel durations (HIP events on the call's stream)
     stage_steps = args.steps if args.no_extras else max(args.steps, 10)
     dt_staged, _, stages = timed_steps(wl, stage_steps, 1, profile=True)
@@ -484,6 +495,18 @@ def main():
         result["unmasked"] = {"ms_per_step": ms_un, "kept_rows": n_un * cfg.A, "tokens_per_s": n_un * cfg.A * k_un / dt_un,
                               "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
                               "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
+    if cfg.dtype == "bf16" and not args.no_extras:
+        # the same step nearer to on-policy: the old policy 20 times closer, so that few ratios leave the clip range
+        # and almost no row of the backward products is zero (zero rows cost the matrix cores less power)
+        wl.set_old_policy(args.policy_drift / 20)
+        wl.state = pcm.pcm_state_init(cfg.K, dev)
+        k_n = max(2, min(10, args.steps))
+        dt_n, n_n, _ = timed_steps(wl, k_n, 1)
+        st_n = wl.act_out["stats"].cpu().tolist()
+        result["near_on_policy"] = {"policy_drift": args.policy_drift / 20, "ms_per_step": dt_n / k_n * 1e3,
+                                    "tokens_per_s": n_n * cfg.A * k_n / dt_n, "clip_fraction": st_n[0],
+                                    "mean_ratio": st_n[1]}
+        wl.set_old_policy(args.policy_drift)
     if cfg.dtype == "bf16" and args.extras:
         # the same step with the loss of App. D (entropy bonus 1e-3, token-mean normalisation) and with one
         # ratio per chunk: extended entry point, same kernels plus two small ones in the per-chunk case
