@@ -45,17 +45,28 @@ def stored_traffic(name):
         return None
 
 
-def gemm_flops_per_launch(M, d, ff, V):
-    """Algorithmic flops of one launch of each head GEMM over M token rows (2 flops per multiply-add)."""
+def gemm_flops_per_launch(M, d, ff, V, M_bwd=None):
+    """Flops of one launch of each head GEMM: the forward products over M token rows, the backward products over
+    M_bwd rows (those the library ran them over; M if not given).  2 flops per multiply-add."""
+    B = M if M_bwd is None else M_bwd
     return {"gemm_gate_up": 2.0 * M * d * 2 * ff, "gemm_down": 2.0 * M * ff * d, "gemm_logits_loss": 2.0 * M * d * V,
-            "gemm_dWo": 2.0 * M * d * V, "gemm_dy": 2.0 * M * V * d, "gemm_dWd": 2.0 * M * ff * d,
-            "gemm_da": 2.0 * M * d * ff, "gemm_dWg_dWu": 2.0 * M * d * ff, "gemm_dX": 2.0 * M * 2 * ff * d}
+            "gemm_dWo": 2.0 * B * d * V, "gemm_dy": 2.0 * B * V * d, "gemm_dWd": 2.0 * B * ff * d,
+            "gemm_da": 2.0 * B * d * ff, "gemm_dWg_dWu": 2.0 * B * d * ff, "gemm_dX": 2.0 * B * 2 * ff * d}
+
+
+def backward_rows(rows, clip_fractions, dense):
+    """Mean number of rows the backward products ran over: the library drops the rows whose gradient the clip
+    removes when they are at least one in sixteen (kept chunks of active groups have a non-zero advantage, so in a
+    one-panel batch those are all the rows it drops)."""
+    if dense or not clip_fractions:
+        return float(rows)
+    return float(np.mean([rows * (1.0 - c) if c >= 1.0 / 16 else rows for c in clip_fractions]))
 
 
 class Workload:
     """Device-resident inputs of `n_batches` consecutive training steps plus the head."""
 
-    def __init__(self, cfg, device, n_batches, policy_drift=0.01):
+    def __init__(self, cfg, device, n_batches, policy_drift=0.01, dense_backward=False):
         import torch
         from workloads import make_head_torch, make_hidden_torch, make_rollouts, perturb_torch
         import paper_2605_16154_amd as pcm
@@ -68,6 +79,7 @@ class Workload:
         self.hidden = make_hidden_torch(cfg, device)
         self.W = make_head_torch(cfg, device)
         self.set_old_policy(policy_drift)
+        self.dense_backward = dense_backward
         self.state = pcm.pcm_state_init(cfg.K, device)
         # the forward products' operand layouts of the weights, written once: they change with the weights (once per
         # optimizer step), not with the batch
@@ -118,7 +130,7 @@ class Workload:
                                                   cfg.A, self.W["Wg"], self.W["Wu"], self.W["Wd"], self.W["Wo"],
                                                   0.2, 0.4, 1.0 / cfg.T, out=self.act_out,
                                                   packed_weights=None if loss_variants.get("composed_head") else self.packed,
-                                                  **loss_variants)
+                                                  dense_backward=self.dense_backward, **loss_variants)
         return nk
 
 
@@ -130,13 +142,17 @@ def timed_steps(wl, steps, warmup, B=None, profile=False, **loss_variants):
     if profile:
         wl.pcm.pcm_profile_enable(True)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    clip = torch.zeros(steps, device=wl.dev) if profile else None
     t0 = time.perf_counter()
     marks[0].record()
     for t in range(warmup, warmup + steps):
         nk = wl.step(t, B, **loss_variants)
+        if profile:
+            clip[t - warmup] = wl.act_out["stats"][0]      # device-side copy, no synchronisation
         marks[t - warmup + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    wl.clip_fractions = clip.cpu().tolist() if profile else []
     wl.step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))   # per-step device time
     stages = None
     if profile:
@@ -380,6 +396,8 @@ def main():
     ap.add_argument("--yardstick", action="store_true",
                     help="also time the vendor BLAS on the gate/up shape (a yardstick beside the roofline, not part of `value`)")
     ap.add_argument("--cpu-sample-chunks", type=int, default=384)
+    ap.add_argument("--dense-backward", action="store_true",
+                    help="backward products over all kept rows, also those whose gradient the clip removes")
     ap.add_argument("--policy-drift", type=float, default=0.01,
                     help="standard deviation of the weight noise that separates the old policy (whose log-probabilities "
                          "enter the ratio) from the current one; weights themselves have standard deviation 0.02")
@@ -409,7 +427,7 @@ def main():
             cfg = cfg.with_(n_groups=cfg.n_groups * args.scale_groups)
         print(json.dumps(selection_only(cfg, dev, max(args.steps, 50), args.warmup)))
         return
-    wl = Workload(cfg, dev, cfg.n_steps, args.policy_drift)
+    wl = Workload(cfg, dev, cfg.n_steps, args.policy_drift, args.dense_backward)
     if args.copy_calibration:
         src = torch.zeros(1 << 27, dtype=torch.float64, device=dev)
         dst = torch.empty_like(src)
@@ -442,7 +460,8 @@ def main():
     tf_zero, clk_zero = pcm.pcm_measure_mfma_rate(False, 100)
     mfma_only = {"random_operands": {"tflops": tf_rand, "clock_ghz": clk_rand},
                  "zero_operands": {"tflops": tf_zero, "clock_ghz": clk_zero}}
-    flops = gemm_flops_per_launch(rows, cfg.d, cfg.ff, cfg.V)
+    rows_bwd = backward_rows(rows, wl.clip_fractions, args.dense_backward or cfg.dtype != "bf16")
+    flops = gemm_flops_per_launch(rows, cfg.d, cfg.ff, cfg.V, rows_bwd)
     per_stage = {}
     for name, (ms, launches) in stages.items():
         if launches == 0:
@@ -450,7 +469,8 @@ def main():
         per_stage[name] = {"ms_per_launch": ms / launches, "launches_per_step": launches / stage_steps}
         if name in flops:
             per_stage[name]["tflops"] = flops[name] / (ms / launches * 1e-3) / 1e12
-    total_flops_step = 3.0 * (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * rows
+    total_flops_step = 3.0 * (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * rows           # Eq. 11 over all kept rows
+    executed_flops_step = (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * (rows + 2.0 * rows_bwd)
     if cfg.dtype == "bf16":
         gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / stage_steps
         dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
@@ -462,9 +482,11 @@ def main():
                     "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
                     "mfma_only_sustained": mfma_only,
                     "frac_of_mfma_only_random": achieved / tf_rand,
-                    "all_head_gemms": {"tflops": total_flops_step / (gemm_ms_step * 1e-3) / 1e12,
-                                       "frac": total_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                                       "ms_per_step": gemm_ms_step}}
+                    # executed flops: forward over all kept rows, backward over the rows with a gradient
+                    "all_head_gemms": {"tflops": executed_flops_step / (gemm_ms_step * 1e-3) / 1e12,
+                                       "frac": executed_flops_step / (gemm_ms_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                       "ms_per_step": gemm_ms_step, "rows_forward": rows, "rows_backward_mean": rows_bwd,
+                                       "tflops_if_all_rows_counted": total_flops_step / (gemm_ms_step * 1e-3) / 1e12}}
     else:
         # fp32 correctness configuration: plain vector-ALU products (forward and backward stages of the fp32 path),
         # against the fp32 vector peak 256 CU x 4 SIMD x 64 lanes x 2 flop x 2.4 GHz

@@ -324,6 +324,14 @@ PCM_API int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens, co
  * over the same activation buffers, every panel after the first adds its weight gradients to the earlier ones'
  * (fp32), the loss is reduced once at the end.  The workspace is bounded by the panel, not by the batch.
  *
+ * Rows without a gradient (dtype PCM_BF16, PCM_HEAD_AS_WRITTEN, entropy_coef == 0; grpo_masked_actor_step does the
+ * same): a row whose ratio the clip cuts, or whose advantage or chunk weight is zero, has an all-zero row of
+ * d loss / d logits (Eq. 11 with the clipped surrogate), so it adds nothing to any weight gradient and its row of dX
+ * is zero.  When at least one row in sixteen of a panel is such a row, the backward products run over the other rows
+ * only (copied into dense operands; the decision is taken on the device from the loss stage's results).  The
+ * outputs are those of the backward pass over all rows up to the order of the fp32 sums.  dense_backward != 0
+ * switches this off.
+ *
  * Precision of PCM_RATIO_CHUNK with dtype PCM_BF16: the log-probabilities of a chunk's A rows add up in the
  * exponent of its ratio, and so would their bf16 errors (about 2e-3 each, 2e-2 for A = 56).  The forward pass
  * therefore carries a and y as pairs of bf16 values (value + rounding remainder) through the down and the logit
@@ -353,6 +361,8 @@ typedef struct {
                                    runs in every call although the weights change once per optimizer step.  The
                                    caller re-packs after every change of the weights; Wg, Wu, Wd, Wo must still be
                                    given (the backward pass reads them as they are). */
+    int dense_backward;         /* dtype PCM_BF16: non-zero = backward products over all kept rows, also over rows
+                                   without a gradient (see "Rows without a gradient" above); 0 = the default */
 } pcm_loss_options;
 
 /* ------------------------------------------------------------------------------------------

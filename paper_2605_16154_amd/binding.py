@@ -31,7 +31,7 @@ class LossOptions(C.Structure):
     _fields_ = [("eps_low", C.c_float), ("eps_high", C.c_float), ("loss_scale", C.c_float),
                 ("entropy_coef", C.c_float), ("normalisation", C.c_int), ("ratio_level", C.c_int),
                 ("chunk_weight", C.c_void_p), ("head_evaluation", C.c_int), ("panel_rows", C.c_int),
-                ("packed_weights", C.c_void_p)]
+                ("packed_weights", C.c_void_p), ("dense_backward", C.c_int)]
 
 
 def _sig(fn, res, args):
@@ -275,14 +275,16 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                            entropy_coef: float = 0.0, chunk_ratio: bool = False,
                            chunk_weight: Optional[torch.Tensor] = None,
                            composed_head: bool = False, panel_rows: int = 0,
-                           packed_weights: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+                           packed_weights: Optional[torch.Tensor] = None,
+                           dense_backward: bool = False) -> Dict[str, torch.Tensor]:
     """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[5], and if requested dWg, dWu, dWd, dWo, dX).
 
     `out` may carry preallocated tensors under those names (they are reused, not reallocated).  With none of
     token_mean, entropy_coef, chunk_ratio, chunk_weight, composed_head set this is grpo_masked_actor_step
     (stats[4] stays 0); otherwise grpo_masked_actor_step_ex.  composed_head = PCM_HEAD_COMPOSED (down and logit
     projection applied as one matrix); panel_rows = target height of the row panels of the bf16 path (0: default);
-    packed_weights = the operand layouts from pcm_pack_head_weights (the step then skips its own weight re-layout).
+    packed_weights = the operand layouts from pcm_pack_head_weights (the step then skips its own weight re-layout);
+    dense_backward = backward products over all kept rows, also those whose gradient is zero (bf16 path).
     """
     dev = hidden.device
     d, ff = Wg.shape
@@ -324,14 +326,14 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                  buf("dWd", (ff, d), torch.float32), buf("dWo", (d, V), torch.float32)]
     dX = buf("dX", (rows, d), hidden.dtype) if want_dX else None
     extended = (token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None or composed_head
-                or panel_rows != 0 or packed_weights is not None)
+                or panel_rows != 0 or packed_weights is not None or dense_backward)
     opt = None
     if extended:
         if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
             raise PcmError("chunk_weight is shorter than max_kept_chunks")
         opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
                           _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head), int(panel_rows),
-                          _ptr(packed_weights, torch.uint8, "packed_weights"))
+                          _ptr(packed_weights, torch.uint8, "packed_weights"), int(dense_backward))
         need = lib().grpo_masked_actor_step_ex_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype,
                                                                int(want_grads or want_dX), C.byref(opt))
     else:

@@ -28,6 +28,7 @@ struct LossOptions {
     const float* chunk_weight;   // device [max_chunks] or null: multiplies the terms of a chunk
     int panel_rows;              // bf16 path: target height of the row panels (0 = the library's choice)
     const void* packed_weights;  // bf16 path: operand layouts written by pcm_pack_head_weights, or null
+    int dense_backward;          // bf16 path: backward products over all kept rows, also those without a gradient
 };
 
 struct ActorIO {
@@ -88,6 +89,32 @@ int launch_chunk_ratio(const ActorShape& sh, const ActorIO& io, RowMeta meta, Ro
 int launch_scale_rows(const ActorShape& sh, const ActorIO& io, void* dz, const void* extra, const float* coef,
                       int64_t row_offset, int64_t rows_pad, int elem_bytes, hipStream_t s);
 
+// Backward pass over the rows that carry a gradient only (bf16 path).  A kernel lists the panel's rows whose factor
+// in dz is non-zero and writes, to device memory, what the backward products then read: their row count and which
+// buffers hold their row-indexed operands (the panel's own, or copies of the listed rows).
+struct LiveSources {
+    static constexpr int kCount = 4;
+    enum : int { kDz = 0, kY = 1, kA = 2, kX = 3 };
+    const void* p[kCount];
+};
+struct LivePlan {
+    const void* src[LiveSources::kCount];
+    int32_t n_rows;    // rows of the backward products
+    int32_t listed;    // 1: the products run over the listed rows (operands copied), 0: over all live rows
+};
+// A row carries a gradient when the clip does not cut it (RowOut::clipped) and its advantage and chunk weight are
+// non-zero; clipped and adv are the panel's parts of those arrays.
+int launch_live_row_list(const ActorShape& sh, const ActorIO& io, const uint8_t* clipped, const float* adv,
+                         int64_t row_offset, int64_t rows_pad, const LiveSources& whole, const LiveSources& listed,
+                         int32_t* idx, LivePlan* plan, hipStream_t s);
+// dst[m] = src[idx[m]] (rows of row_bytes bytes, a multiple of 16) when the plan says listed; else nothing.
+int launch_gather_listed(const void* src, const int32_t* idx, const LivePlan* plan, int64_t rows_pad, int64_t row_bytes,
+                         void* dst, hipStream_t s);
+// Zero rows of the panel's part of dX (rows_in_dX rows exist) wherever the listed products write nothing.
+int launch_zero_unlisted(const ActorShape& sh, const ActorIO& io, const uint8_t* clipped, const float* adv,
+                         int64_t row_offset, int64_t rows_pad, int64_t rows_in_dX, int64_t row_bytes, void* dX,
+                         hipStream_t s);
+
 // Number of live rows from the device-side kept count.
 __device__ inline int64_t live_rows(const int32_t* n_kept, int max_chunks, int A) {
     int nk = *n_kept;
@@ -129,7 +156,7 @@ __device__ inline LossRow loss_row(float logp, float logp_old, float adv, float 
 // actor_f32.hip / actor_bf16.hip ---------------------------------------------------------------
 size_t actor_f32_workspace_bytes(const ActorShape& sh, bool want_grads);
 int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
-size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio, bool composed, int panel_target);
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, const LossOptions& opt, bool composed);
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s);
 size_t packed_head_bytes(int d, int ff, int V);
 int pack_head_weights(const void* Wg, const void* Wu, const void* Wd, const void* Wo, int d, int ff, int V, void* packed,

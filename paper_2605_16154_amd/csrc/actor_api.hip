@@ -19,9 +19,16 @@ bool shape_valid(const ActorShape& sh) {
 }  // namespace
 
 namespace {
-size_t workspace_need(const ActorShape& sh, int dtype, bool bwd, bool chunk_ratio, bool composed, int panel_rows) {
-    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd)
-                            : actor_bf16_workspace_bytes(sh, bwd, chunk_ratio, composed, panel_rows);
+size_t workspace_need(const ActorShape& sh, int dtype, bool bwd, const LossOptions& opt, bool composed) {
+    return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd, opt, composed);
+}
+LossOptions plain_options(float eps_low, float eps_high, float loss_scale) {
+    return LossOptions{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0, nullptr, 0};
+}
+LossOptions from_boundary(const pcm_loss_options& o) {
+    return LossOptions{o.eps_low, o.eps_high, o.loss_scale, o.entropy_coef, o.normalisation == PCM_NORM_TOKEN_MEAN,
+                       o.ratio_level == PCM_RATIO_CHUNK, o.chunk_weight, o.panel_rows, o.packed_weights,
+                       o.dense_backward != 0};
 }
 }  // namespace
 
@@ -29,15 +36,15 @@ extern "C" size_t grpo_masked_actor_step_workspace_bytes(int max_kept_chunks, in
                                                          int dtype, int want_grads) {
     ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
     if (!shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
-    return workspace_need(sh, dtype, want_grads != 0, false, false, 0);
+    return workspace_need(sh, dtype, want_grads != 0, plain_options(0.f, 0.f, 1.f), false);
 }
 
 extern "C" size_t grpo_masked_actor_step_ex_workspace_bytes(int max_kept_chunks, int A, int d, int ff, int V, int dtype,
                                                             int want_grads, const pcm_loss_options* options) {
     ActorShape sh{max_kept_chunks, 1, 1, A, d, ff, V};
     if (!options || !shape_valid(sh) || !shape_supported(sh, dtype)) return 0;
-    return workspace_need(sh, dtype, want_grads != 0, options->ratio_level == PCM_RATIO_CHUNK,
-                          options->head_evaluation == PCM_HEAD_COMPOSED, options->panel_rows);
+    return workspace_need(sh, dtype, want_grads != 0, from_boundary(*options),
+                          options->head_evaluation == PCM_HEAD_COMPOSED);
 }
 
 namespace {
@@ -66,7 +73,7 @@ int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_
     }
     // the split-precision forward pass of the per-chunk ratio exists for the evaluation as written only
     if (dtype == PCM_BF16 && opt.chunk_ratio && composed) return PCM_EUNSUPPORTED;
-    const size_t need = workspace_need(sh, dtype, bwd, opt.chunk_ratio != 0, composed, opt.panel_rows);
+    const size_t need = workspace_need(sh, dtype, bwd, opt, composed);
     if (!workspace_ok(workspace, workspace_bytes, need)) return PCM_EWORKSPACE;
 
     ActorIO io{hidden, tokens, logp_old, adv, kept_idx, n_kept, Wg, Wu, Wd, Wo, opt,
@@ -84,7 +91,7 @@ extern "C" int grpo_masked_actor_step(const void* hidden, const uint8_t* tokens,
                                       float eps_low, float eps_high, float loss_scale, float* loss_out,
                                       float* logp_out, float* dWg, float* dWu, float* dWd, float* dWo, void* dX,
                                       float* stats_out, void* workspace, size_t workspace_bytes, void* stream) {
-    const LossOptions opt{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0, nullptr};
+    const LossOptions opt = plain_options(eps_low, eps_high, loss_scale);
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
                           Wu, Wd, Wo, opt, false, loss_out, logp_out, dWg, dWu, dWd, dWo, dX, stats_out, 4, workspace,
                           workspace_bytes, stream);
@@ -102,9 +109,7 @@ extern "C" int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* toke
         (options->ratio_level != PCM_RATIO_TOKEN && options->ratio_level != PCM_RATIO_CHUNK) ||
         (options->head_evaluation != PCM_HEAD_AS_WRITTEN && options->head_evaluation != PCM_HEAD_COMPOSED))
         return PCM_EINVAL;
-    const LossOptions opt{options->eps_low, options->eps_high, options->loss_scale, options->entropy_coef,
-                          options->normalisation == PCM_NORM_TOKEN_MEAN, options->ratio_level == PCM_RATIO_CHUNK,
-                          options->chunk_weight, options->panel_rows, options->packed_weights};
+    const LossOptions opt = from_boundary(*options);
     return run_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, max_kept_chunks, T, N, A, d, ff, V, dtype, Wg,
                           Wu, Wd, Wo, opt, options->head_evaluation == PCM_HEAD_COMPOSED, loss_out, logp_out, dWg, dWu,
                           dWd, dWo, dX, stats_out, 5, workspace, workspace_bytes, stream);

@@ -20,6 +20,14 @@
 // Rows are padded to a multiple of 256; padding rows are zero with zero advantage, so they
 // contribute nothing to any output.
 //
+// Backward over the rows that carry a gradient: a row whose ratio the clip cuts (or whose advantage or weight is
+// zero) has an all-zero row of dz, hence of dy, du, dv and dX, and adds nothing to a weight gradient.  After the loss
+// a kernel lists the other rows; when at least one row in sixteen drops out, dz, y, a and X are copied row by row
+// into dense matrices of the listed rows and every backward product runs over those (the da epilogue reads its
+// factors through the list, dX is written through it, its other rows zero-filled).  The decision, the row count and
+// the operand addresses stay in device memory: no host synchronisation.  Without an entropy bonus only (with one,
+// every row has a gradient), and not in the composed evaluation.
+//
 // A long batch is worked through in row panels (kPanelRows rows, a multiple of both the tile height
 // and the chunk length): gather, forward, loss and backward run panel by panel over the same
 // activation buffers, the weight gradients of every panel after the first are added to what the
@@ -137,6 +145,10 @@ struct Bf16Workspace {
     bf16 *X, *fu, *fv, *a, *y, *dz, *dz_extra;   // one panel each; fu, fv: SwiGLU derivative factors, then du, dv
     bf16 *a_lo, *y_lo;                           // per-chunk ratio: rounding remainders of a and y
     bf16* dy;
+    bf16 *du, *xy, *dzc;   // backward over listed rows: du (before that the listed rows of a), the listed rows of y and
+                           // later of X, the listed rows of dz; dv takes the place of a
+    int32_t* live_idx;     // [Rp] the listed rows
+    LivePlan* plan;        // null: backward over all rows
     bf16 *Wdo, *G;  // composed evaluation: Wd Wo and a^T dz, both [ff, V]
     float* parts;   // partial products of split reductions
     RowMeta meta;   // whole batch
@@ -146,9 +158,16 @@ struct Bf16Workspace {
     size_t bytes;
 };
 
-Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, bool split, bool composed, int panel_target) {
+// Whether the backward products of a call run over the listed rows (see the head of this file).
+bool lists_live_rows(const LossOptions& opt, bool bwd, bool composed) {
+    return bwd && !composed && !opt.dense_backward && opt.entropy_coef == 0.f;
+}
+
+Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, const LossOptions& opt, bool composed) {
     Carver c(ws);
     Bf16Workspace w{};
+    const bool split = opt.chunk_ratio != 0;
+    const int panel_target = opt.panel_rows;
     const size_t Mp = (size_t)ceil_div64(sh.rows_max(), kTileM) * kTileM;
     const size_t Rp = (size_t)panel_rows(sh, composed, panel_target);
     const size_t d = sh.d, ff = sh.ff, V = sh.V;
@@ -176,6 +195,13 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, bool s
     w.out.coef = c.take<float>(Mp);
     if (bwd) w.dz_extra = c.take<bf16>(Rp * V);
     if (bwd) w.dy = c.take<bf16>(Rp * d);
+    if (lists_live_rows(opt, bwd, composed)) {
+        w.du = c.take<bf16>(Rp * ff);
+        w.xy = c.take<bf16>(Rp * d);
+        w.dzc = c.take<bf16>(Rp * V);
+        w.live_idx = c.take<int32_t>(Rp);
+        w.plan = c.take<LivePlan>(1);
+    }
     w.Wdo = c.take<bf16>(ff * V);
     if (grads) w.G = c.take<bf16>(ff * V);
     w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
@@ -268,8 +294,8 @@ int pack_head_weights(const void* Wg, const void* Wu, const void* Wd, const void
     return launch_status();
 }
 
-size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, bool chunk_ratio, bool composed, int panel_target) {
-    return carve(nullptr, sh, want_grads, want_grads, chunk_ratio, composed, panel_target).bytes;
+size_t actor_bf16_workspace_bytes(const ActorShape& sh, bool want_grads, const LossOptions& opt, bool composed) {
+    return carve(nullptr, sh, want_grads, want_grads, opt, composed).bytes;
 }
 
 int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t s) {
@@ -279,7 +305,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
     // errors: the forward pass then carries a and y as pairs of bf16 values (value and rounding remainder) through
     // the down and the logit product, which brings the error of a log-probability from about 2e-3 down to 1e-5.
     const bool split = io.opt.chunk_ratio != 0;
-    Bf16Workspace w = carve(ws, sh, bwd, grads, split, io.composed, io.opt.panel_rows);
+    Bf16Workspace w = carve(ws, sh, bwd, grads, io.opt, io.composed);
     const int d = sh.d, ff = sh.ff, V = sh.V;
     const bf16* Wg = static_cast<const bf16*>(io.Wg);
     const bf16* Wu = static_cast<const bf16*>(io.Wu);
@@ -355,6 +381,68 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         }
         if (!bwd) continue;
 
+        if (w.plan != nullptr) {
+            // backward over the rows with a gradient; row counts and row-indexed operands come from the plan
+            const bf16* const* const src = reinterpret_cast<const bf16* const*>(w.plan->src);
+            const KeptRows lr{&w.plan->n_rows, Mp, 1, 0};
+            bf16* const dv = w.a;                       // free once the listed rows of a are copied
+            {
+                StageTimer t(ST_LIVE_ROWS, s);
+                const LiveSources whole{{w.dz, w.y, w.a, w.X}}, listed{{w.dzc, w.xy, w.du, w.xy}};
+                rc = launch_live_row_list(sh, io, out.clipped, meta.adv, row0, Mp, whole, listed, w.live_idx, w.plan, s);
+                if (rc != PCM_OK) return rc;
+                launch_gather_listed(w.dz, w.live_idx, w.plan, Mp, (int64_t)V * 2, w.dzc, s);
+                if (grads) launch_gather_listed(w.y, w.live_idx, w.plan, Mp, (int64_t)d * 2, w.xy, s);
+                if (grads) launch_gather_listed(w.a, w.live_idx, w.plan, Mp, (int64_t)ff * 2, w.du, s);
+            }
+            {
+                StageTimer t(ST_GEMM_DY, s);
+                GemmProblem p = problem(w.dz, V, Wo, V, Mp, d, V, lr, kRowsAreM);                                // dy = dz Wo^T
+                p.A_sel = src + LiveSources::kDz;
+                launch_gemm(p, EpiStoreBf16{w.dy, d, Mp}, s);
+            }
+            if (grads) {
+                GemmProblem p = problem(w.y, d, w.dz, V, d, V, Mp, lr, kRowsAreK);                               // dWo (+)= y^T dz
+                p.A_sel = src + LiveSources::kY;
+                p.B_sel = src + LiveSources::kDz;
+                launch_weight_grad(p, io.dWo, w.parts, !first, ST_GEMM_DWO, s);
+                p = problem(w.a, ff, w.dy, d, ff, d, Mp, lr, kRowsAreK);                                         // dWd (+)= a^T dy
+                p.A_sel = src + LiveSources::kA;
+                launch_weight_grad(p, io.dWd, w.parts, !first, ST_GEMM_DWD, s);
+            }
+            {
+                StageTimer t(ST_GEMM_DA, s);                                                                     // du, dv from da = dy Wd^T
+                launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, lr, kRowsAreM),
+                            EpiSwigluBackward<true>{w.fu, w.fv, ff, w.live_idx, w.du, dv}, s);
+            }
+            if (grads) {
+                {
+                    StageTimer t(ST_LIVE_ROWS, s);
+                    launch_gather_listed(w.X, w.live_idx, w.plan, Mp, (int64_t)d * 2, w.xy, s);
+                }
+                GemmProblem p = problem(w.X, d, w.du, ff, d, ff, Mp, lr, kRowsAreK);                             // dWg (+)= X^T du
+                p.A_sel = src + LiveSources::kX;
+                launch_weight_grad(p, io.dWg, w.parts, !first, ST_GEMM_DWG_DWU, s);
+                p.B = dv;                                                                                        // dWu (+)= X^T dv
+                p.B2 = dv;
+                launch_weight_grad(p, io.dWu, w.parts, !first, ST_GEMM_DWG_DWU, s);
+            }
+            if (io.dX) {
+                const int64_t rows_left = sh.rows_max() - row0;
+                bf16* const dX = static_cast<bf16*>(io.dX) + row0 * d;
+                {
+                    StageTimer t(ST_LIVE_ROWS, s);
+                    rc = launch_zero_unlisted(sh, io, out.clipped, meta.adv, row0, Mp, rows_left < Mp ? rows_left : Mp, (int64_t)d * 2, dX,
+                                              s);
+                    if (rc != PCM_OK) return rc;
+                }
+                StageTimer t(ST_GEMM_DX, s);
+                GemmProblem p = problem(w.du, ff, Wg, ff, Mp, d, ff, lr, kRowsAreM);                             // dX = du Wg^T + dv Wu^T
+                p.A2 = dv; p.B2 = Wu; p.K2 = ff;
+                launch_gemm(p, EpiScatterBf16{dX, d, w.live_idx}, s);
+            }
+            continue;
+        }
         if (io.composed) {      // one panel: nothing to add to
             if (grads) {
                 // G = a^T dz [ff, V] over the kept rows, rounded to bf16 as the operand of the two products below
@@ -369,7 +457,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
                                    ST_GEMM_DWO, s);                                                               // dWo = Wd^T G
             }
             StageTimer t(ST_GEMM_DA, s);                                                                          // da = dz W_do^T
-            launch_gemm(problem(w.dz, V, w.Wdo, V, Mp, ff, V, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);
+            launch_gemm(problem(w.dz, V, w.Wdo, V, Mp, ff, V, kr, kRowsAreM), EpiSwigluBackward<false>{w.fu, w.fv, ff, nullptr, nullptr, nullptr}, s);
         } else {
             {
                 StageTimer t(ST_GEMM_DY, s);
@@ -382,7 +470,7 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
                                    s);                                                                            // dWd (+)= a^T dy
             }
             StageTimer t(ST_GEMM_DA, s);
-            launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward{w.fu, w.fv, ff}, s);   // fu <- du, fv <- dv
+            launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward<false>{w.fu, w.fv, ff, nullptr, nullptr, nullptr}, s);   // fu <- du, fv <- dv
         }
         if (grads) {
             launch_weight_grad(problem(w.X, d, w.fu, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, !first, ST_GEMM_DWG_DWU,

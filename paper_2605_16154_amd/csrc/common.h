@@ -60,6 +60,7 @@ enum Stage : int {
     ST_OPT_NORM,
     ST_OPT_ADAMW,
     ST_LABEL_PHASES,
+    ST_LIVE_ROWS,
     ST_COUNT
 };
 

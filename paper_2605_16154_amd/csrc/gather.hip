@@ -179,7 +179,161 @@ __global__ __launch_bounds__(256) void scale_rows(T* __restrict__ dz, const T* _
     }
 }
 
+// Whether panel row r (batch row r + row_offset) carries a gradient.
+struct RowGradient {
+    const uint8_t* clipped;
+    const float* adv;
+    const float* chunk_weight;   // by chunk of the batch, or null
+    int64_t row_offset;
+    int A;
+    __device__ bool operator()(int r) const {
+        if (clipped[r] != 0 || adv[r] == 0.f) return false;
+        return chunk_weight == nullptr || chunk_weight[(r + row_offset) / A] != 0.f;
+    }
+};
+
+// Rows whose gradient factor is zero (ratio cut by the clip, zero advantage, zero weight) have an all-zero row of
+// dz and add nothing to any gradient.  One workgroup lists the panel's rows with a non-zero factor, in order, and
+// decides whether the backward products run over that list or over all live rows.
+// Rows are swept 1024 at a time (thread t looks at row 1024 q + t, so reads are contiguous); a sweep of kListRounds
+// such rounds first counts the rows with a gradient per round and wavefront, turns the counts into positions with
+// one scan, then writes the row numbers.
+constexpr int kListRounds = 64;
+__global__ __launch_bounds__(1024) void live_row_list(RowGradient has_gradient, const int32_t* __restrict__ n_kept,
+                                                       int max_chunks, int A, int64_t row_offset, int rows_pad,
+                                                       LiveSources whole, LiveSources listed, int32_t* __restrict__ idx,
+                                                       LivePlan* __restrict__ plan) {
+    __shared__ int32_t count[kListRounds * 16];   // [round][wavefront], then the position of its first listed row
+    __shared__ int32_t wave_sum[16];
+    int64_t rows64 = live_rows(n_kept, max_chunks, A) - row_offset;
+    const int rows = (int)(rows64 < 0 ? 0 : (rows64 > rows_pad ? rows_pad : rows64));
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int total = 0;
+    for (int sweep0 = 0; sweep0 < rows; sweep0 += kListRounds * 1024) {
+        for (int q = 0; q < kListRounds; ++q) {
+            const int r = sweep0 + q * 1024 + t;
+            const uint64_t mask = __ballot(r < rows && has_gradient(r));
+            if (lane == 0) count[q * 16 + wave] = __popcll(mask);
+        }
+        __syncthreads();
+        const int mine = count[t];                       // entry t = (round t / 16, wavefront t % 16): row order
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        int before = 0, sweep_total = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int v = wave_sum[q];
+            before += q < wave ? v : 0;
+            sweep_total += v;
+        }
+        count[t] = total + before + incl - mine;
+        __syncthreads();
+        for (int q = 0; q < kListRounds; ++q) {
+            const int r = sweep0 + q * 1024 + t;
+            const bool live = r < rows && has_gradient(r);
+            const uint64_t mask = __ballot(live);
+            if (live) idx[count[q * 16 + wave] + __popcll(mask & ((1ull << lane) - 1ull))] = r;
+        }
+        total += sweep_total;
+        __syncthreads();
+    }
+    // the list pays once the rows it drops outweigh the copies it needs: at least one row in sixteen
+    const bool use_list = (int64_t)(rows - total) * 16 >= rows && rows > 0;
+    const int n = use_list ? total : rows;
+    if (!use_list)
+        for (int r = t; r < rows; r += 1024) idx[r] = r;
+    for (int m = n + t; m < (n + 255) / 256 * 256; m += 1024) idx[m] = -1;   // up to the end of the last row tile
+    if (t == 0) {
+        plan->n_rows = n;
+        plan->listed = use_list ? 1 : 0;
+        for (int q = 0; q < LiveSources::kCount; ++q) plan->src[q] = use_list ? listed.p[q] : whole.p[q];
+    }
+}
+
+// dst[m] = src[idx[m]] for the listed rows, zero rows from there to the end of the last row tile; nothing when
+// the backward products run over all live rows.  Rows are row_vecs 16-byte units long; a workgroup moves blocks of
+// kRowsPerBlock rows, striding over the blocks by the grid.
+__global__ __launch_bounds__(kThreads) void gather_listed_rows(const uint4* __restrict__ src, const int32_t* __restrict__ idx,
+                                                               const LivePlan* __restrict__ plan, int row_vecs,
+                                                               uint4* __restrict__ dst) {
+    __shared__ int32_t src_row[kRowsPerBlock];
+    if (!plan->listed) return;
+    const int limit = (plan->n_rows + 255) / 256 * 256;
+    const int tid = threadIdx.x;
+    const int total = kRowsPerBlock * row_vecs;
+    constexpr int kUnroll = 8;
+    for (int r0 = blockIdx.x * kRowsPerBlock; r0 < limit; r0 += gridDim.x * kRowsPerBlock) {
+        __syncthreads();
+        if (tid < kRowsPerBlock) src_row[tid] = idx[r0 + tid];
+        __syncthreads();
+        for (int base = tid; base < total; base += kThreads * kUnroll) {
+            uint4 v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int el = base + u * kThreads;
+                v[u] = make_uint4(0, 0, 0, 0);
+                if (el < total) {
+                    const int row = src_row[el / row_vecs];
+                    if (row >= 0) v[u] = src[(int64_t)row * row_vecs + el % row_vecs];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int el = base + u * kThreads;
+                if (el < total) dst[(int64_t)(r0 + el / row_vecs) * row_vecs + el % row_vecs] = v[u];
+            }
+        }
+    }
+}
+
+// Zero rows of dX for the panel rows the listed products do not write: rows without a gradient, and the rows
+// between the live rows and the end of their row tile (as far as dX has them).
+__global__ __launch_bounds__(kThreads) void zero_unlisted_rows(RowGradient has_gradient,
+                                                               const int32_t* __restrict__ n_kept, int max_chunks, int A,
+                                                               int64_t row_offset, int rows_pad, int rows_in_dX,
+                                                               int row_vecs, uint4* __restrict__ dX) {
+    int64_t rows64 = live_rows(n_kept, max_chunks, A) - row_offset;
+    const int rows = (int)(rows64 < 0 ? 0 : (rows64 > rows_pad ? rows_pad : rows64));
+    const int limit = min(rows_in_dX, (rows + 255) / 256 * 256);
+    for (int r = blockIdx.x; r < limit; r += gridDim.x) {
+        if (r < rows && has_gradient(r)) continue;
+        for (int c = threadIdx.x; c < row_vecs; c += kThreads) dX[(int64_t)r * row_vecs + c] = make_uint4(0, 0, 0, 0);
+    }
+}
+
 }  // namespace
+
+int launch_live_row_list(const ActorShape& sh, const ActorIO& io, const uint8_t* clipped, const float* adv,
+                         int64_t row_offset, int64_t rows_pad, const LiveSources& whole, const LiveSources& listed,
+                         int32_t* idx, LivePlan* plan, hipStream_t s) {
+    const RowGradient g{clipped, adv, io.opt.chunk_weight, row_offset, sh.A};
+    live_row_list<<<1, 1024, 0, s>>>(g, io.n_kept, sh.max_chunks, sh.A, row_offset, (int)rows_pad, whole, listed, idx, plan);
+    return launch_status();
+}
+
+int launch_gather_listed(const void* src, const int32_t* idx, const LivePlan* plan, int64_t rows_pad, int64_t row_bytes,
+                         void* dst, hipStream_t s) {
+    const int64_t blocks = ceil_div64(rows_pad, kRowsPerBlock);
+    gather_listed_rows<<<(unsigned)(blocks < 2048 ? blocks : 2048), kThreads, 0, s>>>(
+        static_cast<const uint4*>(src), idx, plan, (int)(row_bytes / 16), static_cast<uint4*>(dst));
+    return launch_status();
+}
+
+int launch_zero_unlisted(const ActorShape& sh, const ActorIO& io, const uint8_t* clipped, const float* adv,
+                         int64_t row_offset, int64_t rows_pad, int64_t rows_in_dX, int64_t row_bytes, void* dX,
+                         hipStream_t s) {
+    const RowGradient g{clipped, adv, io.opt.chunk_weight, row_offset, sh.A};
+    zero_unlisted_rows<<<(unsigned)(rows_pad < 2048 ? rows_pad : 2048), kThreads, 0, s>>>(
+        g, io.n_kept, sh.max_chunks, sh.A, row_offset, (int)rows_pad, (int)rows_in_dX, (int)(row_bytes / 16),
+        static_cast<uint4*>(dX));
+    return launch_status();
+}
 
 int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t row_offset, int64_t rows_pad,
                   RowMeta meta, hipStream_t s) {

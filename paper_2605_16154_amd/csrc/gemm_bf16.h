@@ -67,6 +67,10 @@ struct GemmProblem {
     const int32_t* kept;
     int kept_max, rows_per_kept, rows_role;
     int row_offset, skip_if_empty;
+    // Operands chosen on the device: when set, the first-segment operand is read from *A_sel (*B_sel) instead of A
+    // (B); an earlier kernel of the same stream decides which buffer that is.  Single reduction segment only.
+    const bf16* const* A_sel;
+    const bf16* const* B_sel;
 };
 enum RowsRole : int { kRowsUnused = 0, kRowsAreM = 1, kRowsAreK = 2 };
 
@@ -223,8 +227,9 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         const uint32_t ld = (uint32_t)(operand == 0 ? p.lda : p.ldb);
         const int row0 = operand == 0 ? m0 : n0;
         const int layout = operand == 0 ? kLayA : kLayB;
-        const bf16* s1 = operand == 0 ? p.A : p.B;
-        const bf16* s2 = operand == 0 ? p.A2 : p.B2;
+        const bf16* const* sel = operand == 0 ? p.A_sel : p.B_sel;
+        const bf16* s1 = sel != nullptr ? *sel : (operand == 0 ? p.A : p.B);
+        const bf16* s2 = sel != nullptr ? s1 : (operand == 0 ? p.A2 : p.B2);
         if (layout == kRowsByK) {
             const uint32_t row = (uint32_t)wave * 64u + (uint32_t)(lane >> 3);      // + 8 r for load r
 #pragma unroll
@@ -516,6 +521,15 @@ struct RowFetch {
 #pragma unroll
         for (int pass = 0; pass < kPasses; ++pass) r[pass] = *reinterpret_cast<const uint4*>(in + pass * kRowsPerPass * ld_bytes);
     }
+    // The same with the rows given by number: rows[pass] is the row of a matrix (whose row 0, at this wavefront's
+    // columns, is src_col0) that this lane fetches in that pass; a negative number stands for a row of zeros.
+    __device__ void fetch_rows_at(const char* src_col0, int64_t ld_bytes, const int (&rows)[kPasses], int lane) {
+        const char* in = src_col0 + (lane % kLanesPerRow) * 16;
+#pragma unroll
+        for (int pass = 0; pass < kPasses; ++pass)
+            r[pass] = rows[pass] >= 0 ? *reinterpret_cast<const uint4*>(in + (int64_t)rows[pass] * ld_bytes)
+                                      : make_uint4(0, 0, 0, 0);
+    }
     __device__ void stash_rows(char* st, int stride, int lane) const {
         char* dst = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
 #pragma unroll
@@ -525,6 +539,22 @@ struct RowFetch {
         }
     }
 };
+// copy_rows_out with the destination rows given by number (row i of the staging area goes to row rows[i] of the
+// matrix whose row 0, at this wavefront's columns, is dst_col0; negative: not written).
+template <int kRows, int kRowBytes>
+__device__ inline void copy_rows_out_at(const char* st, int stride, char* dst_col0, int64_t ld_bytes, const int32_t* rows,
+                                        int lane) {
+    constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
+    const char* src = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+    char* out = dst_col0 + (lane % kLanesPerRow) * 16;
+#pragma unroll 8
+    for (int pass = 0; pass < kRows / kRowsPerPass; ++pass) {
+        const int row = rows[lane / kLanesPerRow + pass * kRowsPerPass];
+        const uint2 lo = *reinterpret_cast<const uint2*>(src), hi = *reinterpret_cast<const uint2*>(src + 8);
+        if (row >= 0) *reinterpret_cast<uint4*>(out + (int64_t)row * ld_bytes) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        src += kRowsPerPass * stride;
+    }
+}
 
 // C (bf16, row-major) = acc; rows at and beyond row_limit are not written.
 struct EpiStoreBf16 {
@@ -542,6 +572,25 @@ struct EpiStoreBf16 {
         const int row_base = tc.m0 + tc.wm * 128, col_base = tc.n0 + tc.wn * 128;
         copy_rows_out<128, 256>(st, kStride, reinterpret_cast<char*>(C + (int64_t)row_base * ldc + col_base), ldc * 2,
                                 row_limit - row_base, tc.lane);
+    }
+};
+
+// Rows of acc written to the rows of C (bf16, row-major) that row_idx names: row m of the product goes to row
+// row_idx[m]; negative entries are not written.
+struct EpiScatterBf16 {
+    bf16* C;
+    int64_t ldc;
+    const int32_t* row_idx;
+    __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
+        constexpr int kStride = 264;
+        char* st = wave_stage(tc, lds);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            stage_tile_row(st, kStride, tc.lane, i * 32 + (tc.lane & 31), 0, 4,
+                           [&](int j, int e) { return acc[i][j][e]; });
+        __builtin_amdgcn_wave_barrier();
+        const int row_base = tc.m0 + tc.wm * 128, col_base = tc.n0 + tc.wn * 128;
+        copy_rows_out_at<128, 256>(st, kStride, reinterpret_cast<char*>(C + col_base), ldc * 2, row_idx + row_base, tc.lane);
     }
 };
 
@@ -685,31 +734,54 @@ struct EpiSwigluForward {
     }
 };
 
-// acc = da.  In place: fu <- du = da * fu, fv <- dv = da * fv  (bf16, [M, ff]; the factors are
-// those written by the forward epilogue).  Works through the wavefront's 128 x 128 block in four
-// passes of 32 rows; the rows of the next pass are fetched into registers while the current pass
-// is computed.
+// acc = da.  du = da * fu, dv = da * fv (bf16, [M, ff]; the factors are those written by the forward epilogue).
+// kIndexed = false: in place, fu <- du, fv <- dv.  kIndexed = true: the rows of the product are a selection of the
+// rows the forward pass ran over: product row m takes its factors from row row_idx[m] of fu, fv (negative: a row of
+// zeros) and writes row m of du, dv (other buffers).  Works through the wavefront's 128 x 128 block in four passes of
+// 32 rows; the rows of the next pass are fetched into registers while the current pass is computed.
+template <bool kIndexed>
 struct EpiSwigluBackward {
     bf16 *fu, *fv;
     int64_t ld;
+    const int32_t* row_idx;
+    bf16 *du, *dv;
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
         constexpr int kStride = 520;                       // [du 128 | dv 128] bf16 + 8 bytes
         char* st = wave_stage(tc, lds);
-        const int col_base = tc.n0 + tc.wn * 128;
+        const int row_base = tc.m0 + tc.wm * 128, col_base = tc.n0 + tc.wn * 128;
         const int64_t ld_bytes = ld * 2;
-        char* const u0 = reinterpret_cast<char*>(fu + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
-        char* const v0 = reinterpret_cast<char*>(fv + (int64_t)(tc.m0 + tc.wm * 128) * ld + col_base);
+        const int64_t at = (kIndexed ? 0 : (int64_t)row_base * ld) + col_base;
+        const char* const u0 = reinterpret_cast<const char*>(fu + at);
+        const char* const v0 = reinterpret_cast<const char*>(fv + at);
+        char* const du0 = reinterpret_cast<char*>((kIndexed ? du : fu) + (int64_t)row_base * ld + col_base);
+        char* const dv0 = reinterpret_cast<char*>((kIndexed ? dv : fv) + (int64_t)row_base * ld + col_base);
+        // the 128 row numbers of this wavefront's block, two per lane; a pass hands them to the lanes that fetch the rows
+        int idx_lo = 0, idx_hi = 0;
+        if (kIndexed) {
+            idx_lo = row_idx[row_base + tc.lane];
+            idx_hi = row_idx[row_base + 64 + tc.lane];
+        }
         RowFetch<32, 256> ru, rv;
-        ru.fetch_rows(u0, ld_bytes, tc.lane);
-        rv.fetch_rows(v0, ld_bytes, tc.lane);
+        auto fetch = [&](int pass) {
+            if (kIndexed) {
+                int rows[RowFetch<32, 256>::kPasses];
+#pragma unroll
+                for (int q = 0; q < RowFetch<32, 256>::kPasses; ++q)
+                    rows[q] = __shfl(pass < 2 ? idx_lo : idx_hi,
+                                     (pass & 1) * 32 + tc.lane / RowFetch<32, 256>::kLanesPerRow + q * RowFetch<32, 256>::kRowsPerPass, 64);
+                ru.fetch_rows_at(u0, ld_bytes, rows, tc.lane);
+                rv.fetch_rows_at(v0, ld_bytes, rows, tc.lane);
+            } else {
+                ru.fetch_rows(u0 + pass * 32 * ld_bytes, ld_bytes, tc.lane);
+                rv.fetch_rows(v0 + pass * 32 * ld_bytes, ld_bytes, tc.lane);
+            }
+        };
+        fetch(0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {                      // 32 rows per pass
             ru.stash_rows(st, kStride, tc.lane);
             rv.stash_rows(st + 256, kStride, tc.lane);
-            if (i < 3) {
-                ru.fetch_rows(u0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
-                rv.fetch_rows(v0 + (i + 1) * 32 * ld_bytes, ld_bytes, tc.lane);
-            }
+            if (i < 3) fetch(i + 1);
             __builtin_amdgcn_wave_barrier();
             const int lr = tc.lane & 31;
 #pragma unroll
@@ -721,19 +793,19 @@ struct EpiSwigluBackward {
                     char* pv = pu + 256;
                     const bf16x4 u4 = *reinterpret_cast<const bf16x4*>(pu);
                     const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(pv);
-                    float du[4], dv[4];
+                    float gu[4], gv[4];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const float g = acc[i][j][4 * q + t];
-                        du[t] = g * (float)u4[t];
-                        dv[t] = g * (float)v4[t];
+                        gu[t] = g * (float)u4[t];
+                        gv[t] = g * (float)v4[t];
                     }
-                    *reinterpret_cast<bf16x4*>(pu) = to_bf16x4(du[0], du[1], du[2], du[3]);
-                    *reinterpret_cast<bf16x4*>(pv) = to_bf16x4(dv[0], dv[1], dv[2], dv[3]);
+                    *reinterpret_cast<bf16x4*>(pu) = to_bf16x4(gu[0], gu[1], gu[2], gu[3]);
+                    *reinterpret_cast<bf16x4*>(pv) = to_bf16x4(gv[0], gv[1], gv[2], gv[3]);
                 }
             __builtin_amdgcn_wave_barrier();
-            copy_rows_out<32, 256>(st, kStride, u0 + i * 32 * ld_bytes, ld_bytes, 32, tc.lane);
-            copy_rows_out<32, 256>(st + 256, kStride, v0 + i * 32 * ld_bytes, ld_bytes, 32, tc.lane);
+            copy_rows_out<32, 256>(st, kStride, du0 + i * 32 * ld_bytes, ld_bytes, 32, tc.lane);
+            copy_rows_out<32, 256>(st + 256, kStride, dv0 + i * 32 * ld_bytes, ld_bytes, 32, tc.lane);
             __builtin_amdgcn_wave_barrier();
         }
     }

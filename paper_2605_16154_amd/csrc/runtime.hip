@@ -14,7 +14,7 @@ const char* const kStageNames[ST_COUNT] = {
     "gemm_logits_loss", "gemm_dWo",        "gemm_dy",        "gemm_dWd",    "gemm_da",
     "gemm_dWg_dWu",    "gemm_dX",          "reduce",         "f32_forward", "f32_loss",
     "f32_backward",    "opt_grad_norm",    "opt_adamw",
-    "label_phases"};
+    "label_phases",    "live_rows"};
 
 struct Pending {
     int stage;

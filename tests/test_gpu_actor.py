@@ -339,6 +339,41 @@ def test_bf16_row_panels_add_up_to_the_whole_batch(pcm, n_kept, variants):
         assert rel(got[k], whole[k]) <= 1e-5, k
 
 
+@pytest.mark.parametrize("n_kept,old_rel,variants,listed", [
+    (120, 0.5, {}, True),                        # many clipped rows, four panels (the last one ragged)
+    (101, 0.5, dict(chunk_ratio=True), True),    # one ratio per chunk: whole chunks drop out
+    (120, 0.01, {}, False),                      # fewer than one row in sixteen clipped: all rows stay
+])
+def test_bf16_backward_over_the_rows_with_a_gradient(pcm, n_kept, old_rel, variants, listed):
+    """Rows whose ratio the clip cuts have a zero row of dz: the backward products run over the other rows only
+    (when enough drop out).  Against the checker, and against the library's own backward pass over all rows
+    (dense_backward): per-row outputs bit for bit, weight gradients up to the order of the fp32 sums; also with
+    only dX or only the weight gradients asked for."""
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=8, N=16, K=4, B=8, d=512, ff=768, seed=37)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, cfg.seed, 0)
+    pr = make_problem(cfg, wstd=0.05, margin=0.08, kept=kept[:n_kept], old_rel=old_rel, eps=(0.2, 0.4))
+    if variants.get("chunk_ratio"):
+        from test_gpu_actor_variants import condition_chunks
+        pr = condition_chunks(pr, (0.2, 0.4), 0.02)
+    kw = dict(eps=(0.2, 0.4), torch_dtype=torch.bfloat16, max_kept=128, variants=variants, panel_rows=1792)
+    ref, got = run_both(pcm, pr, **kw)
+    assert (ref["stats"][0] >= 1 / 8) if listed else (ref["stats"][0] < 1 / 32), ref["stats"]
+    n = len(ref["rows"])
+    check(ref, got, BF16_TOL, n, stats_tol=5e-2)
+    _, dense = run_both(pcm, pr, dense_backward=True, **kw)
+    assert np.array_equal(got["loss"], dense["loss"]) and np.array_equal(got["logp"][:n], dense["logp"][:n])
+    assert np.array_equal(got["dX"][:n], dense["dX"][:n])
+    for k in GRADS:
+        assert rel(got[k], dense[k]) <= 1e-5, (k, rel(got[k], dense[k]))
+    _, only_dx = run_both(pcm, pr, want_grads=False, **kw)
+    assert np.array_equal(only_dx["dX"][:n], got["dX"][:n])
+    _, only_dw = run_both(pcm, pr, want_dX=False, **kw)
+    for k in GRADS:
+        assert np.array_equal(only_dw[k], got[k]), k
+
+
 @pytest.mark.timeout(1200)
 def test_bf16_full_size_head_whole_batch_against_checker(pcm, composed):
     """LIBERO-shaped head (d = 4096, ff = 11008) in the launch configuration the benchmark times: the whole
