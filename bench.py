@@ -45,13 +45,14 @@ def stored_traffic(name):
         return None
 
 
-def gemm_flops_per_launch(M, d, ff, V, M_bwd=None):
-    """Flops of one launch of each head GEMM: the forward products over M token rows, the backward products over
-    M_bwd rows (those the library ran them over; M if not given).  2 flops per multiply-add."""
+def gemm_flops_per_step(M, d, ff, V, M_bwd=None):
+    """Flops per step of each head GEMM stage (all its launches: one per row panel, two for dWg and dWu): the forward
+    products over M token rows, the backward products over M_bwd rows (those the library ran them over; M if not
+    given).  2 flops per multiply-add."""
     B = M if M_bwd is None else M_bwd
     return {"gemm_gate_up": 2.0 * M * d * 2 * ff, "gemm_down": 2.0 * M * ff * d, "gemm_logits_loss": 2.0 * M * d * V,
             "gemm_dWo": 2.0 * B * d * V, "gemm_dy": 2.0 * B * V * d, "gemm_dWd": 2.0 * B * ff * d,
-            "gemm_da": 2.0 * B * d * ff, "gemm_dWg_dWu": 2.0 * B * d * ff, "gemm_dX": 2.0 * B * 2 * ff * d}
+            "gemm_da": 2.0 * B * d * ff, "gemm_dWg_dWu": 2 * 2.0 * B * d * ff, "gemm_dX": 2.0 * B * 2 * ff * d}
 
 
 def backward_rows(rows, clip_fractions, dense):
@@ -373,10 +374,29 @@ def optimizer_step_timing(wl, iters=10):
     n_param = sum(w.numel() for w in master)
     ms_norm = st["opt_grad_norm"][0] / iters
     ms_upd = st["opt_adamw"][0] / iters
+    # the same with the sum of the squares of the gradients taken from the actor step (it gathers them where it
+    # writes the final gradient values): no norm pass; and what asking for that sum costs the actor step
+    k = 5
+    dt_plain, _, _ = timed_steps(wl, k, 1)
+    dt_sq, _, _ = timed_steps(wl, k, 1, grad_sumsq=True)
+    sumsq = wl.act_out["grad_sumsq"]
+    grads = [wl.act_out["d" + n].reshape(-1) for n in names]
+    pcm.pcm_profile_enable(True)
+    for t in range(3 + iters, 3 + 2 * iters):
+        norm_given = pcm.pcm_adamw_clip_step(grads, master, m, v, t, weights_bf16=lowp, grad_sumsq=sumsq)
+    torch.cuda.synchronize()
+    st2 = pcm.pcm_profile_collect()
+    pcm.pcm_profile_enable(False)
+    want = float(torch.sqrt(sum((g.double() ** 2).sum() for g in grads)).item())
     return {"parameters": n_param, "grad_norm": float(norm.item()), "ms_per_step": ms_norm + ms_upd,
             "grad_norm_pass": {"ms": ms_norm, "bytes": 4 * n_param, "GB_per_s": 4 * n_param / ms_norm / 1e6},
             "adamw_pass": {"ms": ms_upd, "bytes": 30 * n_param, "GB_per_s": 30 * n_param / ms_upd / 1e6,
-                           "frac_of_hbm_peak": 30 * n_param / ms_upd / 1e6 / HBM_PEAK_GBPS}}
+                           "frac_of_hbm_peak": 30 * n_param / ms_upd / 1e6 / HBM_PEAK_GBPS},
+            "with_sum_of_squares_from_actor_step": {
+                "ms_per_step": (st2["opt_grad_norm"][0] + st2["opt_adamw"][0]) / iters,
+                "norm_stage_ms": st2["opt_grad_norm"][0] / iters,
+                "grad_norm": float(norm_given.item()), "grad_norm_recomputed_fp64": want,
+                "actor_step_ms_with": dt_sq / k * 1e3, "actor_step_ms_without": dt_plain / k * 1e3}}
 
 
 def main():
@@ -461,25 +481,26 @@ def main():
     mfma_only = {"random_operands": {"tflops": tf_rand, "clock_ghz": clk_rand},
                  "zero_operands": {"tflops": tf_zero, "clock_ghz": clk_zero}}
     rows_bwd = backward_rows(rows, wl.clip_fractions, args.dense_backward or cfg.dtype != "bf16")
-    flops = gemm_flops_per_launch(rows, cfg.d, cfg.ff, cfg.V, rows_bwd)
+    flops = gemm_flops_per_step(rows, cfg.d, cfg.ff, cfg.V, rows_bwd)
     per_stage = {}
     for name, (ms, launches) in stages.items():
         if launches == 0:
             continue
         per_stage[name] = {"ms_per_launch": ms / launches, "launches_per_step": launches / stage_steps}
         if name in flops:
-            per_stage[name]["tflops"] = flops[name] / (ms / launches * 1e-3) / 1e12
+            per_stage[name]["tflops"] = flops[name] * stage_steps / (ms * 1e-3) / 1e12
     total_flops_step = 3.0 * (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * rows           # Eq. 11 over all kept rows
     executed_flops_step = (6.0 * cfg.d * cfg.ff + 2.0 * cfg.d * cfg.V) * (rows + 2.0 * rows_bwd)
     if cfg.dtype == "bf16":
         gemm_ms_step = sum(stages[s][0] for s in GEMM_STAGES) / stage_steps
         dominant = max(GEMM_STAGES, key=lambda s: stages[s][0])
         dom_ms = stages[dominant][0] / stages[dominant][1]
-        achieved = flops[dominant] / (dom_ms * 1e-3) / 1e12
+        launches_step = stages[dominant][1] / stage_steps                    # one per row panel
+        achieved = flops[dominant] / launches_step / (dom_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": f"gemm_bf16 ({dominant})", "achieved": achieved,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                     "traffic": stored_traffic("gemm_gate_up_cfg2_traffic.txt") if cfg.name == "cfg2" else None,
-                    "flops_per_launch": flops[dominant], "ms_per_launch": dom_ms,
+                    "flops_per_launch": flops[dominant] / launches_step, "ms_per_launch": dom_ms,
                     "mfma_only_sustained": mfma_only,
                     "frac_of_mfma_only_random": achieved / tf_rand,
                     # executed flops: forward over all kept rows, backward over the rows with a gradient

@@ -363,6 +363,12 @@ typedef struct {
                                    given (the backward pass reads them as they are). */
     int dense_backward;         /* dtype PCM_BF16: non-zero = backward products over all kept rows, also over rows
                                    without a gradient (see "Rows without a gradient" above); 0 = the default */
+    double* grad_sumsq_out;     /* device f64 [1], 8-byte aligned, or NULL: receives the sum of the squares of all
+                                   elements of dWg, dWu, dWd, dWo, gathered where their final values are written
+                                   (fp64 throughout, summed in a fixed order), so that
+                                   pcm_adamw_clip_step_ex needs no pass of its own over the gradients for the norm.
+                                   dtype PCM_BF16, PCM_HEAD_AS_WRITTEN and all four gradients asked for; otherwise
+                                   PCM_EUNSUPPORTED (PCM_EINVAL if misaligned). */
 } pcm_loss_options;
 
 /* ------------------------------------------------------------------------------------------
@@ -414,6 +420,10 @@ PCM_API int grpo_masked_actor_step_ex(const void* hidden, const uint8_t* tokens,
  *   grad_norm_out device f32 [1] or NULL: the norm before clipping
  * Errors: PCM_EINVAL for a null or misaligned pointer or a hyper-parameter out of range (step < 1,
  * beta outside [0, 1), eps <= 0, negative lr / weight decay, max_grad_norm <= 0).
+ *
+ * pcm_adamw_clip_step_ex: the same with the sum of the squares of all gradient elements given (grad_sumsq, device
+ * f64 [1], as grpo_masked_actor_step_ex leaves it in pcm_loss_options.grad_sumsq_out): the norm is its square root
+ * and the gradients are read once, by the update.  grad_sumsq == NULL makes it pcm_adamw_clip_step.
  * ------------------------------------------------------------------------------------------ */
 PCM_API size_t pcm_adamw_clip_step_workspace_bytes(int n_tensors, const int64_t* numel);
 PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float* const* grads,
@@ -422,6 +432,12 @@ PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float
                                 double beta2, double eps, double weight_decay, double max_grad_norm,
                                 float* grad_norm_out, void* workspace, size_t workspace_bytes,
                                 void* stream);
+PCM_API int pcm_adamw_clip_step_ex(int n_tensors, const int64_t* numel, const float* const* grads,
+                                   float* const* weights, float* const* m, float* const* v,
+                                   void* const* weights_bf16, int64_t step, double lr, double beta1,
+                                   double beta2, double eps, double weight_decay, double max_grad_norm,
+                                   const double* grad_sumsq, float* grad_norm_out, void* workspace,
+                                   size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -31,7 +31,7 @@ class LossOptions(C.Structure):
     _fields_ = [("eps_low", C.c_float), ("eps_high", C.c_float), ("loss_scale", C.c_float),
                 ("entropy_coef", C.c_float), ("normalisation", C.c_int), ("ratio_level", C.c_int),
                 ("chunk_weight", C.c_void_p), ("head_evaluation", C.c_int), ("panel_rows", C.c_int),
-                ("packed_weights", C.c_void_p), ("dense_backward", C.c_int)]
+                ("packed_weights", C.c_void_p), ("dense_backward", C.c_int), ("grad_sumsq_out", C.c_void_p)]
 
 
 def _sig(fn, res, args):
@@ -77,6 +77,9 @@ def lib() -> C.CDLL:
     _sig(L.pcm_adamw_clip_step, i32,
          [i32, C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i64,
           f64, f64, f64, f64, f64, f64, vp, vp, sz, vp])
+    _sig(L.pcm_adamw_clip_step_ex, i32,
+         [i32, C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), i64,
+          f64, f64, f64, f64, f64, f64, vp, vp, vp, sz, vp])
     _sig(L.pcm_profile_enable, i32, [i32])
     _sig(L.pcm_profile_stage_count, i32, [])
     _sig(L.pcm_profile_stage_name, C.c_char_p, [i32])
@@ -276,7 +279,7 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                            chunk_weight: Optional[torch.Tensor] = None,
                            composed_head: bool = False, panel_rows: int = 0,
                            packed_weights: Optional[torch.Tensor] = None,
-                           dense_backward: bool = False) -> Dict[str, torch.Tensor]:
+                           dense_backward: bool = False, grad_sumsq: bool = False) -> Dict[str, torch.Tensor]:
     """-> dict(loss f32[1], logp f32[max_kept*A], stats f32[5], and if requested dWg, dWu, dWd, dWo, dX).
 
     `out` may carry preallocated tensors under those names (they are reused, not reallocated).  With none of
@@ -284,7 +287,9 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
     (stats[4] stays 0); otherwise grpo_masked_actor_step_ex.  composed_head = PCM_HEAD_COMPOSED (down and logit
     projection applied as one matrix); panel_rows = target height of the row panels of the bf16 path (0: default);
     packed_weights = the operand layouts from pcm_pack_head_weights (the step then skips its own weight re-layout);
-    dense_backward = backward products over all kept rows, also those whose gradient is zero (bf16 path).
+    dense_backward = backward products over all kept rows, also those whose gradient is zero (bf16 path);
+    grad_sumsq = also return "grad_sumsq" (f64[1]): the sum of the squares of the four weight gradients, for
+    pcm_adamw_clip_step(grad_sumsq=...).
     """
     dev = hidden.device
     d, ff = Wg.shape
@@ -326,14 +331,16 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
                  buf("dWd", (ff, d), torch.float32), buf("dWo", (d, V), torch.float32)]
     dX = buf("dX", (rows, d), hidden.dtype) if want_dX else None
     extended = (token_mean or entropy_coef != 0.0 or chunk_ratio or chunk_weight is not None or composed_head
-                or panel_rows != 0 or packed_weights is not None or dense_backward)
+                or panel_rows != 0 or packed_weights is not None or dense_backward or grad_sumsq)
+    sumsq = buf("grad_sumsq", (1,), torch.float64) if grad_sumsq else None
     opt = None
     if extended:
         if chunk_weight is not None and chunk_weight.shape[0] < max_kept_chunks:
             raise PcmError("chunk_weight is shorter than max_kept_chunks")
         opt = LossOptions(eps_low, eps_high, loss_scale, entropy_coef, int(token_mean), int(chunk_ratio),
                           _ptr(chunk_weight, torch.float32, "chunk_weight"), int(composed_head), int(panel_rows),
-                          _ptr(packed_weights, torch.uint8, "packed_weights"), int(dense_backward))
+                          _ptr(packed_weights, torch.uint8, "packed_weights"), int(dense_backward),
+                          _ptr(sumsq, torch.float64, "grad_sumsq"))
         need = lib().grpo_masked_actor_step_ex_workspace_bytes(max_kept_chunks, A, d, ff, V, dtype,
                                                                int(want_grads or want_dX), C.byref(opt))
     else:
@@ -359,10 +366,13 @@ def grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept_idx, n_kept, T: i
 
 def pcm_adamw_clip_step(grads, weights, m, v, step: int, lr: float = 1e-5, beta1: float = 0.9, beta2: float = 0.999,
                         eps: float = 1e-8, weight_decay: float = 0.0, max_grad_norm: float = 2.0, weights_bf16=None,
-                        grad_norm_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                        grad_norm_out: Optional[torch.Tensor] = None,
+                        grad_sumsq: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Global-norm clipping + AdamW over lists of fp32 tensors (updated in place); -> grad norm f32[1].
 
     `weights_bf16`, if given, is a list (entries may be None) of bf16 tensors that receive the new weights.
+    `grad_sumsq` (f64[1], as the actor step returns it) is the sum of the squares of all gradient elements: the call
+    is then pcm_adamw_clip_step_ex, which reads the gradients once instead of twice.
     """
     n = len(grads)
     if not (len(weights) == len(m) == len(v) == n) or (weights_bf16 is not None and len(weights_bf16) != n):
@@ -385,10 +395,14 @@ def pcm_adamw_clip_step(grads, weights, m, v, step: int, lr: float = 1e-5, beta1
     if need == 0:
         raise PcmError("pcm_adamw_clip_step: bad tensor list")
     ws, ws_bytes = _workspace(need, dev)
-    rc = lib().pcm_adamw_clip_step(n, numel, arr(grads, torch.float32, "grads"), arr(weights, torch.float32, "weights"),
-                                   arr(m, torch.float32, "m"), arr(v, torch.float32, "v"), lowp, step, lr, beta1,
-                                   beta2, eps, weight_decay, max_grad_norm, _ptr(grad_norm_out, torch.float32, "norm"),
-                                   ws, ws_bytes, _stream())
+    head = (n, numel, arr(grads, torch.float32, "grads"), arr(weights, torch.float32, "weights"),
+            arr(m, torch.float32, "m"), arr(v, torch.float32, "v"), lowp, step, lr, beta1, beta2, eps, weight_decay,
+            max_grad_norm)
+    tail = (_ptr(grad_norm_out, torch.float32, "norm"), ws, ws_bytes, _stream())
+    if grad_sumsq is not None:
+        rc = lib().pcm_adamw_clip_step_ex(*head, _ptr(grad_sumsq, torch.float64, "grad_sumsq"), *tail)
+    else:
+        rc = lib().pcm_adamw_clip_step(*head, *tail)
     _check(rc, "pcm_adamw_clip_step")
     return grad_norm_out
 

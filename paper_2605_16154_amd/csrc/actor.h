@@ -29,6 +29,7 @@ struct LossOptions {
     int panel_rows;              // bf16 path: target height of the row panels (0 = the library's choice)
     const void* packed_weights;  // bf16 path: operand layouts written by pcm_pack_head_weights, or null
     int dense_backward;          // bf16 path: backward products over all kept rows, also those without a gradient
+    double* grad_sumsq_out;      // bf16 path: device [1] or null: sum of the squares of all four weight gradients
 };
 
 struct ActorIO {
@@ -76,8 +77,14 @@ struct RowOut {
 int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void* X, int64_t row_offset, int64_t rows_pad,
                   RowMeta meta, hipStream_t s);
 
-// Sums the per-row loss terms and statistics in a fixed order (one workgroup, fp64 accumulators).
-int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipStream_t s);
+// Partial sums of squares of the four weight gradients, left by the launches that wrote their final values.
+struct SumsqLists {
+    const double* parts[4];
+    int count[4];
+};
+// Sums the per-row loss terms and statistics in a fixed order (one workgroup, fp64 accumulators); with lists, also
+// the partial sums of squares into io.opt.grad_sumsq_out.
+int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, const SumsqLists& lists, hipStream_t s);
 
 // Per-chunk ratio: from the per-row dlogp, one ratio, one clipped term and one dz factor per kept chunk
 // (written to every row of the chunk; the term only to its first row).

@@ -23,12 +23,12 @@ size_t workspace_need(const ActorShape& sh, int dtype, bool bwd, const LossOptio
     return dtype == PCM_F32 ? actor_f32_workspace_bytes(sh, bwd) : actor_bf16_workspace_bytes(sh, bwd, opt, composed);
 }
 LossOptions plain_options(float eps_low, float eps_high, float loss_scale) {
-    return LossOptions{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0, nullptr, 0};
+    return LossOptions{eps_low, eps_high, loss_scale, 0.f, 0, 0, nullptr, 0, nullptr, 0, nullptr};
 }
 LossOptions from_boundary(const pcm_loss_options& o) {
     return LossOptions{o.eps_low, o.eps_high, o.loss_scale, o.entropy_coef, o.normalisation == PCM_NORM_TOKEN_MEAN,
                        o.ratio_level == PCM_RATIO_CHUNK, o.chunk_weight, o.panel_rows, o.packed_weights,
-                       o.dense_backward != 0};
+                       o.dense_backward != 0, o.grad_sumsq_out};
 }
 }  // namespace
 
@@ -70,6 +70,10 @@ int run_actor_step(const void* hidden, const uint8_t* tokens, const float* logp_
     if (opt.packed_weights != nullptr) {
         if (reinterpret_cast<uintptr_t>(opt.packed_weights) & 255u) return PCM_EINVAL;
         if (dtype != PCM_BF16 || composed) return PCM_EUNSUPPORTED;
+    }
+    if (opt.grad_sumsq_out != nullptr) {
+        if (reinterpret_cast<uintptr_t>(opt.grad_sumsq_out) & 7u) return PCM_EINVAL;
+        if (dtype != PCM_BF16 || composed || n_grad != 4) return PCM_EUNSUPPORTED;
     }
     // the split-precision forward pass of the per-chunk ratio exists for the evaluation as written only
     if (dtype == PCM_BF16 && opt.chunk_ratio && composed) return PCM_EUNSUPPORTED;

@@ -41,6 +41,7 @@ namespace {
 
 constexpr int kPackNone = 0, kPackGate = 1, kPackUp = 2;
 constexpr size_t kMaxSplitTiles = 256;   // tiles x parts of a split reduction: one workgroup per CU
+constexpr size_t kSumBlocksMax = 2048;   // workgroups of sum_parts_f32 at most
 
 __device__ inline int packed_row(int c, int mode) {
     if (mode == kPackNone) return c;
@@ -80,16 +81,41 @@ void transpose(hipStream_t s, const bf16* src, int R, int C, bf16* dst, int64_t 
                                         reinterpret_cast<uint16_t*>(dst), ld_dst, mode);
 }
 
-// out[i] = sum over the parts of a split reduction (n is a multiple of 4; parts are n floats apart).
-__global__ void sum_parts_f32(const float* parts, int n_parts, size_t n, float* out) {
+__global__ void fill_zero_f64(double* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0;
+}
+
+// Sum over a workgroup of 256 threads (every thread gets the result).
+__device__ inline double block_sum_256(double x) {
+    __shared__ double wave_part[4];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
+}
+
+// out[i] = sum over the parts of a split reduction (n is a multiple of 4; parts are n floats apart); kAdd: added
+// to what out holds.  With sumsq_parts, on the final panel, every workgroup also writes the sum of the squares of
+// the values it left in out to sumsq_parts[workgroup].
+template <bool kAdd>
+__global__ __launch_bounds__(256) void sum_parts_f32(const float* parts, int n_parts, size_t n, float* out, double* sumsq_parts,
+                                                     FinalPanel final_panel) {
     const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
+    double sq = 0.0;
     for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
-        float4 acc = *reinterpret_cast<const float4*>(parts + i);
-        for (int s = 1; s < n_parts; ++s) {
+        float4 acc = kAdd ? *reinterpret_cast<const float4*>(out + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s = 0; s < n_parts; ++s) {
             const float4 v = *reinterpret_cast<const float4*>(parts + (size_t)s * n + i);
             acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
         }
         *reinterpret_cast<float4*>(out + i) = acc;
+        sq += (double)acc.x * acc.x + (double)acc.y * acc.y + (double)acc.z * acc.z + (double)acc.w * acc.w;
+    }
+    if (sumsq_parts != nullptr && final_panel()) {
+        sq = block_sum_256(sq);
+        if (threadIdx.x == 0) sumsq_parts[blockIdx.x] = sq;
     }
 }
 
@@ -149,6 +175,8 @@ struct Bf16Workspace {
                            // later of X, the listed rows of dz; dv takes the place of a
     int32_t* live_idx;     // [Rp] the listed rows
     LivePlan* plan;        // null: backward over all rows
+    double* sumsq[4];      // sums of squares of the final dWg, dWu, dWd, dWo by workgroup (null: not asked for)
+    int sumsq_count[4];
     bf16 *Wdo, *G;  // composed evaluation: Wd Wo and a^T dz, both [ff, V]
     float* parts;   // partial products of split reductions
     RowMeta meta;   // whole batch
@@ -202,6 +230,14 @@ Bf16Workspace carve(void* ws, const ActorShape& sh, bool bwd, bool grads, const 
         w.live_idx = c.take<int32_t>(Rp);
         w.plan = c.take<LivePlan>(1);
     }
+    if (grads && opt.grad_sumsq_out != nullptr) {
+        const size_t tiles[4] = {d / kTileM * (ff / kTileN), d / kTileM * (ff / kTileN), ff / kTileM * (d / kTileN),
+                                 d / kTileM * (V / kTileN)};
+        for (int q = 0; q < 4; ++q) {
+            w.sumsq_count[q] = (int)(4 * tiles[q] > kSumBlocksMax ? 4 * tiles[q] : kSumBlocksMax);
+            w.sumsq[q] = c.take<double>((size_t)w.sumsq_count[q]);
+        }
+    }
     w.Wdo = c.take<bf16>(ff * V);
     if (grads) w.G = c.take<bf16>(ff * V);
     w.parts = c.take<float>(kMaxSplitTiles * (size_t)kTileM * kTileN);
@@ -229,18 +265,12 @@ struct KeptRows {
     int row_offset;
 };
 
-// sum_parts_f32 that adds to `out` instead of overwriting it.
-__global__ void add_parts_f32(const float* parts, int n_parts, size_t n, float* out) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x * 4;
-    for (size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; i < n; i += stride) {
-        float4 acc = *reinterpret_cast<const float4*>(out + i);
-        for (int s = 0; s < n_parts; ++s) {
-            const float4 v = *reinterpret_cast<const float4*>(parts + (size_t)s * n + i);
-            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-        }
-        *reinterpret_cast<float4*>(out + i) = acc;
-    }
-}
+// Where a weight-gradient launch leaves the sums of the squares of its final values: the unsplit GEMM four per
+// output tile, the kernel that sums a split reduction one per workgroup (parts == nullptr: nowhere).
+struct SumsqTarget {
+    double* parts;
+    FinalPanel final_panel;
+};
 
 // C[M, N] = product of p with a long reduction and possibly a small output: fp32 (C32) or rounded to bf16
 // (C16), exactly one of the two given.  A small output is computed as several partial products over slices of
@@ -248,25 +278,27 @@ __global__ void add_parts_f32(const float* parts, int n_parts, size_t n, float* 
 // kLayA = kLayB = kKByRows: A^T B over the kept rows with both operands stored [rows][features].
 // accumulate (fp32 output only): the product is added to C.
 template <int kLayA, int kLayB>
-void launch_reduction_gemm(GemmProblem p, float* C32, bf16* C16, float* parts, bool accumulate, int stage, hipStream_t s) {
+void launch_reduction_gemm(GemmProblem p, float* C32, bf16* C16, float* parts, bool accumulate, const SumsqTarget& sq, int stage,
+                           hipStream_t s) {
     p.splits = pick_splits((p.M / kTileM) * (p.N / kTileN), p.K1 / kTileK);
     StageTimer t(stage, s);
     if (p.splits == 1) {
         p.skip_if_empty = accumulate ? 1 : 0;
-        if (C32) launch_gemm<kLayA, kLayB>(p, EpiStoreF32{C32, p.N, 0, accumulate ? 1 : 0}, s);
+        if (C32) launch_gemm<kLayA, kLayB>(p, EpiStoreF32{C32, p.N, 0, accumulate ? 1 : 0, sq.parts, sq.final_panel}, s);
         else launch_gemm<kLayA, kLayB>(p, EpiStoreBf16{C16, p.N, p.M}, s);
         return;
     }
     const size_t n = (size_t)p.M * p.N;
-    launch_gemm<kLayA, kLayB>(p, EpiStoreF32{parts, p.N, (int64_t)n, 0}, s);
+    launch_gemm<kLayA, kLayB>(p, EpiStoreF32{parts, p.N, (int64_t)n, 0, nullptr, FinalPanel{}}, s);
     size_t blocks = (n / 4 + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    if (C32 && accumulate) add_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32);
-    else if (C32) sum_parts_f32<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32);
+    if (blocks > kSumBlocksMax) blocks = kSumBlocksMax;
+    if (C32 && accumulate) sum_parts_f32<true><<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32, sq.parts, sq.final_panel);
+    else if (C32) sum_parts_f32<false><<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C32, sq.parts, sq.final_panel);
     else sum_parts_bf16<<<(unsigned)blocks, 256, 0, s>>>(parts, p.splits, n, C16);
 }
-void launch_weight_grad(const GemmProblem& p, float* C, float* parts, bool accumulate, int stage, hipStream_t s) {
-    launch_reduction_gemm<kKByRows, kKByRows>(p, C, nullptr, parts, accumulate, stage, s);
+void launch_weight_grad(const GemmProblem& p, float* C, float* parts, bool accumulate, const SumsqTarget& sq, int stage,
+                        hipStream_t s) {
+    launch_reduction_gemm<kKByRows, kKByRows>(p, C, nullptr, parts, accumulate, sq, stage, s);
 }
 
 GemmProblem problem(const bf16* A, int64_t lda, const bf16* B, int64_t ldb, int M, int N, int K,
@@ -322,12 +354,16 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         if (io.composed) {
             // W_do = Wd Wo [ff, V], from the weights as given (Wd [rows][K], Wo [K][rows])
             launch_reduction_gemm<kRowsByK, kKByRows>(problem(Wd, d, Wo, V, ff, V, d, all_rows, kRowsUnused), nullptr, w.Wdo,
-                                                      w.parts, false, ST_WEIGHT_LAYOUT, s);
+                                                      w.parts, false, SumsqTarget{}, ST_WEIGHT_LAYOUT, s);
         } else {
             transpose(s, Wd, ff, d, w.WdT, ff, kPackNone, ST_WEIGHT_LAYOUT);   // [ff, d] -> [d, ff]
             transpose(s, Wo, d, V, w.WoT, d, kPackNone, ST_WEIGHT_LAYOUT);     // [d, V]  -> [V, d]
         }
     }
+
+    const bool want_sumsq = grads && io.opt.grad_sumsq_out != nullptr && ws != nullptr && w.sumsq[0] != nullptr;
+    if (want_sumsq)   // slots no launch of this call writes must read as zero (a fill kernel: safe under graph capture)
+        for (int q = 0; q < 4; ++q) fill_zero_f64<<<(w.sumsq_count[q] + 255) / 256, 256, 0, s>>>(w.sumsq[q], w.sumsq_count[q]);
 
     int rc = PCM_OK;
     for (int64_t row0 = 0; row0 < w.Mp; row0 += w.Rp) {
@@ -335,6 +371,11 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
         const int Mp = (int)(w.Mp - row0 < w.Rp ? w.Mp - row0 : w.Rp);
         const bool first = row0 == 0;
         const KeptRows kr{io.n_kept, sh.max_chunks, sh.A, (int)row0};
+        SumsqTarget sq[4] = {};    // dWg, dWu, dWd, dWo
+        if (want_sumsq) {
+            const FinalPanel fp{io.n_kept, sh.max_chunks, sh.A, row0, row0 + w.Rp >= w.Mp ? INT64_MAX : row0 + w.Rp};
+            for (int q = 0; q < 4; ++q) sq[q] = SumsqTarget{w.sumsq[q], fp};
+        }
         const RowMeta meta{w.meta.token + row0, w.meta.logp_old + row0, w.meta.adv + row0};
         const RowOut out{w.out.term + row0, w.out.ratio + row0, w.out.dlogp + row0, w.out.clipped + row0,
                          w.out.entropy + row0, w.out.coef + row0};
@@ -405,10 +446,10 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
                 GemmProblem p = problem(w.y, d, w.dz, V, d, V, Mp, lr, kRowsAreK);                               // dWo (+)= y^T dz
                 p.A_sel = src + LiveSources::kY;
                 p.B_sel = src + LiveSources::kDz;
-                launch_weight_grad(p, io.dWo, w.parts, !first, ST_GEMM_DWO, s);
+                launch_weight_grad(p, io.dWo, w.parts, !first, sq[3], ST_GEMM_DWO, s);
                 p = problem(w.a, ff, w.dy, d, ff, d, Mp, lr, kRowsAreK);                                         // dWd (+)= a^T dy
                 p.A_sel = src + LiveSources::kA;
-                launch_weight_grad(p, io.dWd, w.parts, !first, ST_GEMM_DWD, s);
+                launch_weight_grad(p, io.dWd, w.parts, !first, sq[2], ST_GEMM_DWD, s);
             }
             {
                 StageTimer t(ST_GEMM_DA, s);                                                                     // du, dv from da = dy Wd^T
@@ -422,10 +463,10 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
                 }
                 GemmProblem p = problem(w.X, d, w.du, ff, d, ff, Mp, lr, kRowsAreK);                             // dWg (+)= X^T du
                 p.A_sel = src + LiveSources::kX;
-                launch_weight_grad(p, io.dWg, w.parts, !first, ST_GEMM_DWG_DWU, s);
+                launch_weight_grad(p, io.dWg, w.parts, !first, sq[0], ST_GEMM_DWG_DWU, s);
                 p.B = dv;                                                                                        // dWu (+)= X^T dv
                 p.B2 = dv;
-                launch_weight_grad(p, io.dWu, w.parts, !first, ST_GEMM_DWG_DWU, s);
+                launch_weight_grad(p, io.dWu, w.parts, !first, sq[1], ST_GEMM_DWG_DWU, s);
             }
             if (io.dX) {
                 const int64_t rows_left = sh.rows_max() - row0;
@@ -447,14 +488,14 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
             if (grads) {
                 // G = a^T dz [ff, V] over the kept rows, rounded to bf16 as the operand of the two products below
                 launch_reduction_gemm<kKByRows, kKByRows>(problem(w.a, ff, w.dz, V, ff, V, Mp, kr, kRowsAreK), nullptr, w.G,
-                                                          w.parts, false, ST_GEMM_DWD, s);
+                                                          w.parts, false, SumsqTarget{}, ST_GEMM_DWD, s);
                 {
                     StageTimer t(ST_GEMM_DWD, s);                                                                 // dWd = G Wo^T
                     launch_gemm<kRowsByK, kRowsByK>(problem(w.G, V, Wo, V, ff, d, V, all_rows, kRowsUnused),
-                                                    EpiStoreF32{io.dWd, d, 0, 0}, s);
+                                                    EpiStoreF32{io.dWd, d, 0, 0, nullptr, FinalPanel{}}, s);
                 }
                 launch_weight_grad(problem(Wd, d, w.G, V, d, V, ff, all_rows, kRowsUnused), io.dWo, w.parts, false,
-                                   ST_GEMM_DWO, s);                                                               // dWo = Wd^T G
+                                   SumsqTarget{}, ST_GEMM_DWO, s);                                                               // dWo = Wd^T G
             }
             StageTimer t(ST_GEMM_DA, s);                                                                          // da = dz W_do^T
             launch_gemm(problem(w.dz, V, w.Wdo, V, Mp, ff, V, kr, kRowsAreM), EpiSwigluBackward<false>{w.fu, w.fv, ff, nullptr, nullptr, nullptr}, s);
@@ -464,19 +505,19 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
                 launch_gemm(problem(w.dz, V, Wo, V, Mp, d, V, kr, kRowsAreM), EpiStoreBf16{w.dy, d, Mp}, s);          // dy = dz Wo^T
             }
             if (grads) {
-                launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, !first, ST_GEMM_DWO,
-                                   s);                                                                            // dWo (+)= y^T dz
-                launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, !first, ST_GEMM_DWD,
-                                   s);                                                                            // dWd (+)= a^T dy
+                launch_weight_grad(problem(w.y, d, w.dz, V, d, V, Mp, kr, kRowsAreK), io.dWo, w.parts, !first, sq[3],
+                                   ST_GEMM_DWO, s);                                                                            // dWo (+)= y^T dz
+                launch_weight_grad(problem(w.a, ff, w.dy, d, ff, d, Mp, kr, kRowsAreK), io.dWd, w.parts, !first, sq[2],
+                                   ST_GEMM_DWD, s);                                                                            // dWd (+)= a^T dy
             }
             StageTimer t(ST_GEMM_DA, s);
             launch_gemm(problem(w.dy, d, Wd, d, Mp, ff, d, kr, kRowsAreM), EpiSwigluBackward<false>{w.fu, w.fv, ff, nullptr, nullptr, nullptr}, s);   // fu <- du, fv <- dv
         }
         if (grads) {
-            launch_weight_grad(problem(w.X, d, w.fu, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, !first, ST_GEMM_DWG_DWU,
-                               s);                                                                                // dWg (+)= X^T du
-            launch_weight_grad(problem(w.X, d, w.fv, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, !first, ST_GEMM_DWG_DWU,
-                               s);                                                                                // dWu (+)= X^T dv
+            launch_weight_grad(problem(w.X, d, w.fu, ff, d, ff, Mp, kr, kRowsAreK), io.dWg, w.parts, !first, sq[0],
+                               ST_GEMM_DWG_DWU, s);                                                                                // dWg (+)= X^T du
+            launch_weight_grad(problem(w.X, d, w.fv, ff, d, ff, Mp, kr, kRowsAreK), io.dWu, w.parts, !first, sq[1],
+                               ST_GEMM_DWG_DWU, s);                                                                                // dWu (+)= X^T dv
         }
         if (io.dX) {
             StageTimer t(ST_GEMM_DX, s);
@@ -486,7 +527,10 @@ int actor_bf16_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_
             launch_gemm(p, EpiStoreBf16{static_cast<bf16*>(io.dX) + row0 * d, d, (int)(rows_left < Mp ? rows_left : Mp)}, s);
         }
     }
-    rc = launch_loss_reduce(sh, io, w.out, s);
+    SumsqLists lists{};
+    if (want_sumsq)
+        for (int q = 0; q < 4; ++q) { lists.parts[q] = w.sumsq[q]; lists.count[q] = w.sumsq_count[q]; }
+    rc = launch_loss_reduce(sh, io, w.out, lists, s);
     if (rc != PCM_OK) return rc;
     return launch_status();
 }

@@ -316,7 +316,7 @@ int actor_f32_run(const ActorShape& sh, const ActorIO& io, void* ws, hipStream_t
             if (rc != PCM_OK) return rc;
         }
     }
-    rc = launch_loss_reduce(sh, io, w.out, s);
+    rc = launch_loss_reduce(sh, io, w.out, SumsqLists{}, s);
     if (rc != PCM_OK) return rc;
     if (!bwd) return launch_status();
     {

@@ -90,7 +90,8 @@ __global__ __launch_bounds__(1024) void loss_reduce(const float* __restrict__ te
                                                      const uint8_t* __restrict__ clipped,
                                                      const float* __restrict__ entropy,
                                                      const int32_t* __restrict__ n_kept, int max_chunks, int A,
-                                                     LossOptions opt, float* loss_out, float* stats_out, int n_stats) {
+                                                     LossOptions opt, float* loss_out, float* stats_out, int n_stats,
+                                                     SumsqLists lists) {
     __shared__ double red[5][1024];
     const int64_t rows = live_rows(n_kept, max_chunks, A);
     double acc[5] = {0, 0, 0, 0, 0};
@@ -107,6 +108,19 @@ __global__ __launch_bounds__(1024) void loss_reduce(const float* __restrict__ te
         if ((int)threadIdx.x < half)
             for (int q = 0; q < 5; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + half];
         __syncthreads();
+    }
+    if (opt.grad_sumsq_out != nullptr && lists.parts[0] != nullptr) {   // uniform over the workgroup
+        __shared__ double red_sq[1024];
+        double sq = 0.0;
+        for (int q = 0; q < 4; ++q)
+            for (int i = threadIdx.x; i < lists.count[q]; i += 1024) sq += lists.parts[q][i];
+        red_sq[threadIdx.x] = sq;
+        __syncthreads();
+        for (int half = 512; half > 0; half >>= 1) {
+            if ((int)threadIdx.x < half) red_sq[threadIdx.x] += red_sq[threadIdx.x + half];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) *opt.grad_sumsq_out = red_sq[0];
     }
     if (threadIdx.x == 0) {
         const double scale = (double)objective_scale(opt, rows);
@@ -355,10 +369,10 @@ int launch_gather(const ActorShape& sh, const ActorIO& io, int elem_bytes, void*
     return launch_status();
 }
 
-int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, hipStream_t s) {
+int launch_loss_reduce(const ActorShape& sh, const ActorIO& io, RowOut out, const SumsqLists& lists, hipStream_t s) {
     StageTimer t(ST_REDUCE, s);
     loss_reduce<<<1, 1024, 0, s>>>(out.term, out.ratio, out.dlogp, out.clipped, out.entropy, io.n_kept,
-                                   sh.max_chunks, sh.A, io.opt, io.loss_out, io.stats_out, io.n_stats);
+                                   sh.max_chunks, sh.A, io.opt, io.loss_out, io.stats_out, io.n_stats, lists);
     return launch_status();
 }
 

@@ -172,6 +172,13 @@ __device__ inline bf16x8 read_transposed_fragment(const char* lds_ptr) {
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// An epilogue may ask to run although the workgroup's reduction range is empty and skip_if_empty is set (it then
+// sees a zero accumulator): it says so through a member runs_when_empty().
+template <class E>
+__device__ inline auto runs_when_empty(const E& e, int) -> decltype(e.runs_when_empty()) { return e.runs_when_empty(); }
+template <class E>
+__device__ inline bool runs_when_empty(const E&, long) { return false; }
+
 template <class Epilogue, int kLayA, int kLayB>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epilogue epi) {
     constexpr int kTileElems = kTileM * kTileK;                  // one operand tile
@@ -431,7 +438,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16(GemmProblem p, Epil
         __syncthreads();
     }
 
-    if (p.skip_if_empty && step_begin >= step_end) return;    // nothing to add (uniform over the workgroup)
+    if (p.skip_if_empty && step_begin >= step_end && !runs_when_empty(epi, 0)) return;   // nothing to add (uniform over the workgroup)
     TileCoord tc{m0, n0, wm, wn, lane, split};
     epi(tc, acc, reinterpret_cast<char*>(smem));
 }
@@ -494,9 +501,9 @@ __device__ inline void copy_rows_out(const char* st, int stride, char* dst, int6
 }
 // The same for fp32 rows that are added to what global memory holds (16 bytes = 4 floats per lane).
 template <int kRows, int kRowBytes>
-__device__ inline void add_rows_out(const char* st, int stride, char* dst, int64_t ld_bytes, int lane) {
+__device__ inline void add_rows_out(char* st, int stride, char* dst, int64_t ld_bytes, int lane) {
     constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
-    const char* src = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+    char* src = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
     char* out = dst + (lane / kLanesPerRow) * ld_bytes + (lane % kLanesPerRow) * 16;
     const int64_t out_step = kRowsPerPass * ld_bytes;
 #pragma unroll 8
@@ -505,9 +512,25 @@ __device__ inline void add_rows_out(const char* st, int stride, char* dst, int64
         f32x4 cur = *reinterpret_cast<const f32x4*>(out);
         cur += add;
         *reinterpret_cast<f32x4*>(out) = cur;
+        *reinterpret_cast<f32x4*>(src) = cur;      // the staging area now holds what was written (see staged_sum_of_squares)
         src += kRowsPerPass * stride;
         out += out_step;
     }
+}
+// Sum of the squares of the kRows fp32 rows in the staging area, this lane's share (the 16 bytes per pass that
+// copy_rows_out / add_rows_out move), in fp64: squares of large fp32 values leave the fp32 range.
+template <int kRows, int kRowBytes>
+__device__ inline double staged_sum_of_squares(const char* st, int stride, int lane) {
+    constexpr int kLanesPerRow = kRowBytes / 16, kRowsPerPass = 64 / kLanesPerRow;
+    const char* src = st + (lane / kLanesPerRow) * stride + (lane % kLanesPerRow) * 16;
+    double sq = 0.0;
+#pragma unroll 1
+    for (int pass = 0; pass < kRows / kRowsPerPass; ++pass) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+        sq += (double)v[0] * (double)v[0] + (double)v[1] * (double)v[1] + (double)v[2] * (double)v[2] + (double)v[3] * (double)v[3];
+        src += kRowsPerPass * stride;
+    }
+    return sq;
 }
 // Global memory -> staging area, the mirror image of copy_rows_out (all kRows rows), in two halves so
 // that the loads can be in flight while other work runs: fetch_rows issues them into registers,
@@ -638,19 +661,39 @@ struct EpiStoreBf16Split {
     }
 };
 
+// Whether a row panel [row_begin, row_end) of a batch holds the batch's last live rows (panel 0 if there are none):
+// the weight gradients that panel leaves are the final ones.
+struct FinalPanel {
+    const int32_t* n_kept;
+    int max_chunks, A;
+    int64_t row_begin, row_end;
+    __device__ bool operator()() const {
+        const int64_t rows = live_rows(n_kept, max_chunks, A);
+        return rows <= row_end && (rows > row_begin || row_begin == 0);
+    }
+};
+
 // C (fp32, row-major) = acc.  With a split reduction, part s goes to C + s * split_stride (its own
 // M x N matrix; the caller sums the parts), so no atomics are needed and the sum is reproducible.
 // accumulate: C += acc instead (a batch processed in row panels adds every panel's weight gradient).
+// sumsq_parts (unsplit outputs with ldc = N only): on the final panel every wavefront also writes the sum of the
+// squares of the values it leaves in C to sumsq_parts[4 * tile + wavefront] (for the gradient norm of the optimizer
+// step, which then needs no pass of its own over the gradients).
 struct EpiStoreF32 {
     float* C;
     int64_t ldc;
     int64_t split_stride;
     int accumulate;
+    double* sumsq_parts;
+    FinalPanel final_panel;
+    __device__ bool runs_when_empty() const { return sumsq_parts != nullptr && final_panel(); }
     __device__ void operator()(const TileCoord& tc, f32x16 (&acc)[4][4], char* lds) const {
         float* const C = this->C + tc.split * split_stride;
         constexpr int kStride = 528;                       // 128 fp32 + 16 bytes: conflict-free 16-byte accesses
         char* st = wave_stage(tc, lds);
         const int col_base = tc.n0 + tc.wn * 128;
+        const bool want_sq = sumsq_parts != nullptr && final_panel();
+        double sq = 0.0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {                      // 32 rows per pass
 #pragma unroll
@@ -666,7 +709,14 @@ struct EpiStoreF32 {
             char* const dst = reinterpret_cast<char*>(C + (int64_t)row_base * ldc + col_base);
             if (accumulate) add_rows_out<32, 512>(st, kStride, dst, ldc * 4, tc.lane);
             else copy_rows_out<32, 512>(st, kStride, dst, ldc * 4, 32, tc.lane);
+            if (want_sq) sq += staged_sum_of_squares<32, 512>(st, kStride, tc.lane);
             __builtin_amdgcn_wave_barrier();
+        }
+        if (want_sq) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+            const int tile = (tc.m0 / kTileM) * (int)(ldc / kTileN) + tc.n0 / kTileN;
+            if (tc.lane == 0) sumsq_parts[tile * 4 + tc.wm * 2 + tc.wn] = sq;
         }
     }
 };

@@ -186,10 +186,12 @@ PCM_API size_t pcm_adamw_clip_step_workspace_bytes(int n_tensors, const int64_t*
     return carve(nullptr, count_chunks(n_tensors, numel)).bytes;
 }
 
-PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float* const* grads, float* const* weights,
-                                float* const* m, float* const* v, void* const* weights_bf16, int64_t step, double lr,
-                                double beta1, double beta2, double eps, double weight_decay, double max_grad_norm,
-                                float* grad_norm_out, void* workspace, size_t workspace_bytes, void* stream) {
+PCM_API int pcm_adamw_clip_step_ex(int n_tensors, const int64_t* numel, const float* const* grads, float* const* weights,
+                                   float* const* m, float* const* v, void* const* weights_bf16, int64_t step, double lr,
+                                   double beta1, double beta2, double eps, double weight_decay, double max_grad_norm,
+                                   const double* grad_sumsq, float* grad_norm_out, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    if (reinterpret_cast<uintptr_t>(grad_sumsq) & 7u) return PCM_EINVAL;
     if (n_tensors < 1 || n_tensors > kMaxTensors || !numel || !grads || !weights || !m || !v) return PCM_EINVAL;
     if (step < 1 || !(lr >= 0.0) || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || !(eps > 0.0) ||
         !(weight_decay >= 0.0) || !(max_grad_norm > 0.0))
@@ -224,14 +226,26 @@ PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float
     c.eps = (float)eps;
     {
         StageTimer t(ST_OPT_NORM, s);
-        sumsq_chunks<<<(unsigned)chunks, kThreads, 0, s>>>(tl, w.partial);
-        finish_norm<<<1, 1024, 0, s>>>(w.partial, chunks, max_grad_norm, 1e-6, w.result, grad_norm_out);
+        if (grad_sumsq != nullptr) {      // the sum of squares is given: one "partial"
+            finish_norm<<<1, 1024, 0, s>>>(grad_sumsq, 1, max_grad_norm, 1e-6, w.result, grad_norm_out);
+        } else {
+            sumsq_chunks<<<(unsigned)chunks, kThreads, 0, s>>>(tl, w.partial);
+            finish_norm<<<1, 1024, 0, s>>>(w.partial, chunks, max_grad_norm, 1e-6, w.result, grad_norm_out);
+        }
     }
     {
         StageTimer t(ST_OPT_ADAMW, s);
         adamw_chunks<<<(unsigned)chunks, kThreads, 0, s>>>(tl, w.result, c);
     }
     return launch_status();
+}
+
+PCM_API int pcm_adamw_clip_step(int n_tensors, const int64_t* numel, const float* const* grads, float* const* weights,
+                                float* const* m, float* const* v, void* const* weights_bf16, int64_t step, double lr,
+                                double beta1, double beta2, double eps, double weight_decay, double max_grad_norm,
+                                float* grad_norm_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return pcm_adamw_clip_step_ex(n_tensors, numel, grads, weights, m, v, weights_bf16, step, lr, beta1, beta2, eps,
+                                  weight_decay, max_grad_norm, nullptr, grad_norm_out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

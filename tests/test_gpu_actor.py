@@ -110,7 +110,7 @@ def run_both(pcm, pr, eps=(0.2, 0.2), scale=None, torch_dtype=torch.float32, max
         *(dev(W[k], torch_dtype) for k in ("Wg", "Wu", "Wd", "Wo")), eps[0], eps[1], scale,
         max_kept_chunks=max_kept, **kw)
     torch.cuda.synchronize()
-    return ref, {k: v.float().cpu().numpy() for k, v in out.items()}
+    return ref, {k: (v.double() if v.dtype == torch.float64 else v.float()).cpu().numpy() for k, v in out.items()}
 
 
 ROW_FACTOR = 2.5
@@ -367,6 +367,12 @@ def test_bf16_backward_over_the_rows_with_a_gradient(pcm, n_kept, old_rel, varia
     assert np.array_equal(got["dX"][:n], dense["dX"][:n])
     for k in GRADS:
         assert rel(got[k], dense[k]) <= 1e-5, (k, rel(got[k], dense[k]))
+    # the sum of the squares of the four weight gradients, gathered where their final values are written
+    _, with_sq = run_both(pcm, pr, grad_sumsq=True, **kw)
+    want = sum(float((with_sq[k].astype(np.float64) ** 2).sum()) for k in GRADS)
+    assert abs(float(with_sq["grad_sumsq"][0]) - want) <= 2e-5 * want, (with_sq["grad_sumsq"], want)
+    for k in GRADS:
+        assert np.array_equal(with_sq[k], got[k]), k
     _, only_dx = run_both(pcm, pr, want_grads=False, **kw)
     assert np.array_equal(only_dx["dX"][:n], got["dX"][:n])
     _, only_dw = run_both(pcm, pr, want_dX=False, **kw)
@@ -413,8 +419,11 @@ def test_bf16_full_size_head_whole_batch_against_checker(pcm, composed):
     logp_old[rows_t] = torch.from_numpy(lp_old).to(dv)
 
     full = pcm.grpo_masked_actor_step(hidden, tokens, logp_old, adv_t, kept_t, nk_t, *args, W["Wg"], W["Wu"], W["Wd"],
-                                      W["Wo"], 0.2, 0.2, scale, composed_head=composed)
+                                      W["Wo"], 0.2, 0.2, scale, composed_head=composed, grad_sumsq=not composed)
     torch.cuda.synchronize()
+    if not composed:     # sum of the squares of the weight gradients, written by the launches that finish them
+        want = sum(float((full[k].double() ** 2).sum().item()) for k in GRADS)
+        assert abs(float(full.pop("grad_sumsq").item()) - want) <= 2e-5 * want
     ref = O.actor_step(hid_rows, tok_rows, lp_old.astype(np.float64), adv_chunks, np.arange(len(kept)), 1, cfg.A,
                        Wn["Wg"], Wn["Wu"], Wn["Wd"], Wn["Wo"], 0.2, 0.2, scale)
     assert 0.02 < ref["stats"][0] < 0.98                          # clipped and unclipped rows both occur
@@ -499,8 +508,11 @@ def test_bf16_large_configs_chained_selection_and_sampled_rows(pcm, name):
 
     scale = 1.0 / cfg.T
     out = pcm.grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept, nk, *args, W["Wg"], W["Wu"], W["Wd"], W["Wo"],
-                                     0.2, 0.2, scale)
+                                     0.2, 0.2, scale, grad_sumsq=True)
     torch.cuda.synchronize()
+    # the final panel (wherever the kept rows end) leaves the sum of the squares of the accumulated gradients
+    want = sum(float((out[k].double() ** 2).sum().item()) for k in GRADS)
+    assert abs(float(out["grad_sumsq"].item()) - want) <= 2e-5 * want, (out["grad_sumsq"], want)
     ref = O.actor_step(sub_hidden, sub_tokens, lp_old, sub_adv, np.arange(len(pick)), 1, cfg.A, Wn["Wg"], Wn["Wu"],
                        Wn["Wd"], Wn["Wo"], 0.2, 0.2, scale)
     sel = np.concatenate([np.arange(q * cfg.A, (q + 1) * cfg.A) for q in pick_pos])

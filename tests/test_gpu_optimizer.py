@@ -123,6 +123,25 @@ def test_several_steps_track_the_checker():
         assert np.all(err <= 1e-4 * moved + 8 * np.spacing(np.abs(w0).astype(np.float32))), float(err.max())
 
 
+def test_given_sum_of_squares_replaces_the_norm_pass():
+    """pcm_adamw_clip_step_ex with the sum of the squares of the gradients handed in (as the actor step leaves it):
+    the same norm and the same update as the call that sums them itself."""
+    import paper_2605_16154_amd as pcm
+    dev = torch.device("cuda:0")
+    shapes = ((256, 1024), (256, 1024), (1024, 256), (256, 256))
+    for seed, gscale, step in ((11, 1e-3, 1), (12, 0.5, 4)):
+        w, g, m, v = _case(seed, shapes, gscale)
+        ref_w, ref_m, ref_v, ref_norm, _, _, _ = _run(w, g, m, v, step)
+        t = lambda xs: [torch.from_numpy(x.copy()).to(dev).reshape(-1) for x in xs]
+        dw, dg, dm, dv = t(w), t(g), t(m), t(v)
+        sumsq = torch.tensor([sum(float((x.astype(np.float64) ** 2).sum()) for x in g)], dtype=torch.float64, device=dev)
+        norm = pcm.pcm_adamw_clip_step(dg, dw, dm, dv, step, grad_sumsq=sumsq)
+        torch.cuda.synchronize()
+        assert abs(float(norm.item()) - ref_norm) <= 1e-6 * ref_norm
+        for got, ref in zip(dw + dm + dv, ref_w + ref_m + ref_v):
+            np.testing.assert_allclose(got.cpu().numpy().reshape(ref.shape), ref, rtol=2e-6, atol=1e-30)
+
+
 def test_bad_arguments_are_rejected():
     import paper_2605_16154_amd as pcm
     dev = torch.device("cuda:0")
