@@ -387,7 +387,7 @@ def optimizer_step_timing(wl, iters=10):
     torch.cuda.synchronize()
     st2 = pcm.pcm_profile_collect()
     pcm.pcm_profile_enable(False)
-    want = float(torch.sqrt(sum((g.double() ** 2).sum() for g in grads)).item())
+    want = float(torch.stack([(g.double() ** 2).sum() for g in grads]).sum().sqrt().item())
     return {"parameters": n_param, "grad_norm": float(norm.item()), "ms_per_step": ms_norm + ms_upd,
             "grad_norm_pass": {"ms": ms_norm, "bytes": 4 * n_param, "GB_per_s": 4 * n_param / ms_norm / 1e6},
             "adamw_pass": {"ms": ms_upd, "bytes": 30 * n_param, "GB_per_s": 30 * n_param / ms_upd / 1e6,

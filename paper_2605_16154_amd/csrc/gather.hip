@@ -200,9 +200,11 @@ struct RowGradient {
     const float* chunk_weight;   // by chunk of the batch, or null
     int64_t row_offset;
     int A;
-    __device__ bool operator()(int r) const {
-        if (clipped[r] != 0 || adv[r] == 0.f) return false;
-        return chunk_weight == nullptr || chunk_weight[(r + row_offset) / A] != 0.f;
+    __device__ bool operator()(int r) const {      // all loads unconditional, so that a loop of calls can overlap them
+        const uint8_t cut = clipped[r];
+        const float a = adv[r];
+        const float w = chunk_weight != nullptr ? chunk_weight[(r + row_offset) / A] : 1.f;
+        return cut == 0 && a != 0.f && w != 0.f;
     }
 };
 
@@ -212,7 +214,7 @@ struct RowGradient {
 // Rows are swept 1024 at a time (thread t looks at row 1024 q + t, so reads are contiguous); a sweep of kListRounds
 // such rounds first counts the rows with a gradient per round and wavefront, turns the counts into positions with
 // one scan, then writes the row numbers.
-constexpr int kListRounds = 64;
+constexpr int kListRounds = 64;   // one bit each in a 64-bit word per thread
 __global__ __launch_bounds__(1024) void live_row_list(RowGradient has_gradient, const int32_t* __restrict__ n_kept,
                                                        int max_chunks, int A, int64_t row_offset, int rows_pad,
                                                        LiveSources whole, LiveSources listed, int32_t* __restrict__ idx,
@@ -224,9 +226,17 @@ __global__ __launch_bounds__(1024) void live_row_list(RowGradient has_gradient, 
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     int total = 0;
     for (int sweep0 = 0; sweep0 < rows; sweep0 += kListRounds * 1024) {
+        // this thread's rows of the sweep, one bit per round; read first (independent loads, many in flight), the
+        // wavefront votes afterwards
+        uint64_t mine_bits = 0;
+#pragma unroll 8
         for (int q = 0; q < kListRounds; ++q) {
             const int r = sweep0 + q * 1024 + t;
-            const uint64_t mask = __ballot(r < rows && has_gradient(r));
+            const bool g = has_gradient(r < rows ? r : rows - 1);
+            if (r < rows && g) mine_bits |= 1ull << q;
+        }
+        for (int q = 0; q < kListRounds; ++q) {
+            const uint64_t mask = __ballot((mine_bits >> q) & 1ull);
             if (lane == 0) count[q * 16 + wave] = __popcll(mask);
         }
         __syncthreads();
@@ -249,10 +259,9 @@ __global__ __launch_bounds__(1024) void live_row_list(RowGradient has_gradient, 
         count[t] = total + before + incl - mine;
         __syncthreads();
         for (int q = 0; q < kListRounds; ++q) {
-            const int r = sweep0 + q * 1024 + t;
-            const bool live = r < rows && has_gradient(r);
+            const bool live = (mine_bits >> q) & 1ull;
             const uint64_t mask = __ballot(live);
-            if (live) idx[count[q * 16 + wave] + __popcll(mask & ((1ull << lane) - 1ull))] = r;
+            if (live) idx[count[q * 16 + wave] + __popcll(mask & ((1ull << lane) - 1ull))] = sweep0 + q * 1024 + t;
         }
         total += sweep_total;
         __syncthreads();

@@ -87,20 +87,25 @@ def kernel_source_hash() -> str:
     return h.hexdigest()[:16]
 
 
-def _mean_counter(path: str, counter_name: str, kernel_substr: str):
+def _mean_counter(path: str, counter_name: str, kernel_substr: str, large_only: bool = False):
+    """Mean of a counter over the launches of the kernels whose name contains kernel_substr.  large_only keeps the
+    launches within a factor two of the largest: the calibration kernel is a library elementwise kernel that the
+    program may also launch on a handful of elements."""
     vals = []
     for f in glob.glob(os.path.join(path, "**", "*counter_collection.csv"), recursive=True):
         for row in csv.DictReader(open(f)):
             if row["Counter_Name"] == counter_name and kernel_substr in row["Kernel_Name"]:
                 vals.append(float(row["Counter_Value"]))
+    if large_only and vals:
+        vals = [v for v in vals if 2 * v >= max(vals)]
     return (sum(vals) / len(vals), len(vals)) if vals else (float("nan"), 0)
 
 
 def traffic(fetch_dir: str, write_dir: str, kernel_substr: str) -> str:
     fetch, nf = _mean_counter(fetch_dir, "FETCH_SIZE", kernel_substr)
     write, nw = _mean_counter(write_dir, "WRITE_SIZE", kernel_substr)
-    cal_f, _ = _mean_counter(fetch_dir, "FETCH_SIZE", "CUDAFunctorOnSelf_add<double>")
-    cal_w, _ = _mean_counter(write_dir, "WRITE_SIZE", "CUDAFunctorOnSelf_add<double>")
+    cal_f, _ = _mean_counter(fetch_dir, "FETCH_SIZE", "CUDAFunctorOnSelf_add<double>", large_only=True)
+    cal_w, _ = _mean_counter(write_dir, "WRITE_SIZE", "CUDAFunctorOnSelf_add<double>", large_only=True)
     gib = float(1 << 20)   # KiB in 1 GiB
     return (f"kernel={kernel_substr}\nlaunches_fetch={nf}\nlaunches_write={nw}\n"
             f"fetch_kib_per_launch={fetch:.1f}\nwrite_kib_per_launch={write:.1f}\n"
@@ -112,8 +117,8 @@ def traffic(fetch_dir: str, write_dir: str, kernel_substr: str) -> str:
 def table(fetch_dir: str, write_dir: str, kernels) -> str:
     """One row per kernel: launches, FETCH_SIZE and WRITE_SIZE per launch scaled to bytes with the factors that the
     1 GiB elementwise calibration kernel of the same runs gives."""
-    cal_f, _ = _mean_counter(fetch_dir, "FETCH_SIZE", "CUDAFunctorOnSelf_add<double>")
-    cal_w, _ = _mean_counter(write_dir, "WRITE_SIZE", "CUDAFunctorOnSelf_add<double>")
+    cal_f, _ = _mean_counter(fetch_dir, "FETCH_SIZE", "CUDAFunctorOnSelf_add<double>", large_only=True)
+    cal_w, _ = _mean_counter(write_dir, "WRITE_SIZE", "CUDAFunctorOnSelf_add<double>", large_only=True)
     gib = float(1 << 20)
     sf, sw = gib / cal_f, gib / cal_w
     out = [f"# scale_fetch={sf:.4f} scale_write={sw:.4f} (FETCH_SIZE / WRITE_SIZE of a kernel that reads and writes exactly 1 GiB)",
