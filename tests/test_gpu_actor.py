@@ -343,6 +343,7 @@ def test_bf16_row_panels_add_up_to_the_whole_batch(pcm, n_kept, variants):
     (120, 0.5, {}, True),                        # many clipped rows, four panels (the last one ragged)
     (101, 0.5, dict(chunk_ratio=True), True),    # one ratio per chunk: whole chunks drop out
     (120, 0.01, {}, False),                      # fewer than one row in sixteen clipped: all rows stay
+    (120, 0.01, dict(chunk_weight="some_zero"), True),   # rows drop out through a zero chunk weight
 ])
 def test_bf16_backward_over_the_rows_with_a_gradient(pcm, n_kept, old_rel, variants, listed):
     """Rows whose ratio the clip cuts have a zero row of dz: the backward products run over the other rows only
@@ -357,9 +358,13 @@ def test_bf16_backward_over_the_rows_with_a_gradient(pcm, n_kept, old_rel, varia
     if variants.get("chunk_ratio"):
         from test_gpu_actor_variants import condition_chunks
         pr = condition_chunks(pr, (0.2, 0.4), 0.02)
+    if variants.get("chunk_weight") is not None:
+        rng = np.random.default_rng(5)
+        variants = dict(chunk_weight=np.where(rng.random(n_kept) < 0.3, 0.0, rng.uniform(0.5, 4.0, n_kept)))
     kw = dict(eps=(0.2, 0.4), torch_dtype=torch.bfloat16, max_kept=128, variants=variants, panel_rows=1792)
     ref, got = run_both(pcm, pr, **kw)
-    assert (ref["stats"][0] >= 1 / 8) if listed else (ref["stats"][0] < 1 / 32), ref["stats"]
+    if "chunk_weight" not in variants:
+        assert (ref["stats"][0] >= 1 / 8) if listed else (ref["stats"][0] < 1 / 32), ref["stats"]
     n = len(ref["rows"])
     check(ref, got, BF16_TOL, n, stats_tol=5e-2)
     _, dense = run_both(pcm, pr, dense_backward=True, **kw)
@@ -378,6 +383,26 @@ def test_bf16_backward_over_the_rows_with_a_gradient(pcm, n_kept, old_rel, varia
     _, only_dw = run_both(pcm, pr, want_dX=False, **kw)
     for k in GRADS:
         assert np.array_equal(only_dw[k], got[k]), k
+
+
+def test_bf16_every_row_clipped(pcm):
+    """No row carries a gradient (every ratio far beyond its threshold on the clipped side): the backward products
+    run over nothing, on every panel; gradients, dX and the sum of squared gradients are exactly zero, the loss is
+    the sum of the clipped terms."""
+    cfg = CONFIGS["cfg2"].with_(n_groups=2, G=8, N=16, K=4, B=8, d=512, ff=768, seed=41)
+    ro = make_rollouts(cfg, 0)
+    _, active = O.advantages(ro["reward"], cfg.G)
+    kept, _, _ = O.sample_chunks(np.array([1.0, 0.3, 0.1, 0.6]), ro["phase"], None, active, cfg.B, cfg.seed, 0)
+    pr = make_problem(cfg, wstd=0.05, kept=kept[:100], old_rel=0.1, eps=(0.2, 0.4))
+    adv_rows = np.repeat(pr["adv"], cfg.N * cfg.A)
+    pr["logp_old"] = np.where(adv_rows > 0, -40.0, 30.0).astype(np.float32)
+    ref, got = run_both(pcm, pr, eps=(0.2, 0.4), torch_dtype=torch.bfloat16, max_kept=128, panel_rows=1792, grad_sumsq=True)
+    assert ref["stats"][0] == 1.0 and got["stats"][0] == 1.0
+    assert abs(got["loss"][0] - ref["loss"]) <= BF16_TOL * abs(ref["loss"])
+    for k in GRADS:
+        assert not got[k].any(), k
+    assert not got["dX"][:len(ref["rows"])].any()
+    assert got["grad_sumsq"][0] == 0.0
 
 
 @pytest.mark.timeout(1200)
