@@ -550,6 +550,14 @@ def main():
                                     "tokens_per_s": n_n * cfg.A * k_n / dt_n, "clip_fraction": st_n[0],
                                     "mean_ratio": st_n[1]}
         wl.set_old_policy(args.policy_drift)
+        if not args.dense_backward:
+            # and in the default regime with every backward product over all kept rows (rows whose gradient the
+            # clip removes multiplied through as zeros): what the step costs without that saving
+            wl.dense_backward = True
+            wl.state = pcm.pcm_state_init(cfg.K, dev)
+            dt_d, n_d, _ = timed_steps(wl, k_n, 1)
+            wl.dense_backward = False
+            result["dense_backward"] = {"ms_per_step": dt_d / k_n * 1e3, "tokens_per_s": n_d * cfg.A * k_n / dt_d}
     if cfg.dtype == "bf16" and args.extras:
         # the same step with the loss of App. D (entropy bonus 1e-3, token-mean normalisation) and with one
         # ratio per chunk: extended entry point, same kernels plus two small ones in the per-chunk case
