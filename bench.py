@@ -538,6 +538,20 @@ def main():
         result["unmasked"] = {"ms_per_step": ms_un, "kept_rows": n_un * cfg.A, "tokens_per_s": n_un * cfg.A * k_un / dt_un,
                               "speedup_masked_vs_unmasked": ms_un / ms_step, "ideal": cfg.N / cfg.B,
                               "paper": "4.8x cumulative actor-update time, 2x H100 (Sec. 5.2, Fig. 4c)"}
+        # memory of the step beyond its inputs and outputs (the library's workspace: activations of one row panel,
+        # operand layouts, row lists), masked against unmasked; the paper's analogue is activation memory (Sec. 5.2)
+        code = pcm.PCM_BF16 if cfg.dtype == "bf16" else pcm.PCM_F32
+        ws = [pcm.grpo_masked_actor_step_workspace_bytes(cfg.T * b_, cfg.A, cfg.d, cfg.ff, cfg.V, code, True)
+              for b_ in (min(cfg.B, cfg.N), cfg.N)]
+        result["workspace_bytes"] = {"masked": ws[0], "unmasked": ws[1]}
+    if cfg.dtype == "bf16" and args.extras and cfg.B < cfg.N:
+        # budget sweep (Sec. 5.3 sweeps B in {8, 12, 16}): step time against kept chunks
+        sweep = {}
+        for b_ in sorted({max(1, cfg.B * 2 // 3), cfg.B, min(cfg.N, cfg.B * 4 // 3)}):
+            wl.state = pcm.pcm_state_init(cfg.K, dev)
+            dt_b, n_b, _ = timed_steps(wl, 5, 1, B=b_)
+            sweep[str(b_)] = {"ms_per_step": dt_b / 5 * 1e3, "kept_rows": n_b * cfg.A}
+        result["budget_sweep"] = sweep
     if cfg.dtype == "bf16" and not args.no_extras:
         # the same step nearer to on-policy: the old policy 20 times closer, so that few ratios leave the clip range
         # and almost no row of the backward products is zero (zero rows cost the matrix cores less power)
