@@ -59,5 +59,21 @@ def build_library(jobs: int = 8) -> str:
     return LIB
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "c", "gpu_client.cpp")
+C_CLIENT = os.path.join(ROOT, "tests", "c", "gpu_client")
+
+
+def build_c_client() -> str:
+    """The torch-free client of the C boundary that tests/test_gpu_c_client.py runs (host code only; it finds
+    libpcm.so relative to its own location)."""
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"), C_CLIENT_SRC,
+           "-o", C_CLIENT, "-L", PKG, "-l:libpcm.so", "-Wl,-rpath,$ORIGIN/../../paper_2605_16154_amd"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the C client failed:\n" + r.stderr)
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build_library())
+    print(build_c_client())
