@@ -17,7 +17,9 @@ def pcm():
     return m
 
 
-def test_captured_step_replays_bit_for_bit(pcm):
+@pytest.mark.parametrize("options", [dict(entropy_coef=1e-3, token_mean=True), dict(grad_sumsq=True)],
+                         ids=["entropy_bonus_dense_backward", "backward_over_listed_rows_with_gradient_norm"])
+def test_captured_step_replays_bit_for_bit(pcm, options):
     cfg = CONFIGS["cfg2"].with_(n_groups=2, G=4, N=16, K=4, B=5, d=256, ff=512, seed=31)
     dev = torch.device("cuda:0")
     ro = make_rollouts(cfg, 0)
@@ -39,7 +41,7 @@ def test_captured_step_replays_bit_for_bit(pcm):
         kept, off, nk = bufs["samp"]
         bufs["act"] = pcm.grpo_masked_actor_step(hidden, tokens, logp_old, adv, kept, nk, cfg.T, cfg.N, cfg.A, W["Wg"],
                                                  W["Wu"], W["Wd"], W["Wo"], 0.2, 0.4, 1.0 / cfg.T, out=bufs["act"],
-                                                 entropy_coef=1e-3, token_mean=True)
+                                                 **options)
 
     def snapshot():
         torch.cuda.synchronize()
@@ -56,6 +58,8 @@ def test_captured_step_replays_bit_for_bit(pcm):
     step(3)
     ref = snapshot()
     assert int(ref["n_kept"].item()) > 0 and ref["dWg"].abs().max().item() > 0
+    if "grad_sumsq" in options:      # enough clipped rows for the backward products to run over the listed rows
+        assert 1 / 8 < ref["stats"][0].item() < 7 / 8
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
